@@ -1,0 +1,175 @@
+/*
+ * hadfl.h -- C-ABI of libhadfl.so: one HADFL aggregation cycle over N model
+ * replicas held in one GPU's memory (Cao et al., "HADFL: Heterogeneity-aware
+ * Decentralized Federated Learning Framework", arXiv 2111.08274).
+ *
+ * A cycle is   hadfl_local_steps -> hadfl_select -> hadfl_aggregate
+ * after one    hadfl_init_replicas.
+ *
+ * Conventions
+ *   - Every call returns a hadfl_status; nothing throws or aborts.  Output
+ *     arguments are written only on HADFL_OK.  hadfl_last_error() gives text.
+ *   - "dev" pointers are device memory owned by the CALLER (allocate them
+ *     with any allocator, e.g. PyTorch tensors) and must outlive the context.
+ *     "host" pointers are ordinary host memory, read or written during the
+ *     call only.  The library owns the host-side context and a few small
+ *     pinned staging buffers, nothing else.
+ *   - All device work is enqueued on the hipStream_t given at init, in call
+ *     order, asynchronously.  Only the hadfl_get_* calls synchronise.
+ *   - No global state; several contexts may coexist.  Calls on one context
+ *     must not overlap in time.
+ *
+ * Data layout
+ *   - Activations are channels-last: a batch is [B][H][W][C].
+ *   - The parameter vector of a network lists its layers in order; a
+ *     convolution contributes weights [kh][kw][Cin][Cout] then bias [Cout]
+ *     (if it has one); a dense layer weights [in][out] (in = flattened
+ *     H,W,C of its input) then bias; batch normalisation gamma [C] then
+ *     beta [C].  After all trainable values come, for every batch-norm layer
+ *     in order, running mean [C] and running variance [C].  m_train counts
+ *     the trainable values, m_total includes the running statistics.
+ *   - Replica k's vector starts at replicas_dev + k*row_stride floats;
+ *     row_stride >= m_total is a multiple of 64 (hadfl_param_count); the
+ *     padding is kept zero.
+ */
+#ifndef HADFL_H
+#define HADFL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef HADFL_BUILD
+#define HADFL_API __attribute__((visibility("default")))
+#else
+#define HADFL_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hadfl_ctx hadfl_ctx;   /* opaque; host memory owned by the library */
+
+typedef enum {
+    HADFL_OK = 0,
+    HADFL_EINVAL = 1,        /* bad argument: null/misaligned pointer, size out of range, ... */
+    HADFL_ENOMEM = 2,        /* host allocation failed */
+    HADFL_EDEVICE = 3,       /* a HIP call failed; text in hadfl_last_error */
+    HADFL_ESTATE = 4,        /* call out of order (e.g. aggregate before select) */
+    HADFL_EUNSUPPORTED = 5   /* valid request this build has no kernel for */
+} hadfl_status;
+
+typedef enum {
+    HADFL_NET_MLP = 0,       /* 784-128-10, ReLU */
+    HADFL_NET_CNN2 = 1,      /* conv3x3(3->32) ReLU pool conv3x3(32->64) ReLU pool FC(4096->10) */
+    HADFL_NET_RESNET18 = 2,  /* ResNet-18 for 32x32 inputs (paper Sec. 4.1) */
+    HADFL_NET_VGG16 = 3,     /* VGG-16 with batch norm for 32x32 inputs (paper Sec. 4.1) */
+    HADFL_NET_NONE = 4,      /* no training: bare parameter rows of m_none values (aggregation only) */
+    HADFL_NET_CUSTOM = 5     /* layer list given in custom_ops */
+} hadfl_net;
+
+typedef enum {
+    HADFL_OP_CONV = 0, HADFL_OP_DENSE = 1, HADFL_OP_RELU = 2, HADFL_OP_MAXPOOL = 3,
+    HADFL_OP_BN = 4, HADFL_OP_ADD = 5, HADFL_OP_GAP = 6
+} hadfl_op_type;
+
+/* One layer of a custom network.  Layer i reads tensor in0 (and in1 for ADD) and writes tensor i+1;
+ * tensor 0 is the input batch.  k/stride/pad: convolution geometry; cout: output channels/features;
+ * bias: nonzero if the layer has a bias.  MAXPOOL is 2x2 stride 2; GAP averages over H,W. */
+typedef struct { int32_t type, in0, in1, k, stride, pad, cout, bias; } hadfl_op;
+
+typedef struct {
+    int32_t n_replicas;      /* K: devices simulated as replicas (Algorithm 1's available set at most) */
+    int32_t n_select;        /* N_p: replicas drawn per aggregation (Sec. 3.3) */
+    int32_t net;             /* hadfl_net */
+    int32_t bf16;            /* 0: fp32 everywhere; 1: bf16 weights/activations, fp32 master + accumulate */
+    int32_t batch;           /* B, the same on every replica (Sec. 2.1) */
+    int32_t n_samples;       /* samples per replica shard; multiple of batch */
+    int32_t in_dim[3];       /* H, W, C of one sample */
+    int32_t n_classes;
+    float lr;                /* learning rate of the local update (Sec. 2.2) */
+    float momentum;          /* 0 gives exactly the paper's update */
+    int32_t t_sync;          /* aggregation every t_sync hyperperiods (Sec. 2.3) */
+    int32_t steps_per_unit;  /* mini-batch steps per unit of the step-count rule */
+    int32_t weight_mode;     /* 0: a_k = Flag_k / sum Flag (the paper's aggregate with unit weight sum);
+                                1: extension, a_k = Flag_k f_k / sum Flag f with f of the selection function */
+    int32_t n_custom_ops;    /* HADFL_NET_CUSTOM only */
+    uint64_t seed;           /* key of the counter-based generator that drives the selection */
+    int64_t m_none;          /* HADFL_NET_NONE only: values per replica */
+    const hadfl_op *custom_ops;   /* host; copied at init */
+} hadfl_config;
+
+typedef struct { int64_t offset, count; int32_t kind, fan_in; } hadfl_tensor_info;
+/* kind: 0 weight, 1 bias, 2 gamma, 3 beta, 4 running mean, 5 running variance */
+
+/* Sizes of the parameter vector of cfg's network (layout described at the top). */
+HADFL_API hadfl_status hadfl_param_count(const hadfl_config *cfg, int64_t *m_train, int64_t *m_total, int64_t *row_stride);
+
+/* Parameter tensors in vector order.  Writes at most cap rows to out (host) and the full count to *n. */
+HADFL_API hadfl_status hadfl_param_layout(const hadfl_config *cfg, hadfl_tensor_info *out, int32_t cap, int32_t *n);
+
+/* Bytes the caller must provide: params_bytes for replicas_dev (n_replicas rows of row_stride floats),
+ * scratch_bytes for scratch_dev (momentum, gradients, activations, the aggregate, small state). */
+HADFL_API hadfl_status hadfl_workspace_bytes(const hadfl_config *cfg, size_t *params_bytes, size_t *scratch_bytes);
+
+/* Algorithm 1, first line: every replica starts from the same model w0; momentum, batch cursors and versions
+ * start at zero.  Also fixes the local step count of every replica (Sec. 2.3, Sec. 3.3):
+ *   E_k = t_sync * steps_per_unit * ratio[k] / gcd(ratio), ratio[k] > 0 the computing-power ratio of
+ * device k (larger = faster, Sec. 4.1).
+ *   w0_dev        dev, [m_total] floats in the layout above; NULL keeps replicas_dev as the caller filled it
+ *   replicas_dev  dev, params_bytes, 256-byte aligned
+ *   scratch_dev   dev, scratch_bytes, 256-byte aligned; contents need not be initialised
+ *   x_dev         dev, [n_replicas][n_samples][H][W][C] floats (NULL for HADFL_NET_NONE)
+ *   y_dev         dev, [n_replicas][n_samples] int32 labels in [0, n_classes)
+ *   ratio_host    host, [n_replicas] int32
+ *   stream        hipStream_t (NULL = the default stream)
+ * Errors: EINVAL for null/misaligned pointers, n_select outside [1, n_replicas], ratio <= 0,
+ * n_samples % batch != 0, sizes out of range; EUNSUPPORTED for layer shapes without a kernel. */
+HADFL_API hadfl_status hadfl_init_replicas(const hadfl_config *cfg, const void *w0_dev, void *replicas_dev,
+                                 void *scratch_dev, const void *x_dev, const int32_t *y_dev,
+                                 const int32_t *ratio_host, void *stream, hadfl_ctx **out);
+
+/* Algorithm 1, inner loop, for all replicas at once: replica k runs E_k steps, each = next batch of its shard
+ * (rows [(c_k*B) mod n_samples, +B), c_k counts its steps since init), forward, softmax cross-entropy averaged
+ * over the batch, backward, buf = momentum*buf + g, w = w - lr*buf (local-update equation of Sec. 2.2).
+ * The version of replica k becomes the number of steps it completed in this call. */
+HADFL_API hadfl_status hadfl_local_steps(hadfl_ctx *ctx);
+
+/* Sec. 3.3, probability-based selection: mu = third quartile of the available replicas' versions,
+ * f_k = exp(-(v_k-mu)^2/2), P_k = f_k / sum f; n_select distinct replicas are drawn one after another in
+ * proportion to f over those remaining, with uniforms from Philox4x32-10 keyed by cfg.seed at counter
+ * (cycle, draw).  The result stays on the device for hadfl_aggregate.
+ *   versions_dev  dev, [n_replicas] int32, or NULL for the versions hadfl_local_steps recorded
+ *   avail_host    host, [n_replicas] bytes (0 = device absent this round, never selected), or NULL = all
+ * Errors: EINVAL if fewer than n_select replicas are available. */
+HADFL_API hadfl_status hadfl_select(hadfl_ctx *ctx, const int32_t *versions_dev, const uint8_t *avail_host, uint64_t cycle);
+
+/* Sec. 2.3, partial aggregation over the replicas flagged by the last hadfl_select:
+ *   w_agg[j] = sum_k a_k * w_k[j], added in ascending k in fp32,
+ * then, if resync != 0, Algorithm 1's global synchronisation: every replica's parameters become w_agg
+ * (optimiser state and batch cursors are local and stay).  ESTATE without a preceding hadfl_select. */
+HADFL_API hadfl_status hadfl_aggregate(hadfl_ctx *ctx, int32_t resync);
+
+/* Read-back; each synchronises the stream.  All outputs are host arrays. */
+HADFL_API hadfl_status hadfl_get_steps(hadfl_ctx *ctx, int32_t *steps /* [n_replicas] E_k */);
+HADFL_API hadfl_status hadfl_get_versions(hadfl_ctx *ctx, int32_t *versions /* [n_replicas] */, int64_t *cursors /* [n_replicas] or NULL */);
+HADFL_API hadfl_status hadfl_get_selected(hadfl_ctx *ctx, int32_t *selected /* [n_select], draw order */,
+                                uint8_t *flag /* [n_replicas] or NULL */, float *weights /* [n_replicas] a_k or NULL */);
+/* replica in [0, n_replicas), or -1 for the last aggregate; n values (<= m_total) in the vector layout */
+HADFL_API hadfl_status hadfl_get_params(hadfl_ctx *ctx, int32_t replica, float *out, size_t n);
+HADFL_API hadfl_status hadfl_get_losses(hadfl_ctx *ctx, float *loss /* [n_replicas] batch-mean loss of each replica's last step */);
+
+/* Per-kernel timing with HIP events on the context's stream.  While enabled, every kernel launch is bracketed
+ * by events (this serialises nothing but adds overhead: use a separate pass from throughput timing).
+ * hadfl_profile_read synchronises, then writes up to cap rows: name (<= 47 chars), launches, total ms. */
+typedef struct { char name[48]; int64_t launches; double total_ms; } hadfl_kernel_time;
+HADFL_API hadfl_status hadfl_profile_enable(hadfl_ctx *ctx, int32_t on);
+HADFL_API hadfl_status hadfl_profile_read(hadfl_ctx *ctx, hadfl_kernel_time *out, int32_t cap, int32_t *n);
+
+HADFL_API const char *hadfl_last_error(const hadfl_ctx *ctx);   /* ctx may be NULL: error of the last failed init on this thread */
+HADFL_API void hadfl_destroy(hadfl_ctx *ctx);                   /* frees host state only; NULL is a no-op */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HADFL_H */
