@@ -276,7 +276,7 @@ hadfl_status hadfl_init_replicas(const hadfl_config* cfg, const void* w0_dev, vo
     ctx->tb.x = (const float*)x_dev; ctx->tb.y = y_dev;
     ctx->tb.order = (int32_t*)(b + c.order);
     ctx->tb.versions = (int32_t*)(b + c.versions);
-    ctx->tb.cursor = (int64_t*)(b + c.cursor);
+    ctx->tb.cursor = (long long*)(b + c.cursor);
     ctx->tb.loss = (float*)(b + c.loss);
     ctx->steps_d = (int32_t*)(b + c.steps);
     ctx->selected = (int32_t*)(b + c.selected);

@@ -1,0 +1,355 @@
+// Memory-bound layers of the local-training path, grouped over the active replicas: ReLU, 2x2 max-pool,
+// residual add, global average pool, batch normalisation (training mode), softmax cross-entropy and the fused
+// SGD/momentum update.  All reductions run in a fixed order (no floating-point atomics): results are repeatable.
+#include "train_kernels.h"
+
+namespace hadfl {
+namespace {
+
+constexpr float kBnEps = 1e-5f;
+constexpr float kBnStatMomentum = 0.1f;
+
+__device__ __forceinline__ long long gtid() { return (long long)blockIdx.x * blockDim.x + threadIdx.x; }
+__device__ __forceinline__ long long gstride() { return (long long)gridDim.x * blockDim.x; }
+
+__global__ __launch_bounds__(256) void relu_fwd_kernel(EwParams p)
+{
+    const int rep = p.order[blockIdx.y];
+    const float* in = p.in + rep * p.in_rep;
+    float* out = p.out + rep * p.out_rep;
+    for (long long i = gtid(); i < p.count; i += gstride()) out[i] = fmaxf(in[i], 0.f);
+}
+
+__global__ __launch_bounds__(256) void relu_bwd_kernel(EwParams p)
+{
+    const int rep = p.order[blockIdx.y];
+    const float* x = p.in + rep * p.in_rep;
+    const float* dout = p.in2 + rep * p.in2_rep;
+    float* din = p.out + rep * p.out_rep;
+    for (long long i = gtid(); i < p.count; i += gstride()) {
+        const float g = x[i] > 0.f ? dout[i] : 0.f;
+        din[i] = p.accumulate ? din[i] + g : g;
+    }
+}
+
+// count = pooled elements; in is [B][H][W][C]
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(EwParams p)
+{
+    const int rep = p.order[blockIdx.y];
+    const float* in = p.in + rep * p.in_rep;
+    float* out = p.out + rep * p.out_rep;
+    const int Ho = p.H / 2, Wo = p.W / 2;
+    for (long long i = gtid(); i < p.count; i += gstride()) {
+        const int c = (int)(i % p.C);
+        long long t = i / p.C;
+        const int xo = (int)(t % Wo); t /= Wo;
+        const int yo = (int)(t % Ho);
+        const int b = (int)(t / Ho);
+        const float* q = in + (((long long)b * p.H + 2 * yo) * p.W + 2 * xo) * p.C + c;
+        const long long rowp = (long long)p.W * p.C;
+        out[i] = fmaxf(fmaxf(q[0], q[p.C]), fmaxf(q[rowp], q[rowp + p.C]));
+    }
+}
+
+// the gradient goes to the first maximal element in (dy, dx) scan order; count = pooled elements
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(EwParams p)
+{
+    const int rep = p.order[blockIdx.y];
+    const float* x = p.in + rep * p.in_rep;
+    const float* dout = p.in2 + rep * p.in2_rep;
+    float* din = p.out + rep * p.out_rep;
+    const int Ho = p.H / 2, Wo = p.W / 2;
+    for (long long i = gtid(); i < p.count; i += gstride()) {
+        const int c = (int)(i % p.C);
+        long long t = i / p.C;
+        const int xo = (int)(t % Wo); t /= Wo;
+        const int yo = (int)(t % Ho);
+        const int b = (int)(t / Ho);
+        const long long base = (((long long)b * p.H + 2 * yo) * p.W + 2 * xo) * p.C + c;
+        const long long rowp = (long long)p.W * p.C;
+        const long long off[4] = {0, p.C, rowp, rowp + p.C};
+        float m = x[base]; int arg = 0;
+#pragma unroll
+        for (int j = 1; j < 4; ++j) { const float v = x[base + off[j]]; if (v > m) { m = v; arg = j; } }
+        const float g = dout[i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float v = (j == arg) ? g : 0.f;
+            float* d = din + base + off[j];
+            *d = p.accumulate ? *d + v : v;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void add_fwd_kernel(EwParams p)
+{
+    const int rep = p.order[blockIdx.y];
+    const float* a = p.in + rep * p.in_rep;
+    const float* b = p.in2 + rep * p.in2_rep;
+    float* out = p.out + rep * p.out_rep;
+    for (long long i = gtid(); i < p.count; i += gstride()) out[i] = a[i] + b[i];
+}
+
+__global__ __launch_bounds__(256) void pass_grad_kernel(EwParams p)
+{
+    const int rep = p.order[blockIdx.y];
+    const float* dout = p.in + rep * p.in_rep;
+    float* din = p.out + rep * p.out_rep;
+    for (long long i = gtid(); i < p.count; i += gstride()) din[i] = p.accumulate ? din[i] + dout[i] : dout[i];
+}
+
+// out[b][c] = mean over H*W; count = B*C
+__global__ __launch_bounds__(256) void gap_fwd_kernel(EwParams p)
+{
+    const int rep = p.order[blockIdx.y];
+    const float* in = p.in + rep * p.in_rep;
+    float* out = p.out + rep * p.out_rep;
+    const int hw = p.H * p.W;
+    for (long long i = gtid(); i < p.count; i += gstride()) {
+        const int c = (int)(i % p.C);
+        const long long b = i / p.C;
+        float s = 0.f;
+        for (int q = 0; q < hw; ++q) s += in[(b * hw + q) * p.C + c];
+        out[i] = s / (float)hw;
+    }
+}
+
+// din[b][q][c] (+)= dout[b][c] / (H*W); count = B*H*W*C
+__global__ __launch_bounds__(256) void gap_bwd_kernel(EwParams p)
+{
+    const int rep = p.order[blockIdx.y];
+    const float* dout = p.in + rep * p.in_rep;
+    float* din = p.out + rep * p.out_rep;
+    const int hw = p.H * p.W;
+    for (long long i = gtid(); i < p.count; i += gstride()) {
+        const int c = (int)(i % p.C);
+        const long long b = i / ((long long)hw * p.C);
+        const float g = dout[b * p.C + c] / (float)hw;
+        din[i] = p.accumulate ? din[i] + g : g;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------
+// Batch normalisation over rows = B*H*W per channel.  Two reduction passes (sum, then squared deviation from
+// the mean) keep the variance accurate in fp32; every pass writes per-chunk partial sums that the next kernel
+// adds in chunk order.
+// Block = 256 threads = 64 channel lanes x 4 row lanes; grid = (chunks * ceil(C/64), n_active).
+// ------------------------------------------------------------------------------------------------------
+template <int PASS>   // 0: sum x   1: sum (x-mean)^2   2 (backward): sum dy and sum dy*xhat
+__global__ __launch_bounds__(256) void bn_reduce_kernel(BnParams p)
+{
+    __shared__ float red[2][4][64];
+    const int g = blockIdx.y, rep = p.order[g];
+    const int cgroups = (p.C + 63) / 64;
+    const int chunk = blockIdx.x / cgroups, cg = blockIdx.x % cgroups;
+    const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+    const int c = cg * 64 + cl;
+    const float* x = p.x + rep * p.x_rep;
+    float* part = p.partial + g * p.partial_rep;
+    float mean = 0.f, istd = 0.f;
+    if (PASS >= 1 && c < p.C) {
+        if (PASS == 1) {
+            float s = 0.f;
+            for (int k = 0; k < p.chunks; ++k) s += part[((long long)k * 2 + 0) * p.C + c];
+            mean = s / (float)p.rows;
+        } else {
+            const float* sv = p.saved + rep * p.saved_rep;
+            mean = sv[c]; istd = sv[p.C + c];
+        }
+    }
+    const int r0 = chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
+    float s0 = 0.f, s1 = 0.f;
+    if (c < p.C) {
+        const float* dy = (PASS == 2) ? p.dy + rep * p.dy_rep : nullptr;
+        for (int r = r0 + rl; r < r1; r += 4) {
+            const float v = x[(long long)r * p.C + c];
+            if (PASS == 0) s0 += v;
+            else if (PASS == 1) { const float d = v - mean; s1 += d * d; }
+            else { const float d = dy[(long long)r * p.C + c]; s0 += d; s1 += d * ((v - mean) * istd); }
+        }
+    }
+    red[0][rl][cl] = s0; red[1][rl][cl] = s1;
+    __syncthreads();
+    if (rl == 0 && c < p.C) {
+        const float t0 = (red[0][0][cl] + red[0][1][cl]) + (red[0][2][cl] + red[0][3][cl]);
+        const float t1 = (red[1][0][cl] + red[1][1][cl]) + (red[1][2][cl] + red[1][3][cl]);
+        if (PASS == 0) part[((long long)chunk * 2 + 0) * p.C + c] = t0;
+        else if (PASS == 1) part[((long long)chunk * 2 + 1) * p.C + c] = t1;
+        else { part[((long long)chunk * 2 + 0) * p.C + c] = t0; part[((long long)chunk * 2 + 1) * p.C + c] = t1; }
+    }
+}
+
+// y = gamma * (x - mean) * istd + beta; the blocks of chunk 0 also store mean / istd and update the running statistics
+__global__ __launch_bounds__(256) void bn_apply_fwd_kernel(BnParams p)
+{
+    const int g = blockIdx.y, rep = p.order[g];
+    const int cgroups = (p.C + 63) / 64;
+    const int chunk = blockIdx.x / cgroups, cg = blockIdx.x % cgroups;
+    const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+    const int c = cg * 64 + cl;
+    if (c >= p.C) return;
+    const float* x = p.x + rep * p.x_rep;
+    float* y = p.y + rep * p.y_rep;
+    const float* part = p.partial + g * p.partial_rep;
+    float* row = p.params + rep * p.row_stride;
+    float s = 0.f, q = 0.f;
+    for (int k = 0; k < p.chunks; ++k) { s += part[((long long)k * 2 + 0) * p.C + c]; q += part[((long long)k * 2 + 1) * p.C + c]; }
+    const float mean = s / (float)p.rows, var = q / (float)p.rows;
+    const float istd = 1.0f / sqrtf(var + kBnEps);
+    const float gamma = row[p.w_off + c], beta = row[p.w_off + p.C + c];
+    if (chunk == 0 && rl == 0) {
+        float* sv = p.saved + rep * p.saved_rep;
+        sv[c] = mean; sv[p.C + c] = istd;
+        const float unb = p.rows > 1 ? q / (float)(p.rows - 1) : var;
+        float* rm = row + p.stat_off;
+        rm[c] = (1.f - kBnStatMomentum) * rm[c] + kBnStatMomentum * mean;
+        rm[p.C + c] = (1.f - kBnStatMomentum) * rm[p.C + c] + kBnStatMomentum * unb;
+    }
+    const int r0 = chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
+    for (int r = r0 + rl; r < r1; r += 4) {
+        const long long i = (long long)r * p.C + c;
+        y[i] = gamma * ((x[i] - mean) * istd) + beta;
+    }
+}
+
+// dx = gamma*istd*(dy - sum(dy)/n - xhat*sum(dy*xhat)/n); chunk-0 blocks write dgamma, dbeta
+__global__ __launch_bounds__(256) void bn_apply_bwd_kernel(BnParams p)
+{
+    const int g = blockIdx.y, rep = p.order[g];
+    const int cgroups = (p.C + 63) / 64;
+    const int chunk = blockIdx.x / cgroups, cg = blockIdx.x % cgroups;
+    const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+    const int c = cg * 64 + cl;
+    if (c >= p.C) return;
+    const float* x = p.x + rep * p.x_rep;
+    const float* dy = p.dy + rep * p.dy_rep;
+    float* dx = p.y + rep * p.y_rep;
+    const float* part = p.partial + g * p.partial_rep;
+    const float* sv = p.saved + rep * p.saved_rep;
+    float db = 0.f, dg = 0.f;
+    for (int k = 0; k < p.chunks; ++k) { db += part[((long long)k * 2 + 0) * p.C + c]; dg += part[((long long)k * 2 + 1) * p.C + c]; }
+    const float mean = sv[c], istd = sv[p.C + c];
+    const float gamma = p.params[rep * p.row_stride + p.w_off + c];
+    if (chunk == 0 && rl == 0) {
+        float* gr = p.grads + rep * p.row_stride + p.w_off;
+        gr[c] = dg; gr[p.C + c] = db;
+    }
+    const float inv_n = 1.0f / (float)p.rows, k1 = gamma * istd;
+    const int r0 = chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
+    for (int r = r0 + rl; r < r1; r += 4) {
+        const long long i = (long long)r * p.C + c;
+        const float xh = (x[i] - mean) * istd;
+        const float v = k1 * (dy[i] - db * inv_n - xh * dg * inv_n);
+        dx[i] = p.accumulate ? dx[i] + v : v;
+    }
+}
+
+// One workgroup per replica, one thread per sample: softmax, loss, d(loss)/d(logits); loss summed by an LDS tree.
+__global__ __launch_bounds__(1024) void softmax_ce_kernel(LossParams p)
+{
+    __shared__ float red[1024];
+    const int rep = p.order[blockIdx.x];
+    const int b = threadIdx.x;
+    float li = 0.f;
+    if (b < p.batch) {
+        const long long first = (p.cursor[rep] * (long long)p.batch) % p.n_samples;
+        const int label = p.y[(long long)rep * p.n_samples + first + b];
+        const float* z = p.logits + rep * p.logits_rep + (long long)b * p.n_classes;
+        float* dz = p.dlogits + rep * p.dlogits_rep + (long long)b * p.n_classes;
+        float m = z[0];
+        for (int j = 1; j < p.n_classes; ++j) m = fmaxf(m, z[j]);
+        float s = 0.f;
+        for (int j = 0; j < p.n_classes; ++j) s += expf(z[j] - m);
+        li = (logf(s) + m - z[label]) / (float)p.batch;
+        const float inv = 1.0f / s;
+        for (int j = 0; j < p.n_classes; ++j)
+            dz[j] = (expf(z[j] - m) * inv - (j == label ? 1.f : 0.f)) / (float)p.batch;
+    }
+    red[b] = li;
+    __syncthreads();
+    for (int w = blockDim.x / 2; w > 0; w >>= 1) {
+        if (b < w) red[b] += red[b + w];
+        __syncthreads();
+    }
+    if (b == 0) p.loss[rep] = red[0];
+}
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+// buf = momentum*buf + g; w = w - lr*buf (local-update equation; momentum 0 is the paper's form).
+__global__ __launch_bounds__(256) void sgd_kernel(SgdParams p)
+{
+    const int rep = p.order[blockIdx.y];
+    f4* w = reinterpret_cast<f4*>(p.w + rep * p.row_stride);
+    const f4* g = reinterpret_cast<const f4*>(p.g + rep * p.row_stride);
+    f4* buf = p.buf ? reinterpret_cast<f4*>(p.buf + rep * p.row_stride) : nullptr;
+    const long long n4 = p.count / 4;
+    for (long long i = gtid(); i < n4; i += gstride()) {
+        f4 d = g[i];
+        if (buf) { d = buf[i] * p.momentum + d; buf[i] = d; }
+        w[i] = w[i] - d * p.lr;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) { p.cursor[rep] += 1; p.versions[rep] += 1; }
+}
+
+dim3 ew_grid(long long count, int n_active)
+{
+    long long b = (count + 255) / 256;
+    if (b > 2048) b = 2048;
+    if (b < 1) b = 1;
+    return dim3((unsigned)b, (unsigned)n_active);
+}
+
+}  // namespace
+
+#define HADFL_EW_LAUNCH(fn, kern) \
+    hipError_t fn(const EwParams& p, int n_active, hipStream_t s) { \
+        if (n_active < 1 || p.count < 1) return hipSuccess; \
+        hipLaunchKernelGGL(kern, ew_grid(p.count, n_active), dim3(256), 0, s, p); \
+        return hipGetLastError(); }
+HADFL_EW_LAUNCH(launch_relu_fwd, relu_fwd_kernel)
+HADFL_EW_LAUNCH(launch_relu_bwd, relu_bwd_kernel)
+HADFL_EW_LAUNCH(launch_maxpool_fwd, maxpool_fwd_kernel)
+HADFL_EW_LAUNCH(launch_maxpool_bwd, maxpool_bwd_kernel)
+HADFL_EW_LAUNCH(launch_add_fwd, add_fwd_kernel)
+HADFL_EW_LAUNCH(launch_pass_grad, pass_grad_kernel)
+HADFL_EW_LAUNCH(launch_gap_fwd, gap_fwd_kernel)
+HADFL_EW_LAUNCH(launch_gap_bwd, gap_bwd_kernel)
+#undef HADFL_EW_LAUNCH
+
+hipError_t launch_bn_fwd(const BnParams& p, int n_active, hipStream_t s)
+{
+    if (n_active < 1) return hipSuccess;
+    const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active), block(256);
+    hipLaunchKernelGGL(bn_reduce_kernel<0>, grid, block, 0, s, p);
+    hipLaunchKernelGGL(bn_reduce_kernel<1>, grid, block, 0, s, p);
+    hipLaunchKernelGGL(bn_apply_fwd_kernel, grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_bn_bwd(const BnParams& p, int n_active, hipStream_t s)
+{
+    if (n_active < 1) return hipSuccess;
+    const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active), block(256);
+    hipLaunchKernelGGL(bn_reduce_kernel<2>, grid, block, 0, s, p);
+    hipLaunchKernelGGL(bn_apply_bwd_kernel, grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax_ce(const LossParams& p, int n_active, hipStream_t s)
+{
+    if (n_active < 1) return hipSuccess;
+    int threads = 64;
+    while (threads < p.batch) threads *= 2;      // power of two for the tree; batch <= 1024 is checked at init
+    hipLaunchKernelGGL(softmax_ce_kernel, dim3((unsigned)n_active), dim3((unsigned)threads), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_sgd(const SgdParams& p, int n_active, hipStream_t s)
+{
+    if (n_active < 1) return hipSuccess;
+    hipLaunchKernelGGL(sgd_kernel, ew_grid(p.count / 4, n_active), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace hadfl

@@ -1,0 +1,328 @@
+// Host-side schedule of hadfl_local_steps: a fixed launch sequence per sub-step s = 1..E_max, each launch grouped
+// over the replicas that still have steps left (a prefix of the replicas ordered by step count, kept in device
+// memory).  There is no host loop over replicas and no host read-back inside a cycle.
+#include <algorithm>
+
+#include "train.h"
+#include "kernels.h"
+#include "train_kernels.h"
+
+namespace hadfl {
+
+class TrainEngine {
+public:
+    hadfl_config cfg;
+    NetPlan plan;
+    TrainBuffers buf;
+    std::vector<int32_t> steps;
+    int e_max = 0;
+    std::vector<int> n_active;            // n_active[s] = replicas with E_k > s
+    // per-tensor activation / gradient offsets (floats) inside one replica's block of `work`
+    std::vector<int64_t> act_off, grad_off;
+    int64_t rep_block = 0;                // floats of activations + gradients per replica
+    std::vector<int64_t> saved_off;       // per layer (BN): offset of saved mean/istd inside the replica block
+    int64_t shared_off = 0;               // start of the region shared by all layers (split-K partials, BN partials)
+    int64_t shared_floats = 0;
+    std::vector<int> splits;              // per layer: split-K factor of the weight gradient
+    std::vector<int> bn_chunks;           // per layer
+    std::vector<char> grad_written;       // scratch for the backward pass
+};
+
+namespace {
+
+int ilog2_exact(int v) { int s = 0; while ((1 << s) < v) ++s; return (1 << s) == v ? s : -1; }
+
+struct Layout {
+    std::vector<int64_t> act_off, grad_off, saved_off;
+    std::vector<int> splits, bn_chunks;
+    int64_t rep_block = 0, shared_floats = 0;
+};
+
+int64_t up64(int64_t v) { return (v + 63) / 64 * 64; }
+
+Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
+{
+    Layout L;
+    const int T = (int)plan.tensors.size();
+    const int64_t B = cfg.batch;
+    L.act_off.assign(T, -1); L.grad_off.assign(T, -1);
+    int64_t off = 0;
+    for (int t = 1; t < T; ++t) { L.act_off[t] = off; off += up64(B * plan.tensors[t].numel()); }
+    for (int t = 1; t < T; ++t) { L.grad_off[t] = off; off += up64(B * plan.tensors[t].numel()); }
+    L.saved_off.assign(plan.layers.size(), -1);
+    L.splits.assign(plan.layers.size(), 1);
+    L.bn_chunks.assign(plan.layers.size(), 1);
+    int64_t shared = 0;
+    for (size_t i = 0; i < plan.layers.size(); ++i) {
+        const Layer& l = plan.layers[i];
+        const TensorShape a = plan.tensors[l.in0], r = plan.tensors[l.out];
+        if (l.type == HADFL_OP_BN) {
+            L.saved_off[i] = off; off += up64(2 * (int64_t)a.c);
+            const int64_t rows = B * a.h * a.w;
+            int chunks = (int)std::min<int64_t>(128, std::max<int64_t>(1, rows / 128));
+            L.bn_chunks[i] = chunks;
+            shared = std::max<int64_t>(shared, (int64_t)cfg.n_replicas * chunks * 2 * a.c);
+        } else if (l.type == HADFL_OP_CONV || l.type == HADFL_OP_DENSE) {
+            // weight gradient: contraction over K = B*Ho*Wo rows; split it until the launch has enough workgroups
+            const int64_t K = B * r.h * r.w;
+            const int64_t M = (l.type == HADFL_OP_CONV ? (int64_t)l.k * l.k * a.c : a.numel()) + (l.bias ? 1 : 0);
+            const int64_t tiles = ((M + 127) / 128) * ((l.cout + 127) / 128);
+            int64_t want = (1024 + tiles * cfg.n_replicas - 1) / (tiles * cfg.n_replicas);
+            int64_t maxs = std::max<int64_t>(1, K / 64);
+            int s = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, maxs), 64));
+            L.splits[i] = s;
+            if (s > 1) shared = std::max<int64_t>(shared, (int64_t)cfg.n_replicas * s * up64(M * l.cout));
+        }
+    }
+    L.rep_block = up64(off);
+    L.shared_floats = up64(shared);
+    return L;
+}
+
+}  // namespace
+
+int64_t train_work_floats(const hadfl_config& cfg, const NetPlan& plan)
+{
+    if (cfg.net == HADFL_NET_NONE) return 0;
+    const Layout L = make_layout(cfg, plan);
+    return L.rep_block * cfg.n_replicas + L.shared_floats;
+}
+
+hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const TrainBuffers& buf,
+                          const std::vector<int32_t>& steps, const std::vector<int32_t>& order,
+                          TrainEngine** out, std::string& err)
+{
+    (void)order;
+    if (cfg.bf16) { err = "the bf16 path is not built yet"; return HADFL_EUNSUPPORTED; }
+    TrainEngine* e = new TrainEngine();
+    e->cfg = cfg; e->plan = plan; e->buf = buf; e->steps = steps;
+    e->e_max = *std::max_element(steps.begin(), steps.end());
+    e->n_active.assign(e->e_max, 0);
+    for (int s = 0; s < e->e_max; ++s)
+        for (int32_t v : steps) e->n_active[s] += v > s ? 1 : 0;
+    const Layout L = make_layout(cfg, plan);
+    e->act_off = L.act_off; e->grad_off = L.grad_off; e->saved_off = L.saved_off;
+    e->splits = L.splits; e->bn_chunks = L.bn_chunks;
+    e->rep_block = L.rep_block;
+    e->shared_off = L.rep_block * cfg.n_replicas;
+    e->shared_floats = L.shared_floats;
+    *out = e;
+    return HADFL_OK;
+}
+
+void train_destroy(TrainEngine* e) { delete e; }
+
+namespace {
+
+struct Runner {
+    TrainEngine& e;
+    hipStream_t s;
+    Profiler* prof;
+    int na = 0;
+    hipError_t rc = hipSuccess;
+    const char* failed = nullptr;
+
+    const float* act(int t) const { return t == 0 ? e.buf.x : e.buf.work + e.act_off[t]; }
+    float* actw(int t) const { return e.buf.work + e.act_off[t]; }
+    float* grad(int t) const { return e.buf.work + e.grad_off[t]; }
+    float* shared() const { return e.buf.work + e.shared_off; }
+
+    template <typename F> void run(const char* name, F&& f)
+    {
+        if (rc != hipSuccess) return;
+        if (prof) prof->begin(name, s);
+        rc = f();
+        if (prof) prof->end(s);
+        if (rc != hipSuccess) failed = name;
+    }
+
+    GemmParams gemm_base(const Layer& l) const
+    {
+        const TensorShape a = e.plan.tensors[l.in0], r = e.plan.tensors[l.out];
+        GemmParams p{};
+        p.B = e.cfg.batch;
+        if (l.type == HADFL_OP_CONV) {
+            p.H = a.h; p.W = a.w; p.Cin = a.c; p.Ho = r.h; p.Wo = r.w; p.Cout = l.cout;
+            p.R = p.S = l.k; p.stride = l.stride; p.pad = l.pad;
+        } else {
+            p.H = p.W = p.Ho = p.Wo = 1; p.Cin = (int)a.numel(); p.Cout = l.cout;
+            p.R = p.S = 1; p.stride = 1; p.pad = 0;
+        }
+        p.splits = 1; p.kchunk = 1 << 30;
+        p.hw_shift = ilog2_exact(p.Ho * p.Wo); p.w_shift = ilog2_exact(p.Wo);
+        if (p.hw_shift < 0 || p.w_shift < 0) p.hw_shift = p.w_shift = -1;
+        p.w = e.buf.replicas + l.w_off; p.w_rep = e.plan.row_stride;
+        p.has_bias = l.bias;
+        p.order = e.buf.order;
+        p.n_samples = e.cfg.n_samples; p.batch = e.cfg.batch; p.sample_sz = e.plan.tensors[0].numel();
+        return p;
+    }
+
+    void forward_layer(size_t i)
+    {
+        const Layer& l = e.plan.layers[i];
+        const TensorShape a = e.plan.tensors[l.in0], r = e.plan.tensors[l.out];
+        const int64_t B = e.cfg.batch;
+        EwParams q{};
+        q.order = e.buf.order; q.B = (int)B; q.H = a.h; q.W = a.w; q.C = a.c;
+        q.in = act(l.in0); q.in_rep = e.rep_block;
+        q.out = actw(l.out); q.out_rep = e.rep_block;
+        q.count = B * r.numel();
+        switch (l.type) {
+        case HADFL_OP_CONV:
+        case HADFL_OP_DENSE: {
+            GemmParams p = gemm_base(l);
+            p.mode = kFwd;
+            p.M = (int)(B * p.Ho * p.Wo); p.N = p.Cout; p.K = p.R * p.S * p.Cin;
+            p.a = act(l.in0); p.a_rep = e.rep_block;
+            p.cursor = l.in0 == 0 ? e.buf.cursor : nullptr;
+            p.out = actw(l.out); p.out_rep = e.rep_block;
+            run(l.type == HADFL_OP_CONV ? "conv_fwd" : "dense_fwd", [&] { return launch_gemm(p, na, s); });
+            break; }
+        case HADFL_OP_RELU: run("relu_fwd", [&] { return launch_relu_fwd(q, na, s); }); break;
+        case HADFL_OP_MAXPOOL: run("maxpool_fwd", [&] { return launch_maxpool_fwd(q, na, s); }); break;
+        case HADFL_OP_ADD:
+            q.in2 = act(l.in1); q.in2_rep = e.rep_block;
+            run("add_fwd", [&] { return launch_add_fwd(q, na, s); });
+            break;
+        case HADFL_OP_GAP: run("gap_fwd", [&] { return launch_gap_fwd(q, na, s); }); break;
+        case HADFL_OP_BN: {
+            BnParams b = bn_params(i);
+            run("bn_fwd", [&] { return launch_bn_fwd(b, na, s); });
+            break; }
+        }
+    }
+
+    BnParams bn_params(size_t i) const
+    {
+        const Layer& l = e.plan.layers[i];
+        const TensorShape a = e.plan.tensors[l.in0];
+        BnParams b{};
+        b.x = act(l.in0); b.x_rep = e.rep_block;
+        b.y = actw(l.out); b.y_rep = e.rep_block;
+        b.params = e.buf.replicas; b.grads = e.buf.grad; b.row_stride = e.plan.row_stride;
+        b.w_off = l.w_off; b.stat_off = l.stat_off;
+        b.saved = e.buf.work + e.saved_off[i]; b.saved_rep = e.rep_block;
+        b.rows = (int)((int64_t)e.cfg.batch * a.h * a.w); b.C = a.c;
+        b.chunks = e.bn_chunks[i];
+        b.chunk_rows = (b.rows + b.chunks - 1) / b.chunks;
+        b.partial = shared(); b.partial_rep = (long long)b.chunks * 2 * a.c;
+        b.order = e.buf.order;
+        return b;
+    }
+
+    // d(out) is complete; produce d(in0) (and d(in1)), and the parameter gradients of the layer
+    void backward_layer(size_t i)
+    {
+        const Layer& l = e.plan.layers[i];
+        const TensorShape a = e.plan.tensors[l.in0], r = e.plan.tensors[l.out];
+        const int64_t B = e.cfg.batch;
+        const bool need_din = l.in0 != 0;
+        const int acc0 = need_din ? (e.grad_written[l.in0] ? 1 : 0) : 0;
+        EwParams q{};
+        q.order = e.buf.order; q.B = (int)B; q.H = a.h; q.W = a.w; q.C = a.c;
+        q.accumulate = acc0;
+        if (need_din) { q.out = grad(l.in0); q.out_rep = e.rep_block; }
+        switch (l.type) {
+        case HADFL_OP_CONV:
+        case HADFL_OP_DENSE: {
+            // weight (and bias) gradient
+            GemmParams p = gemm_base(l);
+            p.mode = kWgrad;
+            p.M = p.R * p.S * p.Cin + (l.bias ? 1 : 0); p.N = p.Cout; p.K = (int)(B * p.Ho * p.Wo);
+            p.a = act(l.in0); p.a_rep = e.rep_block;
+            p.cursor = l.in0 == 0 ? e.buf.cursor : nullptr;
+            p.dy = grad(l.out); p.dy_rep = e.rep_block;
+            p.splits = e.splits[i];
+            const int64_t mn = (int64_t)p.M * p.N;
+            if (p.splits > 1) {
+                const int slabs = (p.K + 15) / 16;
+                p.kchunk = ((slabs + p.splits - 1) / p.splits) * 16;
+                p.out_split = (mn + 63) / 64 * 64;
+                p.out = shared(); p.out_rep = p.out_split * p.splits;
+            } else {
+                p.out = e.buf.grad + l.w_off; p.out_rep = e.plan.row_stride;
+            }
+            run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", [&] { return launch_gemm(p, na, s); });
+            if (p.splits > 1)
+                run("splitk_reduce", [&] { return launch_splitk_reduce(shared(), p.out_split, p.splits, e.buf.grad + l.w_off,
+                                                                       e.plan.row_stride, mn, e.buf.order, na, s); });
+            if (need_din) {
+                GemmParams d = gemm_base(l);
+                d.mode = kDgrad;
+                d.M = (int)(B * d.H * d.W); d.N = d.Cin; d.K = d.R * d.S * d.Cout;
+                d.a = grad(l.out); d.a_rep = e.rep_block;
+                d.out = grad(l.in0); d.out_rep = e.rep_block;
+                d.accumulate = acc0;
+                run(l.type == HADFL_OP_CONV ? "conv_dgrad" : "dense_dgrad", [&] { return launch_gemm(d, na, s); });
+            }
+            break; }
+        case HADFL_OP_RELU:
+            q.in = act(l.in0); q.in_rep = e.rep_block; q.in2 = grad(l.out); q.in2_rep = e.rep_block;
+            q.count = B * a.numel();
+            run("relu_bwd", [&] { return launch_relu_bwd(q, na, s); });
+            break;
+        case HADFL_OP_MAXPOOL:
+            q.in = act(l.in0); q.in_rep = e.rep_block; q.in2 = grad(l.out); q.in2_rep = e.rep_block;
+            q.count = B * r.numel();
+            run("maxpool_bwd", [&] { return launch_maxpool_bwd(q, na, s); });
+            break;
+        case HADFL_OP_ADD: {
+            q.in = grad(l.out); q.in_rep = e.rep_block; q.count = B * a.numel();
+            run("add_bwd", [&] { return launch_pass_grad(q, na, s); });
+            EwParams q2 = q;
+            if (l.in1 == l.in0) q2.accumulate = 1; else q2.accumulate = e.grad_written[l.in1] ? 1 : 0;
+            q2.out = grad(l.in1);
+            run("add_bwd", [&] { return launch_pass_grad(q2, na, s); });
+            e.grad_written[l.in1] = 1;
+            break; }
+        case HADFL_OP_GAP:
+            q.in = grad(l.out); q.in_rep = e.rep_block; q.count = B * a.numel();
+            run("gap_bwd", [&] { return launch_gap_bwd(q, na, s); });
+            break;
+        case HADFL_OP_BN: {
+            BnParams b = bn_params(i);
+            b.dy = grad(l.out); b.dy_rep = e.rep_block;
+            b.y = grad(l.in0); b.y_rep = e.rep_block;
+            b.accumulate = acc0;
+            run("bn_bwd", [&] { return launch_bn_bwd(b, na, s); });
+            break; }
+        }
+        if (need_din) e.grad_written[l.in0] = 1;
+    }
+};
+
+}  // namespace
+
+hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::string& err)
+{
+    Runner r{*e, s, (prof && prof->on) ? prof : nullptr};
+    const int N = e->cfg.n_replicas;
+    r.run("zero_versions", [&] { return launch_fill_u32((uint32_t*)e->buf.versions, 0u, N, s); });
+    const int T = (int)e->plan.tensors.size();
+    for (int step = 0; step < e->e_max && r.rc == hipSuccess; ++step) {
+        r.na = e->n_active[step];
+        for (size_t i = 0; i < e->plan.layers.size(); ++i) r.forward_layer(i);
+        LossParams lp{};
+        lp.logits = r.act(T - 1); lp.logits_rep = e->rep_block;
+        lp.dlogits = r.grad(T - 1); lp.dlogits_rep = e->rep_block;
+        lp.y = e->buf.y; lp.cursor = e->buf.cursor; lp.n_samples = e->cfg.n_samples; lp.batch = e->cfg.batch;
+        lp.n_classes = e->cfg.n_classes; lp.loss = e->buf.loss; lp.order = e->buf.order;
+        r.run("softmax_ce", [&] { return launch_softmax_ce(lp, r.na, s); });
+        e->grad_written.assign(T, 0);
+        e->grad_written[T - 1] = 1;
+        for (size_t i = e->plan.layers.size(); i-- > 0;) r.backward_layer(i);
+        SgdParams sp{};
+        sp.w = e->buf.replicas; sp.g = e->buf.grad; sp.buf = e->buf.mom; sp.row_stride = e->plan.row_stride;
+        sp.count = e->plan.train_end; sp.lr = e->cfg.lr; sp.momentum = e->cfg.momentum;
+        sp.cursor = e->buf.cursor; sp.versions = e->buf.versions; sp.order = e->buf.order;
+        r.run("sgd", [&] { return launch_sgd(sp, r.na, s); });
+    }
+    if (r.rc != hipSuccess) {
+        err = std::string("kernel launch failed in ") + (r.failed ? r.failed : "?") + ": " + hipGetErrorString(r.rc);
+        return HADFL_EDEVICE;
+    }
+    return HADFL_OK;
+}
+
+}  // namespace hadfl

@@ -16,7 +16,7 @@ struct TrainBuffers {
     const int32_t* y = nullptr;     // [N][n_samples]
     int32_t* order = nullptr;       // [N] replica indices sorted by step count, descending
     int32_t* versions = nullptr;    // [N]
-    int64_t* cursor = nullptr;      // [N] steps taken since init
+    long long* cursor = nullptr;     // [N] steps taken since init
     float* loss = nullptr;          // [N]
 };
 

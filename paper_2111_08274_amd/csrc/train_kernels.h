@@ -1,0 +1,90 @@
+// Kernel launchers of the local-training path (paper Sec. 2.1: forward, backward, update), all grouped over
+// replicas: grid z (or y) indexes a slot g of the active prefix, and order[g] is the replica it works on.
+#pragma once
+#include "hadfl_internal.h"
+
+namespace hadfl {
+
+enum GemmMode { kFwd = 0, kDgrad = 1, kWgrad = 2 };
+
+// One grouped implicit-GEMM launch C[M x N] = A[M x K] * B[K x N] per active replica.
+//  kFwd   : M = B*Ho*Wo, N = Cout,   K = R*S*Cin   A = im2col(X),        B = W[(r,s,ci)][co]
+//  kDgrad : M = B*H*W,   N = Cin,    K = R*S*Cout  A = col(dY),          B = W^T per tap
+//  kWgrad : M = R*S*Cin (+1 bias row), N = Cout, K = B*Ho*Wo  A = im2col(X)^T, B = dY   (split over K)
+// A dense layer is the 1x1 case with H = W = 1 and Cin = flattened input size.
+struct GemmParams {
+    int mode;
+    int B, H, W, Cin, Ho, Wo, Cout, R, S, stride, pad;
+    int M, N, K;
+    int tiles_m, tiles_n;
+    int kchunk, splits;
+    int hw_shift, w_shift;        // log2 of Ho*Wo and Wo (kWgrad) when powers of two, else -1
+    // activation-side source: X (fwd, wgrad) or dY (dgrad)
+    const float* a; long long a_rep;
+    const long long* cursor; int n_samples, batch; long long sample_sz;   // a is the data set when cursor != null
+    const float* w; long long w_rep;              // weights of this layer inside the replica rows
+    const float* dy; long long dy_rep;            // kWgrad: dY
+    float* out; long long out_rep, out_split;     // kWgrad with splits > 1: partial sums [g][split][M*N]
+    int has_bias, relu, accumulate;
+    const int* order;
+};
+hipError_t launch_gemm(const GemmParams& p, int n_active, hipStream_t s);
+// out[rep][i] = sum_s partial[g][s][i], s ascending
+hipError_t launch_splitk_reduce(const float* partial, long long split_stride, int splits, float* out, long long out_rep,
+                                long long count, const int* order, int n_active, hipStream_t s);
+
+struct EwParams {     // element-wise / pooling kernels
+    const float* in; long long in_rep;
+    const float* in2; long long in2_rep;
+    float* out; long long out_rep;
+    long long count;              // elements per replica of `out`
+    int B, H, W, C;               // input geometry where needed
+    int accumulate;
+    const int* order;
+};
+hipError_t launch_relu_fwd(const EwParams& p, int n_active, hipStream_t s);
+// out(din) (+)= in2(dout) where in(x) > 0
+hipError_t launch_relu_bwd(const EwParams& p, int n_active, hipStream_t s);
+hipError_t launch_maxpool_fwd(const EwParams& p, int n_active, hipStream_t s);
+// in = pool input x, in2 = dout (pooled shape), out = din (input shape)
+hipError_t launch_maxpool_bwd(const EwParams& p, int n_active, hipStream_t s);
+hipError_t launch_add_fwd(const EwParams& p, int n_active, hipStream_t s);
+// out(din) (+)= in(dout)
+hipError_t launch_pass_grad(const EwParams& p, int n_active, hipStream_t s);
+hipError_t launch_gap_fwd(const EwParams& p, int n_active, hipStream_t s);
+hipError_t launch_gap_bwd(const EwParams& p, int n_active, hipStream_t s);
+
+struct BnParams {
+    const float* x; long long x_rep;       // [rows][C]
+    float* y; long long y_rep;             // forward output / backward dx
+    const float* dy; long long dy_rep;
+    float* params; long long row_stride;   // replica rows; gamma at w_off, beta at w_off + C, running stats at stat_off
+    float* grads;                          // gradient rows (same layout)
+    long long w_off, stat_off;
+    float* saved; long long saved_rep;     // [2][C]: mean, 1/sqrt(var+eps)
+    float* partial; long long partial_rep; // [chunks][2][C]
+    int rows, C, chunks, chunk_rows;
+    int accumulate;
+    const int* order;
+};
+hipError_t launch_bn_fwd(const BnParams& p, int n_active, hipStream_t s);
+hipError_t launch_bn_bwd(const BnParams& p, int n_active, hipStream_t s);
+
+struct LossParams {
+    const float* logits; long long logits_rep;
+    float* dlogits; long long dlogits_rep;
+    const int* y; const long long* cursor; int n_samples, batch, n_classes;
+    float* loss;
+    const int* order;
+};
+hipError_t launch_softmax_ce(const LossParams& p, int n_active, hipStream_t s);
+
+struct SgdParams {
+    float* w; const float* g; float* buf; long long row_stride; long long count;   // count = trainable extent (multiple of 4)
+    float lr, momentum;
+    long long* cursor; int* versions;      // bumped once per replica per step
+    const int* order;
+};
+hipError_t launch_sgd(const SgdParams& p, int n_active, hipStream_t s);
+
+}  // namespace hadfl

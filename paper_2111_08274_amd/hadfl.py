@@ -59,6 +59,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libhadfl.so is not built: run `python -m paper_2111_08274_amd.build`")
+        # PyTorch ships its own HIP runtime; load it first so the library binds to the same runtime instance
+        # that owns the tensors and streams handed to it (two runtimes in one process do not share devices).
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, i32, i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)
         cfgp = ctypes.POINTER(HadflConfig)
