@@ -1,0 +1,248 @@
+"""Benchmark of one HADFL aggregation cycle on one MI355X.
+
+A step is one whole cycle -- every replica's local SGD steps, the probabilistic selection, the partial aggregate
+and the global synchronisation -- over seeded synthetic inputs already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1|2|3|4|5] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+PAPER_CONTEXT = {"speedup_vs_decentralized_fedavg": 3.15, "speedup_vs_pytorch_distributed": 4.68,
+                 "hardware": "4x V100, PCIe 3.0 x8, CIFAR-10, time-to-max-accuracy (Table 1, Sec. 4.2)"}
+# HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a plain copy of known size; see profiles/),
+# valid only while the kernel's source file is unchanged: (source file, sha256 at measurement, workload, bytes)
+TRAFFIC = {"aggregate": ("paper_2111_08274_amd/csrc/aggregate.hip",
+                         "82d23ef5563a057ede8300c4f42727e1f09a1ffe25e76238a46006f416269703", "agg-stress-n64",
+                         (174613.6 * 2.0 + 43648.5 * 1.0) * 1024.0)}
+
+
+def measured_traffic(kernel, workload):
+    import hashlib
+    ent = TRAFFIC.get(kernel)
+    if not ent or ent[2] != workload:
+        return None
+    try:
+        digest = hashlib.sha256(open(os.path.join(ROOT, ent[0]), "rb").read()).hexdigest()
+    except OSError:
+        return None
+    return ent[3] if digest == ent[1] else None
+
+
+GEMM_KERNELS = ("conv_fwd", "conv_dgrad", "conv_wgrad", "dense_fwd", "dense_dgrad", "dense_wgrad")
+
+
+def build_training(c):
+    import torch
+    from paper_2111_08274_amd import hadfl, synth
+    cfg, x, y = synth.config_inputs(c)
+    hc = hadfl.make_config(cfg["n_replicas"], cfg["n_select"], net=cfg["net"], bf16=cfg["bf16"], batch=cfg["batch"],
+                           n_samples=cfg["n_samples"], in_shape=cfg["in_shape"], lr=cfg["lr"],
+                           momentum=cfg["momentum"], seed=synth.SELECT_SEED)
+    w0 = synth.he_normal_init(hadfl.param_layout(hc), seed=0)
+    ctx = hadfl.Context(hc, cfg["ratio"], w0=w0, x=torch.as_tensor(x), y=torch.as_tensor(y))
+    return cfg, ctx, (w0, x, y)
+
+
+def build_aggregation():
+    import torch
+    from paper_2111_08274_amd import hadfl, synth
+    cfg = dict(synth.CONFIGS[4])
+    N, m = cfg["n_replicas"], cfg["m"]
+    hc = hadfl.make_config(N, cfg["n_select"], net="none", m_none=m, seed=synth.SELECT_SEED)
+    _, _, stride = hadfl.param_count(hc)
+    rep = torch.zeros(N * stride, dtype=torch.float32, device="cuda")
+    g = torch.Generator(device="cuda"); g.manual_seed(404)
+    rep.view(N, stride)[:, :m].normal_(0.0, cfg["std"], generator=g)
+    versions = torch.as_tensor(synth.versions_uniform(N, *cfg["version_range"], seed=304)).cuda()
+    ctx = hadfl.Context(hc, np.ones(N, dtype=np.int32), replicas=rep)
+    return cfg, ctx, versions
+
+
+def time_cycles(fn, steps, warmup):
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(warmup + i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def cpu_baseline_training(c, data, budget_s=20.0):
+    """The oracle as it stands, timed on whole cycles of the same workload until about budget_s of CPU work."""
+    import oracle
+    from oracle import nets
+    from paper_2111_08274_amd import synth
+    cfg = dict(synth.CONFIGS[c])
+    w0, x, y = data
+    fn, shape = nets.NETS[cfg["net"]]
+    net = oracle.Net(fn(), shape, bf16=bool(cfg["bf16"]))
+    N = cfg["n_replicas"]
+    ratio = cfg["ratio"] if cfg["ratio"] is not None else synth.compute_ratios(N, *cfg["ratio_range"], seed=200 + c)
+    cyc = oracle.Cycle(net, N, cfg["n_select"], w0, x.reshape(N, x.shape[1], -1), y, cfg["batch"], cfg["lr"],
+                       cfg["momentum"], ratio, seed=synth.SELECT_SEED)
+    per_cycle = int(cfg["batch"] * cyc.steps.sum())
+    done, t0 = 0, time.perf_counter()
+    while True:
+        cyc.run_cycle(done)
+        done += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or done >= cfg["cycles"] or el * (done + 1) / done > 1.5 * budget_s:
+            break
+    threads = min(oracle.lib().hadfl_oracle_num_threads(), N)
+    return {"value": per_cycle * done / el, "unit": "samples/s", "cores": threads, "kind": "oracle",
+            "sample": "%d whole cycle(s) of workload %d (%d samples each) in %.1f s" % (done, c, per_cycle, el)}
+
+
+def cpu_baseline_aggregation(cfg, budget_s=15.0):
+    import oracle
+    from paper_2111_08274_amd import synth
+    N, m, n_select = 8, cfg["m"], cfg["n_select"]      # only the selected rows are ever read: 8 rows suffice
+    rows = synth.replica_rows_gaussian(N, m, cfg["std"], seed=404)
+    a = np.full(N, 1.0 / n_select)
+    done, t0 = 0, time.perf_counter()
+    while True:
+        oracle.aggregate_f32(rows, a)
+        done += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or done >= 20:
+            break
+    gb = (n_select + 1) * 4.0 * m * done / 1e9
+    return {"value": gb / el, "unit": "GB/s", "cores": oracle.lib().hadfl_oracle_num_threads(), "kind": "oracle",
+            "sample": "%d aggregate(s) of 8 x %d fp32 rows in %.1f s" % (done, m, el)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", type=int, default=2, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy 5 times (known traffic, to scale rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: every replica lives in one MI355X's HBM and no collective is built; "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2111_08274_amd import hadfl, synth
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    hadfl.lib()                      # fails loudly if the HIP library is not built
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    c = args.workload
+    out = {"n_gpus": 1, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "data": "synthetic",
+           "paper_context": PAPER_CONTEXT}
+
+    # ---- aggregation on the 64 x 11.2M stress rows: always measured (the aggregation half of the metric) ----
+    acfg, actx, versions = build_aggregation()
+    a_steps = args.steps if (c == 4 and args.steps) else 200
+    a_warm = args.warmup if (c == 4 and args.warmup is not None) else 20
+    def agg_cycle(i):
+        actx.select(i, versions=versions)
+        actx.aggregate(resync=False)
+    t_agg = time_cycles(agg_cycle, a_steps, a_warm)
+    actx.profile(True)
+    for i in range(50):
+        agg_cycle(1000 + i)
+    prof = actx.profile_read()
+    actx.profile(False)
+    k = prof["aggregate"]
+    agg_ms = k["ms"] / k["launches"]
+    agg_gbs = k["bytes"] / k["launches"] / (agg_ms * 1e-3) / 1e9
+    aggregation = {"workload": acfg["name"], "ms_per_cycle": t_agg * 1e3, "kernel_ms": agg_ms,
+                   "algorithmic_bytes": k["bytes"] / k["launches"], "GB/s": agg_gbs, "frac_of_hbm_peak": agg_gbs / HBM_PEAK_GBS,
+                   "mode": "no broadcast: (n_select+1)*4*M bytes"}
+    if c == 4:
+        out.update(metric="aggregation HBM GB/s over one select+aggregate cycle", value=(k["bytes"] / k["launches"]) / t_agg / 1e9,
+                   unit="GB/s", steps=a_steps, warmup=a_warm, ms_per_step=t_agg * 1e3, dtype="f32",
+                   config={"workload": acfg["name"], "n_replicas": acfg["n_replicas"], "n_select": acfg["n_select"], "m": acfg["m"]})
+        out["roofline"] = {"kernel": "aggregate", "bound": "hbm", "achieved": agg_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                           "frac": agg_gbs / HBM_PEAK_GBS, "traffic": measured_traffic("aggregate", acfg["name"])}
+        if not args.no_cpu_baseline:
+            out["cpu_baseline"] = cpu_baseline_aggregation(acfg)
+        actx.close()
+        print(json.dumps(out))
+        return
+    actx.close()
+    del actx, versions
+    torch.cuda.empty_cache()
+
+    # ---- the training workload: whole cycles ----
+    cfg, ctx, data = build_training(c)
+    steps = args.steps if args.steps else {1: 200, 2: 100, 3: 10, 5: 5}[c]
+    warmup = args.warmup if args.warmup is not None else {1: 20, 2: 10, 3: 2, 5: 1}[c]
+    samples_per_cycle = int(cfg["batch"] * ctx.steps().sum())
+    def cycle(i):
+        ctx.local_steps()
+        ctx.select(i)
+        ctx.aggregate(resync=True)
+    t_cycle = time_cycles(cycle, steps, warmup)
+    t_local = time_cycles(lambda i: ctx.local_steps(), max(2, steps // 2), 1)
+
+    # per-kernel durations from HIP events on the library's stream, a separate pass over the same cycles
+    ctx.profile(True)
+    n_prof = max(2, min(steps, 10))
+    for i in range(n_prof):
+        cycle(10000 + i)
+    prof = ctx.profile_read()
+    ctx.profile(False)
+    total_ms = sum(v["ms"] for v in prof.values())
+    dom = max(prof, key=lambda n: prof[n]["ms"])
+    kd = prof[dom]
+    avg_ms = kd["ms"] / kd["launches"]
+    dtype = "bf16" if cfg["bf16"] else "f32"
+    if dom in GEMM_KERNELS:
+        ach = kd["flops"] / kd["launches"] / (avg_ms * 1e-3) / 1e12
+        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
+                "frac": ach / MFMA_PEAK_TFLOPS[dtype], "traffic": None}
+    else:
+        ach = kd["bytes"] / kd["launches"] / (avg_ms * 1e-3) / 1e9
+        roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": None}
+    roof["avg_launch_ms"] = avg_ms
+    roof["share_of_kernel_time"] = kd["ms"] / total_ms
+    gemm_flops = sum(v["flops"] for n, v in prof.items() if n in GEMM_KERNELS) / n_prof
+    out.update(metric="local-SGD samples/s over all replicas, whole aggregation cycles", value=samples_per_cycle / t_cycle,
+               unit="samples/s", steps=steps, warmup=warmup, ms_per_step=t_cycle * 1e3, dtype=dtype,
+               config={"workload": cfg["name"], "net": cfg["net"], "n_replicas": cfg["n_replicas"],
+                       "n_select": cfg["n_select"], "batch": cfg["batch"], "steps_per_replica": ctx.steps().tolist(),
+                       "samples_per_cycle": samples_per_cycle})
+    out["roofline"] = roof
+    out["local_steps"] = {"ms_per_cycle": t_local * 1e3, "samples/s": samples_per_cycle / t_local,
+                          "algorithmic_TFLOP_per_cycle": gemm_flops / 1e12,
+                          "mfma_utilisation": gemm_flops / t_local / 1e12 / MFMA_PEAK_TFLOPS[dtype]}
+    out["aggregation"] = aggregation
+    out["kernels"] = {n: {"launches_per_cycle": v["launches"] / n_prof, "ms_per_cycle": v["ms"] / n_prof}
+                      for n, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"])}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_training(c, data)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -161,8 +161,10 @@ HADFL_API hadfl_status hadfl_get_losses(hadfl_ctx *ctx, float *loss /* [n_replic
 
 /* Per-kernel timing with HIP events on the context's stream.  While enabled, every kernel launch is bracketed
  * by events (this serialises nothing but adds overhead: use a separate pass from throughput timing).
- * hadfl_profile_read synchronises, then writes up to cap rows: name (<= 47 chars), launches, total ms. */
-typedef struct { char name[48]; int64_t launches; double total_ms; } hadfl_kernel_time;
+ * hadfl_profile_read synchronises, then writes up to cap rows: name (<= 47 chars), launches, total ms, and the
+ * algorithmic work of those launches: flops (2 per multiply-add of the layer's definition; 0 for memory-bound
+ * kernels) and bytes (each operand and result counted once per launch). */
+typedef struct { char name[48]; int64_t launches; double total_ms; double flops; double bytes; } hadfl_kernel_time;
 HADFL_API hadfl_status hadfl_profile_enable(hadfl_ctx *ctx, int32_t on);
 HADFL_API hadfl_status hadfl_profile_read(hadfl_ctx *ctx, hadfl_kernel_time *out, int32_t cap, int32_t *n);
 

@@ -126,10 +126,10 @@ hipEvent_t Profiler::get()
     if (hipEventCreate(&e) != hipSuccess) return nullptr;
     return e;
 }
-void Profiler::begin(const char* name, hipStream_t s)
+void Profiler::begin(const char* name, hipStream_t s, double flops, double bytes)
 {
     if (!on) return;
-    Rec r{name, get(), get()};
+    Rec r{name, get(), get(), flops, bytes};
     if (r.a) (void)hipEventRecord(r.a, s);
     recs.push_back(r);
 }
@@ -355,7 +355,7 @@ hadfl_status hadfl_select(hadfl_ctx* ctx, const int32_t* versions_dev, const uin
     a.seed = ctx->cfg.seed; a.cycle = cycle;
     a.selected = ctx->selected; a.sel_sorted = ctx->sel_sorted; a.sel_weight = ctx->sel_weight;
     a.flag = ctx->flag; a.weights = ctx->weights; a.f = ctx->f;
-    ctx->prof.begin("select", ctx->stream);
+    ctx->prof.begin("select", ctx->stream, 0.0, 13.0 * N);
     hipError_t e = launch_select(a, ctx->stream);
     ctx->prof.end(ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "select kernel");
@@ -367,7 +367,9 @@ hadfl_status hadfl_aggregate(hadfl_ctx* ctx, int32_t resync)
 {
     if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
     if (!ctx->have_selection) return fail(ctx, HADFL_ESTATE, "hadfl_aggregate needs a preceding hadfl_select");
-    ctx->prof.begin(resync ? "aggregate_bcast" : "aggregate", ctx->stream);
+    // algorithmic traffic: n_select rows read, the aggregate written (+ every replica row written when broadcasting)
+    const double agg_bytes = 4.0 * (double)ctx->plan.m_total * (ctx->cfg.n_select + 1 + (resync ? ctx->cfg.n_replicas : 0));
+    ctx->prof.begin(resync ? "aggregate_bcast" : "aggregate", ctx->stream, 0.0, agg_bytes);
     hipError_t e = launch_aggregate(ctx->replicas, ctx->plan.row_stride, ctx->plan.row_stride, ctx->sel_sorted,
                                     ctx->sel_weight, ctx->cfg.n_select, ctx->agg, resync ? ctx->cfg.n_replicas : 0,
                                     ctx->replicas, ctx->stream);
@@ -457,6 +459,8 @@ hadfl_status hadfl_profile_read(hadfl_ctx* ctx, hadfl_kernel_time* out, int32_t 
         }
         rows[i].launches += 1;
         rows[i].total_ms += ms;
+        rows[i].flops += r.flops;
+        rows[i].bytes += r.bytes;
     }
     if (out) for (int32_t i = 0; i < cap && i < (int32_t)rows.size(); ++i) out[i] = rows[i];
     *n = (int32_t)rows.size();

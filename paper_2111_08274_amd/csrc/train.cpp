@@ -127,13 +127,20 @@ struct Runner {
     float* grad(int t) const { return e.buf.work + e.grad_off[t]; }
     float* shared() const { return e.buf.work + e.shared_off; }
 
-    template <typename F> void run(const char* name, F&& f)
+    // flops / bytes: algorithmic work of the launch for all active replicas (reported by the profiler)
+    template <typename F> void run(const char* name, double flops, double bytes, F&& f)
     {
         if (rc != hipSuccess) return;
-        if (prof) prof->begin(name, s);
+        if (prof) prof->begin(name, s, flops * na, bytes * na);
         rc = f();
         if (prof) prof->end(s);
         if (rc != hipSuccess) failed = name;
+    }
+
+    static double gemm_flops(const GemmParams& p) { return 2.0 * p.B * p.Ho * p.Wo * p.R * p.S * (double)p.Cin * p.Cout; }
+    static double gemm_bytes(const GemmParams& p)
+    {
+        return 4.0 * ((double)p.B * p.H * p.W * p.Cin + (double)p.R * p.S * p.Cin * p.Cout + (double)p.B * p.Ho * p.Wo * p.Cout);
     }
 
     GemmParams gemm_base(const Layer& l) const
@@ -177,18 +184,18 @@ struct Runner {
             p.a = act(l.in0); p.a_rep = e.rep_block;
             p.cursor = l.in0 == 0 ? e.buf.cursor : nullptr;
             p.out = actw(l.out); p.out_rep = e.rep_block;
-            run(l.type == HADFL_OP_CONV ? "conv_fwd" : "dense_fwd", [&] { return launch_gemm(p, na, s); });
+            run(l.type == HADFL_OP_CONV ? "conv_fwd" : "dense_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_gemm(p, na, s); });
             break; }
-        case HADFL_OP_RELU: run("relu_fwd", [&] { return launch_relu_fwd(q, na, s); }); break;
-        case HADFL_OP_MAXPOOL: run("maxpool_fwd", [&] { return launch_maxpool_fwd(q, na, s); }); break;
+        case HADFL_OP_RELU: run("relu_fwd", 0, 8.0 * q.count, [&] { return launch_relu_fwd(q, na, s); }); break;
+        case HADFL_OP_MAXPOOL: run("maxpool_fwd", 0, 4.0 * (B * a.numel() + q.count), [&] { return launch_maxpool_fwd(q, na, s); }); break;
         case HADFL_OP_ADD:
             q.in2 = act(l.in1); q.in2_rep = e.rep_block;
-            run("add_fwd", [&] { return launch_add_fwd(q, na, s); });
+            run("add_fwd", 0, 12.0 * q.count, [&] { return launch_add_fwd(q, na, s); });
             break;
-        case HADFL_OP_GAP: run("gap_fwd", [&] { return launch_gap_fwd(q, na, s); }); break;
+        case HADFL_OP_GAP: run("gap_fwd", 0, 4.0 * (B * a.numel() + q.count), [&] { return launch_gap_fwd(q, na, s); }); break;
         case HADFL_OP_BN: {
             BnParams b = bn_params(i);
-            run("bn_fwd", [&] { return launch_bn_fwd(b, na, s); });
+            run("bn_fwd", 0, 8.0 * B * a.numel(), [&] { return launch_bn_fwd(b, na, s); });
             break; }
         }
     }
@@ -243,9 +250,9 @@ struct Runner {
             } else {
                 p.out = e.buf.grad + l.w_off; p.out_rep = e.plan.row_stride;
             }
-            run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", [&] { return launch_gemm(p, na, s); });
+            run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return launch_gemm(p, na, s); });
             if (p.splits > 1)
-                run("splitk_reduce", [&] { return launch_splitk_reduce(shared(), p.out_split, p.splits, e.buf.grad + l.w_off,
+                run("splitk_reduce", 0, 4.0 * mn * (p.splits + 1), [&] { return launch_splitk_reduce(shared(), p.out_split, p.splits, e.buf.grad + l.w_off,
                                                                        e.plan.row_stride, mn, e.buf.order, na, s); });
             if (need_din) {
                 GemmParams d = gemm_base(l);
@@ -254,38 +261,38 @@ struct Runner {
                 d.a = grad(l.out); d.a_rep = e.rep_block;
                 d.out = grad(l.in0); d.out_rep = e.rep_block;
                 d.accumulate = acc0;
-                run(l.type == HADFL_OP_CONV ? "conv_dgrad" : "dense_dgrad", [&] { return launch_gemm(d, na, s); });
+                run(l.type == HADFL_OP_CONV ? "conv_dgrad" : "dense_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return launch_gemm(d, na, s); });
             }
             break; }
         case HADFL_OP_RELU:
             q.in = act(l.in0); q.in_rep = e.rep_block; q.in2 = grad(l.out); q.in2_rep = e.rep_block;
             q.count = B * a.numel();
-            run("relu_bwd", [&] { return launch_relu_bwd(q, na, s); });
+            run("relu_bwd", 0, 12.0 * q.count, [&] { return launch_relu_bwd(q, na, s); });
             break;
         case HADFL_OP_MAXPOOL:
             q.in = act(l.in0); q.in_rep = e.rep_block; q.in2 = grad(l.out); q.in2_rep = e.rep_block;
             q.count = B * r.numel();
-            run("maxpool_bwd", [&] { return launch_maxpool_bwd(q, na, s); });
+            run("maxpool_bwd", 0, 4.0 * (2 * B * a.numel() + q.count), [&] { return launch_maxpool_bwd(q, na, s); });
             break;
         case HADFL_OP_ADD: {
             q.in = grad(l.out); q.in_rep = e.rep_block; q.count = B * a.numel();
-            run("add_bwd", [&] { return launch_pass_grad(q, na, s); });
+            run("add_bwd", 0, 8.0 * q.count, [&] { return launch_pass_grad(q, na, s); });
             EwParams q2 = q;
             if (l.in1 == l.in0) q2.accumulate = 1; else q2.accumulate = e.grad_written[l.in1] ? 1 : 0;
             q2.out = grad(l.in1);
-            run("add_bwd", [&] { return launch_pass_grad(q2, na, s); });
+            run("add_bwd", 0, 8.0 * q.count, [&] { return launch_pass_grad(q2, na, s); });
             e.grad_written[l.in1] = 1;
             break; }
         case HADFL_OP_GAP:
             q.in = grad(l.out); q.in_rep = e.rep_block; q.count = B * a.numel();
-            run("gap_bwd", [&] { return launch_gap_bwd(q, na, s); });
+            run("gap_bwd", 0, 4.0 * (q.count + B * a.c), [&] { return launch_gap_bwd(q, na, s); });
             break;
         case HADFL_OP_BN: {
             BnParams b = bn_params(i);
             b.dy = grad(l.out); b.dy_rep = e.rep_block;
             b.y = grad(l.in0); b.y_rep = e.rep_block;
             b.accumulate = acc0;
-            run("bn_bwd", [&] { return launch_bn_bwd(b, na, s); });
+            run("bn_bwd", 0, 12.0 * B * a.numel(), [&] { return launch_bn_bwd(b, na, s); });
             break; }
         }
         if (need_din) e.grad_written[l.in0] = 1;
@@ -298,7 +305,7 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
 {
     Runner r{*e, s, (prof && prof->on) ? prof : nullptr};
     const int N = e->cfg.n_replicas;
-    r.run("zero_versions", [&] { return launch_fill_u32((uint32_t*)e->buf.versions, 0u, N, s); });
+    r.run("zero_versions", 0, 0, [&] { return launch_fill_u32((uint32_t*)e->buf.versions, 0u, N, s); });
     const int T = (int)e->plan.tensors.size();
     for (int step = 0; step < e->e_max && r.rc == hipSuccess; ++step) {
         r.na = e->n_active[step];
@@ -308,7 +315,7 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
         lp.dlogits = r.grad(T - 1); lp.dlogits_rep = e->rep_block;
         lp.y = e->buf.y; lp.cursor = e->buf.cursor; lp.n_samples = e->cfg.n_samples; lp.batch = e->cfg.batch;
         lp.n_classes = e->cfg.n_classes; lp.loss = e->buf.loss; lp.order = e->buf.order;
-        r.run("softmax_ce", [&] { return launch_softmax_ce(lp, r.na, s); });
+        r.run("softmax_ce", 0, 8.0 * e->cfg.batch * e->cfg.n_classes, [&] { return launch_softmax_ce(lp, r.na, s); });
         e->grad_written.assign(T, 0);
         e->grad_written[T - 1] = 1;
         for (size_t i = e->plan.layers.size(); i-- > 0;) r.backward_layer(i);
@@ -316,7 +323,7 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
         sp.w = e->buf.replicas; sp.g = e->buf.grad; sp.buf = e->buf.mom; sp.row_stride = e->plan.row_stride;
         sp.count = e->plan.train_end; sp.lr = e->cfg.lr; sp.momentum = e->cfg.momentum;
         sp.cursor = e->buf.cursor; sp.versions = e->buf.versions; sp.order = e->buf.order;
-        r.run("sgd", [&] { return launch_sgd(sp, r.na, s); });
+        r.run("sgd", 0, (e->buf.mom ? 20.0 : 12.0) * e->plan.m_train, [&] { return launch_sgd(sp, r.na, s); });
     }
     if (r.rc != hipSuccess) {
         err = std::string("kernel launch failed in ") + (r.failed ? r.failed : "?") + ": " + hipGetErrorString(r.rc);

@@ -32,12 +32,12 @@ void train_destroy(TrainEngine* e);
 
 // Event-pair profiler used by hadfl_profile_*.
 struct Profiler {
-    struct Rec { std::string name; hipEvent_t a, b; };
+    struct Rec { std::string name; hipEvent_t a, b; double flops, bytes; };
     bool on = false;
     std::vector<Rec> recs;
     std::vector<hipEvent_t> pool;
     hipEvent_t get();
-    void begin(const char* name, hipStream_t s);
+    void begin(const char* name, hipStream_t s, double flops = 0.0, double bytes = 0.0);
     void end(hipStream_t s);
     void clear();
     ~Profiler();

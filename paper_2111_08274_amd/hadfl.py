@@ -36,7 +36,8 @@ class HadflTensorInfo(ctypes.Structure):
 
 
 class HadflKernelTime(ctypes.Structure):
-    _fields_ = [("name", ctypes.c_char * 48), ("launches", ctypes.c_int64), ("total_ms", ctypes.c_double)]
+    _fields_ = [("name", ctypes.c_char * 48), ("launches", ctypes.c_int64), ("total_ms", ctypes.c_double),
+                ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
 EXPORTS = ("hadfl_param_count", "hadfl_param_layout", "hadfl_workspace_bytes", "hadfl_init_replicas",
@@ -231,4 +232,5 @@ class Context:
         n = ctypes.c_int32()
         rows = (HadflKernelTime * 256)()
         _check(lib().hadfl_profile_read(self.h, rows, 256, ctypes.byref(n)), self.h)
-        return {rows[i].name.decode(): (rows[i].launches, rows[i].total_ms) for i in range(min(n.value, 256))}
+        return {rows[i].name.decode(): dict(launches=rows[i].launches, ms=rows[i].total_ms, flops=rows[i].flops,
+                                            bytes=rows[i].bytes) for i in range(min(n.value, 256))}
