@@ -160,7 +160,8 @@ HADFL_API hadfl_status hadfl_get_params(hadfl_ctx *ctx, int32_t replica, float *
 HADFL_API hadfl_status hadfl_get_losses(hadfl_ctx *ctx, float *loss /* [n_replicas] batch-mean loss of each replica's last step */);
 
 /* Per-kernel timing with HIP events on the context's stream.  While enabled, every kernel launch is bracketed
- * by events (this serialises nothing but adds overhead: use a separate pass from throughput timing).
+ * by events (this serialises nothing but adds overhead: use a separate pass from throughput timing).  on = 2
+ * additionally tags every name with the layer index and the number of active replicas ("conv_fwd:L12:n16").
  * hadfl_profile_read synchronises, then writes up to cap rows: name (<= 47 chars), launches, total ms, and the
  * algorithmic work of those launches: flops (2 per multiply-add of the layer's definition; 0 for memory-bound
  * kernels) and bytes (each operand and result counted once per launch). */

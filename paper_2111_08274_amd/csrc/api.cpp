@@ -439,6 +439,7 @@ hadfl_status hadfl_profile_enable(hadfl_ctx* ctx, int32_t on)
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     ctx->prof.clear();
     ctx->prof.on = on != 0;
+    ctx->prof.detail = on == 2;
     return HADFL_OK;
 }
 

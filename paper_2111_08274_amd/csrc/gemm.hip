@@ -37,8 +37,7 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
     const int tile_m = blockIdx.x / p.tiles_n, tile_n = blockIdx.x % p.tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int split = blockIdx.y;
-    const int kbeg = split * p.kchunk;
-    const int kend = min(p.K, kbeg + p.kchunk);
+    const int kbeg = (MODE == kDgrad) ? 0 : split * p.kchunk;
 
     // activation-side base for this replica (the data set is indexed through the batch cursor)
     const float* abase;
@@ -50,6 +49,21 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
     }
     const float* wbase = p.w + (long long)rep * p.w_rep;
 
+    // kDgrad: an input pixel (y, x) only receives taps with r = (y + pad) mod stride (likewise s), so the pixels are
+    // split into stride*stride classes by (y mod stride, x mod stride); a class is a dense GEMM over its own tap list
+    // and no multiply-add is spent on taps that never contribute.  blockIdx.y is the class (1 class for stride 1).
+    int d_ph = 0, d_pw = 0, d_r0 = 0, d_s0 = 0, d_ns = p.S, d_hc = p.H, d_wc = p.W, d_m = p.M;
+    int kend = min(p.K, kbeg + p.kchunk);
+    if (MODE == kDgrad) {
+        d_ph = blockIdx.y / p.stride; d_pw = blockIdx.y % p.stride;
+        d_hc = (p.H - d_ph + p.stride - 1) / p.stride; d_wc = (p.W - d_pw + p.stride - 1) / p.stride;
+        d_r0 = (d_ph + p.pad) % p.stride; d_s0 = (d_pw + p.pad) % p.stride;
+        const int nr = d_r0 < p.R ? (p.R - d_r0 + p.stride - 1) / p.stride : 0;
+        d_ns = d_s0 < p.S ? (p.S - d_s0 + p.stride - 1) / p.stride : 0;
+        d_m = p.B * d_hc * d_wc;
+        kend = nr * d_ns * p.Cout;
+        if (m0 >= d_m) return;
+    }
     // ---------------- per-thread, loop-invariant parts of the operand addresses ----------------
     // kFwd / kDgrad: A is read along K for one fixed row m.
     int a_m = 0, a_b = 0, a_y = 0, a_x = 0; bool a_ok = false;
@@ -62,12 +76,13 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
         wa_r = tap / p.S; wa_s = tap - wa_r * p.S;
     } else {
         a_m = m0 + (tid % BM);
-        a_ok = a_m < p.M;
-        const int hw = (MODE == kFwd) ? p.Ho * p.Wo : p.H * p.W;
-        const int ww = (MODE == kFwd) ? p.Wo : p.W;
+        a_ok = a_m < ((MODE == kFwd) ? p.M : d_m);
+        const int hw = (MODE == kFwd) ? p.Ho * p.Wo : d_hc * d_wc;
+        const int ww = (MODE == kFwd) ? p.Wo : d_wc;
         a_b = a_m / hw;
         const int rem = a_m - a_b * hw;
         a_y = rem / ww; a_x = rem - a_y * ww;
+        if (MODE == kDgrad) { a_y = a_y * p.stride + d_ph; a_x = a_x * p.stride + d_pw; }
     }
     const bool fastA = (MODE == kFwd) ? (p.Cin % BK == 0) : (MODE == kDgrad) ? (p.Cout % BK == 0) : (p.Cin % 4 == 0);
     const bool vecN = (p.N % 4 == 0);
@@ -114,10 +129,10 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
                     const int kq = i / BM;
                     if (fastA) {
                         const int tap = k0 / p.Cout, c0 = k0 - tap * p.Cout;
-                        const int r = tap / p.S, s = tap - r * p.S;
-                        const int ty = a_y + p.pad - r, tx = a_x + p.pad - s;
-                        const int yo = ty / p.stride, xo = tx / p.stride;
-                        if (a_ok && ty >= 0 && tx >= 0 && yo * p.stride == ty && xo * p.stride == tx && yo < p.Ho && xo < p.Wo)
+                        const int ir = tap / d_ns, is = tap - ir * d_ns;
+                        const int ty = a_y + p.pad - (d_r0 + ir * p.stride), tx = a_x + p.pad - (d_s0 + is * p.stride);
+                        const int yo = ty / p.stride, xo = tx / p.stride;      // exact: the class fixes the residue
+                        if (a_ok && ty >= 0 && tx >= 0 && yo < p.Ho && xo < p.Wo)
                             v = ld4(abase + (((long long)a_b * p.Ho + yo) * p.Wo + xo) * p.Cout + c0 + kq * 4);
                     } else {
 #pragma unroll
@@ -125,10 +140,10 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
                             const int k = k0 + kq * 4 + j;
                             if (a_ok && k < kend) {
                                 const int tap = k / p.Cout, c = k - tap * p.Cout;
-                                const int r = tap / p.S, s = tap - r * p.S;
-                                const int ty = a_y + p.pad - r, tx = a_x + p.pad - s;
+                                const int ir = tap / d_ns, is = tap - ir * d_ns;
+                                const int ty = a_y + p.pad - (d_r0 + ir * p.stride), tx = a_x + p.pad - (d_s0 + is * p.stride);
                                 const int yo = ty / p.stride, xo = tx / p.stride;
-                                if (ty >= 0 && tx >= 0 && yo * p.stride == ty && xo * p.stride == tx && yo < p.Ho && xo < p.Wo)
+                                if (ty >= 0 && tx >= 0 && yo < p.Ho && xo < p.Wo)
                                     v[j] = abase[(((long long)a_b * p.Ho + yo) * p.Wo + xo) * p.Cout + c];
                             }
                         }
@@ -195,14 +210,18 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
                     const int n = n0 + i % BN, kq = i / BN;
                     if (n < p.N) {
                         if (fastB) {
-                            const int tap = k0 / p.Cout, c0 = k0 - tap * p.Cout;
+                            const int t = k0 / p.Cout, c0 = k0 - t * p.Cout;
+                            const int ir = t / d_ns, is = t - ir * d_ns;
+                            const int tap = (d_r0 + ir * p.stride) * p.S + d_s0 + is * p.stride;
                             v = ld4(wbase + ((long long)tap * p.Cin + n) * p.Cout + c0 + kq * 4);
                         } else {
 #pragma unroll
                             for (int j = 0; j < 4; ++j) {
                                 const int k = k0 + kq * 4 + j;
                                 if (k < kend) {
-                                    const int tap = k / p.Cout, c = k - tap * p.Cout;
+                                    const int t = k / p.Cout, c = k - t * p.Cout;
+                                    const int ir = t / d_ns, is = t - ir * d_ns;
+                                    const int tap = (d_r0 + ir * p.stride) * p.S + d_s0 + is * p.stride;
                                     v[j] = wbase[((long long)tap * p.Cin + n) * p.Cout + c];
                                 }
                             }
@@ -314,13 +333,21 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int m = m0 + (wm * TM + i) * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (m >= p.M) continue;
+                if (m >= ((MODE == kDgrad) ? d_m : p.M)) continue;
                 float r = acc[i][j][v];
-                float* dst = obase + (long long)m * p.N + n;
+                long long row = m;
+                if (MODE == kDgrad && p.stride > 1) {
+                    const int hw = d_hc * d_wc;
+                    const int b = m / hw, rem = m - b * hw;
+                    const int yy = rem / d_wc, xx = rem - yy * d_wc;
+                    row = ((long long)b * p.H + yy * p.stride + d_ph) * p.W + xx * p.stride + d_pw;
+                }
+                float* dst = obase + row * p.N + n;
                 if (MODE == kFwd) {
                     r += bv;
                     if (p.relu) r = fmaxf(r, 0.f);
                 } else if (MODE == kDgrad) {
+                    if (p.mask && !(p.mask[(long long)rep * p.mask_rep + row * p.N + n] > 0.f)) r = 0.f;
                     if (p.accumulate) r += *dst;
                 }
                 *dst = r;
@@ -329,17 +356,27 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
     }
 }
 
+// out[i] = sum over splits of partial[s][i].  A workgroup covers 32 outputs with 8 lanes each: lane j adds the splits
+// s = j, j+8, ... in ascending order, then the 8 partial sums are combined by a fixed butterfly (deterministic).
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, long long split_stride,
                                                             int splits, float* __restrict__ out, long long out_rep,
                                                             long long count, const int* __restrict__ order)
 {
+    __shared__ float red[8][32];
     const int g = blockIdx.y, rep = order[g];
     const float* src = partial + (long long)g * split_stride * splits;
     float* dst = out + (long long)rep * out_rep;
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < count; i += (long long)gridDim.x * 256) {
-        float s = src[i];
-        for (int k = 1; k < splits; ++k) s += src[(long long)k * split_stride + i];
-        dst[i] = s;
+    const int el = threadIdx.x & 31, sl = threadIdx.x >> 5;
+    for (long long i0 = (long long)blockIdx.x * 32; i0 < count; i0 += (long long)gridDim.x * 32) {
+        const long long i = i0 + el;
+        float s = 0.f;
+        if (i < count)
+            for (int k = sl; k < splits; k += 8) s += src[(long long)k * split_stride + i];
+        red[sl][el] = s;
+        __syncthreads();
+        if (sl == 0 && i < count)
+            dst[i] = ((red[0][el] + red[1][el]) + (red[2][el] + red[3][el])) + ((red[4][el] + red[5][el]) + (red[6][el] + red[7][el]));
+        __syncthreads();
     }
 }
 
@@ -349,7 +386,13 @@ hipError_t launch_tile(const GemmParams& p0, int n_active, hipStream_t s)
     GemmParams p = p0;
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = (p.N + BN - 1) / BN;
-    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)p.splits, (unsigned)n_active), block(64 * WM * WN);
+    unsigned gy = (unsigned)p.splits;
+    if (p.mode == kDgrad) {
+        gy = (unsigned)(p.stride * p.stride);
+        const int rows0 = p.B * ((p.H + p.stride - 1) / p.stride) * ((p.W + p.stride - 1) / p.stride);   // largest class
+        p.tiles_m = (rows0 + BM - 1) / BM;
+    }
+    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), gy, (unsigned)n_active), block(64 * WM * WN);
     switch (p.mode) {
     case kFwd: hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, kFwd>), grid, block, 0, s, p); break;
     case kDgrad: hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, kDgrad>), grid, block, 0, s, p); break;
@@ -376,8 +419,8 @@ hipError_t launch_splitk_reduce(const float* partial, long long split_stride, in
                                 long long count, const int* order, int n_active, hipStream_t s)
 {
     if (n_active < 1 || count < 1) return hipSuccess;
-    long long bx = (count + 255) / 256;
-    if (bx > 1024) bx = 1024;
+    long long bx = (count + 31) / 32;
+    if (bx > 4096) bx = 4096;
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)bx, (unsigned)n_active), dim3(256), 0, s, partial,
                        split_stride, splits, out, out_rep, count, order);
     return hipGetLastError();

@@ -27,7 +27,8 @@ __global__ __launch_bounds__(256) void relu_bwd_kernel(EwParams p)
     const float* dout = p.in2 + rep * p.in2_rep;
     float* din = p.out + rep * p.out_rep;
     for (long long i = gtid(); i < p.count; i += gstride()) {
-        const float g = x[i] > 0.f ? dout[i] : 0.f;
+        float g = x[i] > 0.f ? dout[i] : 0.f;
+        if (p.mask && !(p.mask[rep * p.mask_rep + i] > 0.f)) g = 0.f;
         din[i] = p.accumulate ? din[i] + g : g;
     }
 }
@@ -74,7 +75,8 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(EwParams p)
         const float g = dout[i];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float v = (j == arg) ? g : 0.f;
+            // with p.mask set, x is a fused ReLU output: the gradient passes only where it is positive
+            const float v = (j == arg && (!p.mask || m > 0.f)) ? g : 0.f;
             float* d = din + base + off[j];
             *d = p.accumulate ? *d + v : v;
         }
@@ -87,7 +89,10 @@ __global__ __launch_bounds__(256) void add_fwd_kernel(EwParams p)
     const float* a = p.in + rep * p.in_rep;
     const float* b = p.in2 + rep * p.in2_rep;
     float* out = p.out + rep * p.out_rep;
-    for (long long i = gtid(); i < p.count; i += gstride()) out[i] = a[i] + b[i];
+    for (long long i = gtid(); i < p.count; i += gstride()) {
+        const float v = a[i] + b[i];
+        out[i] = p.relu ? fmaxf(v, 0.f) : v;
+    }
 }
 
 __global__ __launch_bounds__(256) void pass_grad_kernel(EwParams p)
@@ -95,7 +100,11 @@ __global__ __launch_bounds__(256) void pass_grad_kernel(EwParams p)
     const int rep = p.order[blockIdx.y];
     const float* dout = p.in + rep * p.in_rep;
     float* din = p.out + rep * p.out_rep;
-    for (long long i = gtid(); i < p.count; i += gstride()) din[i] = p.accumulate ? din[i] + dout[i] : dout[i];
+    const float* mask = p.mask ? p.mask + rep * p.mask_rep : nullptr;
+    for (long long i = gtid(); i < p.count; i += gstride()) {
+        const float g = (!mask || mask[i] > 0.f) ? dout[i] : 0.f;
+        din[i] = p.accumulate ? din[i] + g : g;
+    }
 }
 
 // out[b][c] = mean over H*W; count = B*C
@@ -124,7 +133,8 @@ __global__ __launch_bounds__(256) void gap_bwd_kernel(EwParams p)
     for (long long i = gtid(); i < p.count; i += gstride()) {
         const int c = (int)(i % p.C);
         const long long b = i / ((long long)hw * p.C);
-        const float g = dout[b * p.C + c] / (float)hw;
+        float g = dout[b * p.C + c] / (float)hw;
+        if (p.mask && !(p.mask[rep * p.mask_rep + i] > 0.f)) g = 0.f;
         din[i] = p.accumulate ? din[i] + g : g;
     }
 }
@@ -208,7 +218,8 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_kernel(BnParams p)
     const int r0 = chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
     for (int r = r0 + rl; r < r1; r += 4) {
         const long long i = (long long)r * p.C + c;
-        y[i] = gamma * ((x[i] - mean) * istd) + beta;
+        const float v = gamma * ((x[i] - mean) * istd) + beta;
+        y[i] = p.relu ? fmaxf(v, 0.f) : v;
     }
 }
 
@@ -239,7 +250,8 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_kernel(BnParams p)
     for (int r = r0 + rl; r < r1; r += 4) {
         const long long i = (long long)r * p.C + c;
         const float xh = (x[i] - mean) * istd;
-        const float v = k1 * (dy[i] - db * inv_n - xh * dg * inv_n);
+        float v = k1 * (dy[i] - db * inv_n - xh * dg * inv_n);
+        if (p.mask && !(p.mask[rep * p.mask_rep + i] > 0.f)) v = 0.f;
         dx[i] = p.accumulate ? dx[i] + v : v;
     }
 }
@@ -292,6 +304,42 @@ __global__ __launch_bounds__(256) void sgd_kernel(SgdParams p)
     if (blockIdx.x == 0 && threadIdx.x == 0) { p.cursor[rep] += 1; p.versions[rep] += 1; }
 }
 
+// Narrow dense layer (the classifier: out <= 16): one workgroup per sample row; threads stride over the input
+// features, keep `out` partial sums each and combine them with a fixed butterfly and a fixed LDS order.  Too small
+// for the matrix cores.
+template <int NMAX>
+__global__ __launch_bounds__(256) void dense_small_fwd_kernel(DenseSmallParams p)
+{
+    __shared__ float red[4][NMAX];
+    const int rep = p.order[blockIdx.y];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = blockIdx.x;
+    const float* x = p.x + rep * p.x_rep + (long long)m * p.K;
+    const float* w = p.w + rep * p.w_rep;
+    float acc[NMAX];
+#pragma unroll
+    for (int n = 0; n < NMAX; ++n) acc[n] = 0.f;
+    for (int k = threadIdx.x; k < p.K; k += 256) {
+        const float xv = x[k];
+        const float* wr = w + (long long)k * p.N;
+#pragma unroll
+        for (int n = 0; n < NMAX; ++n) if (n < p.N) acc[n] += xv * wr[n];
+    }
+#pragma unroll
+    for (int n = 0; n < NMAX; ++n) {
+        float v = acc[n];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+        if (lane == 0) red[wave][n] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < p.N) {
+        const int n = threadIdx.x;
+        float* o = p.out + rep * p.out_rep + (long long)m * p.N;
+        o[n] = ((red[0][n] + red[1][n]) + (red[2][n] + red[3][n])) + (p.has_bias ? w[(long long)p.K * p.N + n] : 0.f);
+    }
+}
+
 dim3 ew_grid(long long count, int n_active)
 {
     long long b = (count + 255) / 256;
@@ -316,6 +364,13 @@ HADFL_EW_LAUNCH(launch_pass_grad, pass_grad_kernel)
 HADFL_EW_LAUNCH(launch_gap_fwd, gap_fwd_kernel)
 HADFL_EW_LAUNCH(launch_gap_bwd, gap_bwd_kernel)
 #undef HADFL_EW_LAUNCH
+
+hipError_t launch_dense_small_fwd(const DenseSmallParams& p, int n_active, hipStream_t s)
+{
+    if (n_active < 1 || p.rows < 1) return hipSuccess;
+    hipLaunchKernelGGL(dense_small_fwd_kernel<16>, dim3((unsigned)p.rows, (unsigned)n_active), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
 
 hipError_t launch_bn_fwd(const BnParams& p, int n_active, hipStream_t s)
 {

@@ -38,33 +38,53 @@ __device__ double exp_neg(double x)
     return p * __longlong_as_double(e << 52);
 }
 
+// value held by lane k of the wavefront (k is wave-uniform at every call site)
+__device__ __forceinline__ double lane_value(double v, int k)
+{
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), k);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), k);
+    return __hiloint2double(hi, lo);
+}
+
 __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
 {
     __shared__ double s_sorted[kMaxReplicas];
     __shared__ double s_f[kMaxReplicas];
     __shared__ unsigned char s_flag[kMaxReplicas];
-    __shared__ int s_navail;
+    __shared__ int s_v[kMaxReplicas];
+    __shared__ unsigned char s_av[kMaxReplicas];
     const int lane = threadIdx.x, N = a.n;
 
-    // versions of the available replicas, sorted ascending by rank counting
-    if (lane == 0) {
-        int c = 0;
-        for (int k = 0; k < N; ++k) c += (!a.avail || a.avail[k]) ? 1 : 0;
-        s_navail = c;
+    // versions and availability into LDS (one parallel load), then a rank-counting sort of the available versions:
+    // rank(i) = #{available j : v_j < v_i or (v_j == v_i and j < i)}.  Lanes own elements i = 64q + lane and walk all j
+    // chunk by chunk with cross-lane reads, so no step waits on memory.
+    const int chunks = (N + 63) / 64;
+    for (int i = lane; i < N; i += 64) {
+        s_v[i] = a.versions[i];
+        s_av[i] = (!a.avail || a.avail[i]) ? 1 : 0;
+        s_flag[i] = 0;
     }
     __syncthreads();
-    const int na = s_navail;
-    for (int i = lane; i < N; i += 64) {
-        s_flag[i] = 0;
-        if (a.avail && !a.avail[i]) continue;
-        const int vi = a.versions[i];
+    int na = 0;
+    for (int q = 0; q < chunks; ++q) {
+        const int i = q * 64 + lane;
+        const int vi = i < N ? s_v[i] : 0;
         int rank = 0;
-        for (int j = 0; j < N; ++j) {
-            if (a.avail && !a.avail[j]) continue;
-            const int vj = a.versions[j];
-            rank += (vj < vi || (vj == vi && j < i)) ? 1 : 0;
+        na = 0;
+        for (int c = 0; c < chunks; ++c) {
+            const int idx = c * 64 + lane;
+            const int vjm = idx < N ? s_v[idx] : 0;
+            const unsigned long long mask = __ballot(idx < N && s_av[idx]);
+            na += __popcll(mask);
+#pragma unroll
+            for (int k = 0; k < 64; ++k) {
+                const int vj = __builtin_amdgcn_readlane(vjm, k);
+                const int j = c * 64 + k;
+                const bool bj = (mask >> k) & 1ull;
+                rank += (bj && (vj < vi || (vj == vi && j < i))) ? 1 : 0;
+            }
         }
-        s_sorted[rank] = (double)vi;
+        if (i < N && s_av[i]) s_sorted[rank] = (double)vi;
     }
     __syncthreads();
     // third quartile: linear interpolation at 0.75*(na-1)
@@ -73,11 +93,12 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
     const double frac = pos - (double)lo;
     double mu = s_sorted[lo];
     if (lo + 1 < na) mu = s_sorted[lo] + frac * (s_sorted[lo + 1] - s_sorted[lo]);
+    __syncthreads();                                       // every lane has read the quartile before s_sorted is reused
 
     for (int i = lane; i < N; i += 64) {
         double f = 0.0;
-        if (!a.avail || a.avail[i]) {
-            const double d = (double)a.versions[i] - mu;
+        if (s_av[i]) {
+            const double d = (double)s_v[i] - mu;
             double e = -(d * d) * 0.5;
             if (e < -690.0) e = -690.0;
             f = exp_neg(e);
@@ -87,27 +108,47 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
     }
     __syncthreads();
 
-    if (lane == 0) {
-        for (int t = 0; t < a.n_select; ++t) {
-            double S = 0.0;
-            int last = -1;
-            for (int k = 0; k < N; ++k)
-                if (!s_flag[k] && s_f[k] > 0.0) { S += s_f[k]; last = k; }
-            const U4 o = philox4x32_10(U4{(uint32_t)a.cycle, (uint32_t)(a.cycle >> 32), (uint32_t)t, 0u},
-                                       (uint32_t)a.seed, (uint32_t)(a.seed >> 32));
-            const unsigned long long bits = ((unsigned long long)o.y << 32) | o.x;
-            const double u = (double)(bits >> 11) * 0x1.0p-53;
-            const double thr = u * S;
-            double run = 0.0;
-            int pick = last;
-            for (int k = 0; k < N; ++k) {
-                if (s_flag[k] || !(s_f[k] > 0.0)) continue;
-                run += s_f[k];
-                if (run > thr) { pick = k; break; }
+    // Sequential draws.  The running sum must add f in ascending replica index, one value after another.  The
+    // wavefront walks the replicas in chunks of 64: every lane loads its own value once (one LDS latency per chunk),
+    // then all lanes step through the chunk together with cross-lane reads, and lane k keeps the running sum after
+    // element k.  The total S is the last running sum; the pick is the first live element whose running sum exceeds
+    // u*S, found with one compare and a ballot.  Dead elements add +0.0, which leaves a non-negative sum unchanged.
+    for (int t = 0; t < a.n_select; ++t) {
+        double run = 0.0;
+        for (int c = 0; c < chunks; ++c) {
+            const int idx = c * 64 + lane;
+            const bool live = idx < N && !s_flag[idx] && s_f[idx] > 0.0;
+            const double mine = live ? s_f[idx] : 0.0;
+            const int lim = min(64, N - c * 64);
+            double prefix = 0.0;
+            for (int k = 0; k < lim; ++k) {
+                run = run + lane_value(mine, k);
+                prefix = (lane == k) ? run : prefix;
             }
-            a.selected[t] = pick;
-            s_flag[pick] = 1;
+            if (idx < N) s_sorted[idx] = prefix;          // s_sorted is free after the quartile: reuse as prefix store
         }
+        const double S = run;
+        const U4 o = philox4x32_10(U4{(uint32_t)a.cycle, (uint32_t)(a.cycle >> 32), (uint32_t)t, 0u},
+                                   (uint32_t)a.seed, (uint32_t)(a.seed >> 32));
+        const unsigned long long bits = ((unsigned long long)o.y << 32) | o.x;
+        const double u = (double)(bits >> 11) * 0x1.0p-53;
+        const double thr = u * S;
+        int pick = -1, last = -1;
+        for (int c = 0; c < chunks; ++c) {
+            const int idx = c * 64 + lane;
+            const bool live = idx < N && !s_flag[idx] && s_f[idx] > 0.0;
+            const unsigned long long lm = __ballot(live);
+            const unsigned long long hit = __ballot(live && s_sorted[idx < N ? idx : 0] > thr);
+            if (lm) last = c * 64 + 63 - __clzll(lm);
+            if (pick < 0 && hit) pick = c * 64 + __ffsll((long long)hit) - 1;
+        }
+        if (pick < 0) pick = last;
+        __syncthreads();
+        if (lane == 0) { a.selected[t] = pick; s_flag[pick] = 1; }
+        __syncthreads();
+    }
+
+    if (lane == 0) {
         // aggregation weights a_k and the ascending list the aggregate kernel walks
         double denom = 0.0;
         for (int k = 0; k < N; ++k)

@@ -2,6 +2,7 @@
 // over the replicas that still have steps left (a prefix of the replicas ordered by step count, kept in device
 // memory).  There is no host loop over replicas and no host read-back inside a cycle.
 #include <algorithm>
+#include <cstdio>
 
 #include "train.h"
 #include "kernels.h"
@@ -26,6 +27,14 @@ public:
     std::vector<int> splits;              // per layer: split-K factor of the weight gradient
     std::vector<int> bn_chunks;           // per layer
     std::vector<char> grad_written;       // scratch for the backward pass
+    // ReLU fusion: a ReLU that is the only consumer of a conv / dense / BN / add output is folded into that layer's
+    // store (the layer writes the ReLU's output tensor; the ReLU layer itself issues nothing).  Its backward is folded
+    // into whoever writes the gradient of that tensor: those kernels zero the gradient where the stored output is not
+    // positive, so the tensor's gradient buffer holds the gradient before the ReLU.
+    std::vector<int> out_tensor;          // per layer: tensor the layer writes (its own, or the fused ReLU's)
+    std::vector<char> skip;               // per layer: fused away
+    std::vector<char> fused_relu;         // per layer: applies max(., 0) in its store
+    std::vector<char> masked;             // per tensor: gradient writers must apply the (value > 0) mask
 };
 
 namespace {
@@ -67,9 +76,9 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
             const int64_t K = B * r.h * r.w;
             const int64_t M = (l.type == HADFL_OP_CONV ? (int64_t)l.k * l.k * a.c : a.numel()) + (l.bias ? 1 : 0);
             const int64_t tiles = ((M + 127) / 128) * ((l.cout + 127) / 128);
-            int64_t want = (1024 + tiles * cfg.n_replicas - 1) / (tiles * cfg.n_replicas);
-            int64_t maxs = std::max<int64_t>(1, K / 64);
-            int s = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, maxs), 64));
+            int64_t want = (2048 + tiles * cfg.n_replicas - 1) / (tiles * cfg.n_replicas);
+            int64_t maxs = std::max<int64_t>(1, K / 128);
+            int s = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, maxs), 256));
             L.splits[i] = s;
             if (s > 1) shared = std::max<int64_t>(shared, (int64_t)cfg.n_replicas * s * up64(M * l.cout));
         }
@@ -106,6 +115,21 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
     e->rep_block = L.rep_block;
     e->shared_off = L.rep_block * cfg.n_replicas;
     e->shared_floats = L.shared_floats;
+    {
+        const int nl = (int)plan.layers.size(), T = (int)plan.tensors.size();
+        e->out_tensor.resize(nl); e->skip.assign(nl, 0); e->fused_relu.assign(nl, 0); e->masked.assign(T, 0);
+        std::vector<int> consumers(T, 0);
+        for (const Layer& l : plan.layers) { consumers[l.in0]++; if (l.type == HADFL_OP_ADD) consumers[l.in1]++; }
+        for (int i = 0; i < nl; ++i) e->out_tensor[i] = plan.layers[i].out;
+        for (int j = 0; j < nl; ++j) {
+            const Layer& r = plan.layers[j];
+            if (r.type != HADFL_OP_RELU || r.in0 < 1 || consumers[r.in0] != 1 || r.out == T - 1) continue;
+            const int i = r.in0 - 1;                       // layer i writes tensor i + 1
+            const int pt = plan.layers[i].type;
+            if (pt != HADFL_OP_CONV && pt != HADFL_OP_DENSE && pt != HADFL_OP_BN && pt != HADFL_OP_ADD) continue;
+            e->out_tensor[i] = r.out; e->fused_relu[i] = 1; e->skip[j] = 1; e->masked[r.out] = 1;
+        }
+    }
     *out = e;
     return HADFL_OK;
 }
@@ -119,6 +143,7 @@ struct Runner {
     hipStream_t s;
     Profiler* prof;
     int na = 0;
+    int cur_layer = -1;
     hipError_t rc = hipSuccess;
     const char* failed = nullptr;
 
@@ -131,7 +156,15 @@ struct Runner {
     template <typename F> void run(const char* name, double flops, double bytes, F&& f)
     {
         if (rc != hipSuccess) return;
-        if (prof) prof->begin(name, s, flops * na, bytes * na);
+        if (prof) {
+            if (prof->detail) {
+                char tag[64];
+                std::snprintf(tag, sizeof(tag), "%s:L%d:n%d", name, cur_layer, na);
+                prof->begin(tag, s, flops * na, bytes * na);
+            } else {
+                prof->begin(name, s, flops * na, bytes * na);
+            }
+        }
         rc = f();
         if (prof) prof->end(s);
         if (rc != hipSuccess) failed = name;
@@ -167,13 +200,17 @@ struct Runner {
 
     void forward_layer(size_t i)
     {
+        cur_layer = (int)i;
+        if (e.skip[i]) return;
         const Layer& l = e.plan.layers[i];
         const TensorShape a = e.plan.tensors[l.in0], r = e.plan.tensors[l.out];
         const int64_t B = e.cfg.batch;
+        const int ot = e.out_tensor[i];
         EwParams q{};
         q.order = e.buf.order; q.B = (int)B; q.H = a.h; q.W = a.w; q.C = a.c;
         q.in = act(l.in0); q.in_rep = e.rep_block;
-        q.out = actw(l.out); q.out_rep = e.rep_block;
+        q.out = actw(ot); q.out_rep = e.rep_block;
+        q.relu = e.fused_relu[i];
         q.count = B * r.numel();
         switch (l.type) {
         case HADFL_OP_CONV:
@@ -183,7 +220,16 @@ struct Runner {
             p.M = (int)(B * p.Ho * p.Wo); p.N = p.Cout; p.K = p.R * p.S * p.Cin;
             p.a = act(l.in0); p.a_rep = e.rep_block;
             p.cursor = l.in0 == 0 ? e.buf.cursor : nullptr;
-            p.out = actw(l.out); p.out_rep = e.rep_block;
+            p.out = actw(ot); p.out_rep = e.rep_block;
+            p.relu = e.fused_relu[i];
+            if (l.type == HADFL_OP_DENSE && l.cout <= 16 && l.in0 != 0 && !p.relu) {
+                DenseSmallParams d{};
+                d.x = act(l.in0); d.x_rep = e.rep_block; d.w = p.w; d.w_rep = p.w_rep;
+                d.out = actw(ot); d.out_rep = e.rep_block;
+                d.rows = (int)B; d.K = p.Cin; d.N = l.cout; d.has_bias = l.bias; d.order = e.buf.order;
+                run("dense_small_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_dense_small_fwd(d, na, s); });
+                break;
+            }
             run(l.type == HADFL_OP_CONV ? "conv_fwd" : "dense_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_gemm(p, na, s); });
             break; }
         case HADFL_OP_RELU: run("relu_fwd", 0, 8.0 * q.count, [&] { return launch_relu_fwd(q, na, s); }); break;
@@ -195,6 +241,7 @@ struct Runner {
         case HADFL_OP_GAP: run("gap_fwd", 0, 4.0 * (B * a.numel() + q.count), [&] { return launch_gap_fwd(q, na, s); }); break;
         case HADFL_OP_BN: {
             BnParams b = bn_params(i);
+            b.y = actw(ot); b.relu = e.fused_relu[i];
             run("bn_fwd", 0, 8.0 * B * a.numel(), [&] { return launch_bn_fwd(b, na, s); });
             break; }
         }
@@ -221,14 +268,19 @@ struct Runner {
     // d(out) is complete; produce d(in0) (and d(in1)), and the parameter gradients of the layer
     void backward_layer(size_t i)
     {
+        cur_layer = (int)i;
+        if (e.skip[i]) return;
         const Layer& l = e.plan.layers[i];
         const TensorShape a = e.plan.tensors[l.in0], r = e.plan.tensors[l.out];
         const int64_t B = e.cfg.batch;
         const bool need_din = l.in0 != 0;
         const int acc0 = need_din ? (e.grad_written[l.in0] ? 1 : 0) : 0;
+        const int ot = e.out_tensor[i];          // d(loss)/d(this layer's pre-ReLU output) lives in grad(ot)
+        const float* mask0 = (need_din && e.masked[l.in0]) ? act(l.in0) : nullptr;
         EwParams q{};
         q.order = e.buf.order; q.B = (int)B; q.H = a.h; q.W = a.w; q.C = a.c;
         q.accumulate = acc0;
+        q.mask = mask0; q.mask_rep = e.rep_block;
         if (need_din) { q.out = grad(l.in0); q.out_rep = e.rep_block; }
         switch (l.type) {
         case HADFL_OP_CONV:
@@ -239,7 +291,7 @@ struct Runner {
             p.M = p.R * p.S * p.Cin + (l.bias ? 1 : 0); p.N = p.Cout; p.K = (int)(B * p.Ho * p.Wo);
             p.a = act(l.in0); p.a_rep = e.rep_block;
             p.cursor = l.in0 == 0 ? e.buf.cursor : nullptr;
-            p.dy = grad(l.out); p.dy_rep = e.rep_block;
+            p.dy = grad(ot); p.dy_rep = e.rep_block;
             p.splits = e.splits[i];
             const int64_t mn = (int64_t)p.M * p.N;
             if (p.splits > 1) {
@@ -258,9 +310,10 @@ struct Runner {
                 GemmParams d = gemm_base(l);
                 d.mode = kDgrad;
                 d.M = (int)(B * d.H * d.W); d.N = d.Cin; d.K = d.R * d.S * d.Cout;
-                d.a = grad(l.out); d.a_rep = e.rep_block;
+                d.a = grad(ot); d.a_rep = e.rep_block;
                 d.out = grad(l.in0); d.out_rep = e.rep_block;
                 d.accumulate = acc0;
+                d.mask = mask0; d.mask_rep = e.rep_block;
                 run(l.type == HADFL_OP_CONV ? "conv_dgrad" : "dense_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return launch_gemm(d, na, s); });
             }
             break; }
@@ -275,11 +328,12 @@ struct Runner {
             run("maxpool_bwd", 0, 4.0 * (2 * B * a.numel() + q.count), [&] { return launch_maxpool_bwd(q, na, s); });
             break;
         case HADFL_OP_ADD: {
-            q.in = grad(l.out); q.in_rep = e.rep_block; q.count = B * a.numel();
+            q.in = grad(ot); q.in_rep = e.rep_block; q.count = B * a.numel();
             run("add_bwd", 0, 8.0 * q.count, [&] { return launch_pass_grad(q, na, s); });
             EwParams q2 = q;
             if (l.in1 == l.in0) q2.accumulate = 1; else q2.accumulate = e.grad_written[l.in1] ? 1 : 0;
             q2.out = grad(l.in1);
+            q2.mask = e.masked[l.in1] ? act(l.in1) : nullptr;
             run("add_bwd", 0, 8.0 * q.count, [&] { return launch_pass_grad(q2, na, s); });
             e.grad_written[l.in1] = 1;
             break; }
@@ -289,9 +343,10 @@ struct Runner {
             break;
         case HADFL_OP_BN: {
             BnParams b = bn_params(i);
-            b.dy = grad(l.out); b.dy_rep = e.rep_block;
+            b.dy = grad(ot); b.dy_rep = e.rep_block;
             b.y = grad(l.in0); b.y_rep = e.rep_block;
             b.accumulate = acc0;
+            b.mask = mask0; b.mask_rep = e.rep_block;
             run("bn_bwd", 0, 12.0 * B * a.numel(), [&] { return launch_bn_bwd(b, na, s); });
             break; }
         }

@@ -34,6 +34,7 @@ void train_destroy(TrainEngine* e);
 struct Profiler {
     struct Rec { std::string name; hipEvent_t a, b; double flops, bytes; };
     bool on = false;
+    bool detail = false;            // names carry the layer index and the number of active replicas
     std::vector<Rec> recs;
     std::vector<hipEvent_t> pool;
     hipEvent_t get();

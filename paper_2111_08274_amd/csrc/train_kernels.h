@@ -26,12 +26,24 @@ struct GemmParams {
     const float* dy; long long dy_rep;            // kWgrad: dY
     float* out; long long out_rep, out_split;     // kWgrad with splits > 1: partial sums [g][split][M*N]
     int has_bias, relu, accumulate;
+    // kDgrad: when set, the written gradient is zeroed where mask <= 0 (mask = the ReLU output stored in the tensor
+    // whose gradient is being produced, so the result is the gradient before that fused ReLU)
+    const float* mask; long long mask_rep;
     const int* order;
 };
 hipError_t launch_gemm(const GemmParams& p, int n_active, hipStream_t s);
 // out[rep][i] = sum_s partial[g][s][i], s ascending
 hipError_t launch_splitk_reduce(const float* partial, long long split_stride, int splits, float* out, long long out_rep,
                                 long long count, const int* order, int n_active, hipStream_t s);
+
+struct DenseSmallParams {     // out[m][n] = sum_k x[m][k] w[k][n] + bias[n], N <= 16
+    const float* x; long long x_rep;
+    const float* w; long long w_rep;     // weights [K][N] followed by bias [N]
+    float* out; long long out_rep;
+    int rows, K, N, has_bias;
+    const int* order;
+};
+hipError_t launch_dense_small_fwd(const DenseSmallParams& p, int n_active, hipStream_t s);
 
 struct EwParams {     // element-wise / pooling kernels
     const float* in; long long in_rep;
@@ -40,6 +52,8 @@ struct EwParams {     // element-wise / pooling kernels
     long long count;              // elements per replica of `out`
     int B, H, W, C;               // input geometry where needed
     int accumulate;
+    int relu;                     // forward kernels: apply max(., 0) to the result
+    const float* mask; long long mask_rep;   // backward kernels: zero the written gradient where mask <= 0
     const int* order;
 };
 hipError_t launch_relu_fwd(const EwParams& p, int n_active, hipStream_t s);
@@ -65,6 +79,8 @@ struct BnParams {
     float* partial; long long partial_rep; // [chunks][2][C]
     int rows, C, chunks, chunk_rows;
     int accumulate;
+    int relu;                              // forward: y = max(bn(x), 0)
+    const float* mask; long long mask_rep; // backward: zero dx where mask <= 0
     const int* order;
 };
 hipError_t launch_bn_fwd(const BnParams& p, int n_active, hipStream_t s);

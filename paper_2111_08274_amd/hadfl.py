@@ -226,11 +226,11 @@ class Context:
         return out
 
     def profile(self, on):
-        _check(lib().hadfl_profile_enable(self.h, int(bool(on))), self.h)
+        _check(lib().hadfl_profile_enable(self.h, int(on)), self.h)
 
     def profile_read(self):
         n = ctypes.c_int32()
-        rows = (HadflKernelTime * 256)()
-        _check(lib().hadfl_profile_read(self.h, rows, 256, ctypes.byref(n)), self.h)
+        rows = (HadflKernelTime * 4096)()
+        _check(lib().hadfl_profile_read(self.h, rows, 4096, ctypes.byref(n)), self.h)
         return {rows[i].name.decode(): dict(launches=rows[i].launches, ms=rows[i].total_ms, flops=rows[i].flops,
-                                            bytes=rows[i].bytes) for i in range(min(n.value, 256))}
+                                            bytes=rows[i].bytes) for i in range(min(n.value, 4096))}
