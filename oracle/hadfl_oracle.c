@@ -53,9 +53,14 @@ typedef struct {
     int64_t *off_b;          /* bias / beta offset per op (-1 if none)   */
     int64_t *off_stat;       /* running mean offset per BN op; running var follows */
     int64_t m_train, m_total;
-    int act_rounding;        /* 0: none; 1: activations, weights used in the
-                                forward/backward and stored gradients of
-                                activations are rounded to bfloat16 */
+    int act_rounding;        /* 0: none; 1 (the bf16 workload): every stored
+                                activation (input batch and logits included),
+                                every stored activation gradient, and the
+                                conv / dense weights as used by the forward and
+                                backward pass are rounded to bfloat16; biases,
+                                BN parameters, sums, weight gradients and the
+                                update stay unrounded (fp32 master + fp32
+                                accumulation on the GPU side) */
 } net_t;
 
 static int64_t numel(shape_t s) { return (int64_t)s.h * s.w * s.c; }
@@ -215,7 +220,13 @@ double hadfl_oracle_loss_grad(const net_t *n, double *params, const float *x, co
     double *w = params;
     if (n->act_rounding) {
         w = (double *)malloc(sizeof(double) * (size_t)n->m_train);
-        for (int64_t i = 0; i < n->m_train; ++i) w[i] = round_bf16(params[i]);
+        memcpy(w, params, sizeof(double) * (size_t)n->m_train);
+        for (int i = 0; i < n->n_ops; ++i)
+            if (n->ops[i].type == OP_CONV || n->ops[i].type == OP_DENSE) {
+                const op_t *p = &n->ops[i];
+                int64_t cnt = (p->type == OP_CONV ? (int64_t)p->k * p->k * n->shp[p->in0].c : numel(n->shp[p->in0])) * p->cout;
+                for (int64_t j = 0; j < cnt; ++j) w[n->off_a[i] + j] = round_bf16(params[n->off_a[i] + j]);
+            }
     }
     for (int t = 0; t < T; ++t) {
         act[t] = (double *)calloc((size_t)(B * numel(n->shp[t])), sizeof(double));
@@ -329,8 +340,7 @@ double hadfl_oracle_loss_grad(const net_t *n, double *params, const float *x, co
                 }
             break; }
         }
-        /* the network output (logits) stays unrounded: the loss reads the accumulator */
-        if (p->out != T - 1) round_buf(n, out, B * numel(r));
+        round_buf(n, out, B * numel(r));
     }
 
     /* ---------------- loss (mean over the batch) and its gradient ---------------- */
@@ -365,7 +375,7 @@ double hadfl_oracle_loss_grad(const net_t *n, double *params, const float *x, co
         const double *in = act[p->in0];
         const double *dout = gra[p->out];
         double *din = gra[p->in0];                     /* accumulated: a tensor may feed two ops */
-        if (p->out != T - 1) round_buf(n, gra[p->out], B * numel(r));
+        round_buf(n, gra[p->out], B * numel(r));
         switch (p->type) {
         case OP_CONV: {
             const double *wt = w + n->off_a[i];

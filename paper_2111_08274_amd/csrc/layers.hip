@@ -9,36 +9,51 @@ namespace {
 constexpr float kBnEps = 1e-5f;
 constexpr float kBnStatMomentum = 0.1f;
 
+// Activation tensors are fp32 or bf16 (the bf16 configuration); offsets and per-replica strides are always counted
+// in 4-byte units, so a bf16 tensor occupies the first half of its slot.
+template <typename T> __device__ __forceinline__ T* tptr(const void* base, long long rep, long long rep_stride)
+{
+    return (T*)((char*)base + rep * rep_stride * 4);
+}
+__device__ __forceinline__ float ldf(const float* p, long long i) { return p[i]; }
+__device__ __forceinline__ float ldf(const __bf16* p, long long i) { return (float)p[i]; }
+__device__ __forceinline__ void stf(float* p, long long i, float v) { p[i] = v; }
+__device__ __forceinline__ void stf(__bf16* p, long long i, float v) { p[i] = (__bf16)v; }
+
 __device__ __forceinline__ long long gtid() { return (long long)blockIdx.x * blockDim.x + threadIdx.x; }
 __device__ __forceinline__ long long gstride() { return (long long)gridDim.x * blockDim.x; }
 
+template <typename T>
 __global__ __launch_bounds__(256) void relu_fwd_kernel(EwParams p)
 {
     const int rep = p.order[blockIdx.y];
-    const float* in = p.in + rep * p.in_rep;
-    float* out = p.out + rep * p.out_rep;
-    for (long long i = gtid(); i < p.count; i += gstride()) out[i] = fmaxf(in[i], 0.f);
+    const T* in = tptr<T>(p.in, rep, p.in_rep);
+    T* out = tptr<T>(p.out, rep, p.out_rep);
+    for (long long i = gtid(); i < p.count; i += gstride()) stf(out, i, fmaxf(ldf(in, i), 0.f));
 }
 
+template <typename T>
 __global__ __launch_bounds__(256) void relu_bwd_kernel(EwParams p)
 {
     const int rep = p.order[blockIdx.y];
-    const float* x = p.in + rep * p.in_rep;
-    const float* dout = p.in2 + rep * p.in2_rep;
-    float* din = p.out + rep * p.out_rep;
+    const T* x = tptr<T>(p.in, rep, p.in_rep);
+    const T* dout = tptr<T>(p.in2, rep, p.in2_rep);
+    T* din = tptr<T>(p.out, rep, p.out_rep);
+    const T* mask = p.mask ? tptr<T>(p.mask, rep, p.mask_rep) : nullptr;
     for (long long i = gtid(); i < p.count; i += gstride()) {
-        float g = x[i] > 0.f ? dout[i] : 0.f;
-        if (p.mask && !(p.mask[rep * p.mask_rep + i] > 0.f)) g = 0.f;
-        din[i] = p.accumulate ? din[i] + g : g;
+        float g = ldf(x, i) > 0.f ? ldf(dout, i) : 0.f;
+        if (mask && !(ldf(mask, i) > 0.f)) g = 0.f;
+        stf(din, i, p.accumulate ? ldf(din, i) + g : g);
     }
 }
 
 // count = pooled elements; in is [B][H][W][C]
+template <typename T>
 __global__ __launch_bounds__(256) void maxpool_fwd_kernel(EwParams p)
 {
     const int rep = p.order[blockIdx.y];
-    const float* in = p.in + rep * p.in_rep;
-    float* out = p.out + rep * p.out_rep;
+    const T* in = tptr<T>(p.in, rep, p.in_rep);
+    T* out = tptr<T>(p.out, rep, p.out_rep);
     const int Ho = p.H / 2, Wo = p.W / 2;
     for (long long i = gtid(); i < p.count; i += gstride()) {
         const int c = (int)(i % p.C);
@@ -46,19 +61,20 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(EwParams p)
         const int xo = (int)(t % Wo); t /= Wo;
         const int yo = (int)(t % Ho);
         const int b = (int)(t / Ho);
-        const float* q = in + (((long long)b * p.H + 2 * yo) * p.W + 2 * xo) * p.C + c;
+        const long long q = (((long long)b * p.H + 2 * yo) * p.W + 2 * xo) * p.C + c;
         const long long rowp = (long long)p.W * p.C;
-        out[i] = fmaxf(fmaxf(q[0], q[p.C]), fmaxf(q[rowp], q[rowp + p.C]));
+        stf(out, i, fmaxf(fmaxf(ldf(in, q), ldf(in, q + p.C)), fmaxf(ldf(in, q + rowp), ldf(in, q + rowp + p.C))));
     }
 }
 
 // the gradient goes to the first maximal element in (dy, dx) scan order; count = pooled elements
+template <typename T>
 __global__ __launch_bounds__(256) void maxpool_bwd_kernel(EwParams p)
 {
     const int rep = p.order[blockIdx.y];
-    const float* x = p.in + rep * p.in_rep;
-    const float* dout = p.in2 + rep * p.in2_rep;
-    float* din = p.out + rep * p.out_rep;
+    const T* x = tptr<T>(p.in, rep, p.in_rep);
+    const T* dout = tptr<T>(p.in2, rep, p.in2_rep);
+    T* din = tptr<T>(p.out, rep, p.out_rep);
     const int Ho = p.H / 2, Wo = p.W / 2;
     for (long long i = gtid(); i < p.count; i += gstride()) {
         const int c = (int)(i % p.C);
@@ -69,73 +85,78 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(EwParams p)
         const long long base = (((long long)b * p.H + 2 * yo) * p.W + 2 * xo) * p.C + c;
         const long long rowp = (long long)p.W * p.C;
         const long long off[4] = {0, p.C, rowp, rowp + p.C};
-        float m = x[base]; int arg = 0;
+        float m = ldf(x, base); int arg = 0;
 #pragma unroll
-        for (int j = 1; j < 4; ++j) { const float v = x[base + off[j]]; if (v > m) { m = v; arg = j; } }
-        const float g = dout[i];
+        for (int j = 1; j < 4; ++j) { const float v = ldf(x, base + off[j]); if (v > m) { m = v; arg = j; } }
+        const float g = ldf(dout, i);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             // with p.mask set, x is a fused ReLU output: the gradient passes only where it is positive
             const float v = (j == arg && (!p.mask || m > 0.f)) ? g : 0.f;
-            float* d = din + base + off[j];
-            *d = p.accumulate ? *d + v : v;
+            const long long d = base + off[j];
+            stf(din, d, p.accumulate ? ldf(din, d) + v : v);
         }
     }
 }
 
+template <typename T>
 __global__ __launch_bounds__(256) void add_fwd_kernel(EwParams p)
 {
     const int rep = p.order[blockIdx.y];
-    const float* a = p.in + rep * p.in_rep;
-    const float* b = p.in2 + rep * p.in2_rep;
-    float* out = p.out + rep * p.out_rep;
+    const T* a = tptr<T>(p.in, rep, p.in_rep);
+    const T* b = tptr<T>(p.in2, rep, p.in2_rep);
+    T* out = tptr<T>(p.out, rep, p.out_rep);
     for (long long i = gtid(); i < p.count; i += gstride()) {
-        const float v = a[i] + b[i];
-        out[i] = p.relu ? fmaxf(v, 0.f) : v;
+        const float v = ldf(a, i) + ldf(b, i);
+        stf(out, i, p.relu ? fmaxf(v, 0.f) : v);
     }
 }
 
+template <typename T>
 __global__ __launch_bounds__(256) void pass_grad_kernel(EwParams p)
 {
     const int rep = p.order[blockIdx.y];
-    const float* dout = p.in + rep * p.in_rep;
-    float* din = p.out + rep * p.out_rep;
-    const float* mask = p.mask ? p.mask + rep * p.mask_rep : nullptr;
+    const T* dout = tptr<T>(p.in, rep, p.in_rep);
+    T* din = tptr<T>(p.out, rep, p.out_rep);
+    const T* mask = p.mask ? tptr<T>(p.mask, rep, p.mask_rep) : nullptr;
     for (long long i = gtid(); i < p.count; i += gstride()) {
-        const float g = (!mask || mask[i] > 0.f) ? dout[i] : 0.f;
-        din[i] = p.accumulate ? din[i] + g : g;
+        const float g = (!mask || ldf(mask, i) > 0.f) ? ldf(dout, i) : 0.f;
+        stf(din, i, p.accumulate ? ldf(din, i) + g : g);
     }
 }
 
 // out[b][c] = mean over H*W; count = B*C
+template <typename T>
 __global__ __launch_bounds__(256) void gap_fwd_kernel(EwParams p)
 {
     const int rep = p.order[blockIdx.y];
-    const float* in = p.in + rep * p.in_rep;
-    float* out = p.out + rep * p.out_rep;
+    const T* in = tptr<T>(p.in, rep, p.in_rep);
+    T* out = tptr<T>(p.out, rep, p.out_rep);
     const int hw = p.H * p.W;
     for (long long i = gtid(); i < p.count; i += gstride()) {
         const int c = (int)(i % p.C);
         const long long b = i / p.C;
         float s = 0.f;
-        for (int q = 0; q < hw; ++q) s += in[(b * hw + q) * p.C + c];
-        out[i] = s / (float)hw;
+        for (int q = 0; q < hw; ++q) s += ldf(in, (b * hw + q) * p.C + c);
+        stf(out, i, s / (float)hw);
     }
 }
 
 // din[b][q][c] (+)= dout[b][c] / (H*W); count = B*H*W*C
+template <typename T>
 __global__ __launch_bounds__(256) void gap_bwd_kernel(EwParams p)
 {
     const int rep = p.order[blockIdx.y];
-    const float* dout = p.in + rep * p.in_rep;
-    float* din = p.out + rep * p.out_rep;
+    const T* dout = tptr<T>(p.in, rep, p.in_rep);
+    T* din = tptr<T>(p.out, rep, p.out_rep);
+    const T* mask = p.mask ? tptr<T>(p.mask, rep, p.mask_rep) : nullptr;
     const int hw = p.H * p.W;
     for (long long i = gtid(); i < p.count; i += gstride()) {
         const int c = (int)(i % p.C);
         const long long b = i / ((long long)hw * p.C);
-        float g = dout[b * p.C + c] / (float)hw;
-        if (p.mask && !(p.mask[rep * p.mask_rep + i] > 0.f)) g = 0.f;
-        din[i] = p.accumulate ? din[i] + g : g;
+        float g = ldf(dout, b * p.C + c) / (float)hw;
+        if (mask && !(ldf(mask, i) > 0.f)) g = 0.f;
+        stf(din, i, p.accumulate ? ldf(din, i) + g : g);
     }
 }
 
@@ -145,7 +166,7 @@ __global__ __launch_bounds__(256) void gap_bwd_kernel(EwParams p)
 // adds in chunk order.
 // Block = 256 threads = 64 channel lanes x 4 row lanes; grid = (chunks * ceil(C/64), n_active).
 // ------------------------------------------------------------------------------------------------------
-template <int PASS>   // 0: sum x   1: sum (x-mean)^2   2 (backward): sum dy and sum dy*xhat
+template <int PASS, typename T>   // 0: sum x   1: sum (x-mean)^2   2 (backward): sum dy and sum dy*xhat
 __global__ __launch_bounds__(256) void bn_reduce_kernel(BnParams p)
 {
     __shared__ float red[2][4][64];
@@ -154,7 +175,7 @@ __global__ __launch_bounds__(256) void bn_reduce_kernel(BnParams p)
     const int chunk = blockIdx.x / cgroups, cg = blockIdx.x % cgroups;
     const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
     const int c = cg * 64 + cl;
-    const float* x = p.x + rep * p.x_rep;
+    const T* x = tptr<T>(p.x, rep, p.x_rep);
     float* part = p.partial + g * p.partial_rep;
     float mean = 0.f, istd = 0.f;
     if (PASS >= 1 && c < p.C) {
@@ -170,12 +191,12 @@ __global__ __launch_bounds__(256) void bn_reduce_kernel(BnParams p)
     const int r0 = chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
     float s0 = 0.f, s1 = 0.f;
     if (c < p.C) {
-        const float* dy = (PASS == 2) ? p.dy + rep * p.dy_rep : nullptr;
+        const T* dy = (PASS == 2) ? tptr<T>(p.dy, rep, p.dy_rep) : nullptr;
         for (int r = r0 + rl; r < r1; r += 4) {
-            const float v = x[(long long)r * p.C + c];
+            const float v = ldf(x, (long long)r * p.C + c);
             if (PASS == 0) s0 += v;
             else if (PASS == 1) { const float d = v - mean; s1 += d * d; }
-            else { const float d = dy[(long long)r * p.C + c]; s0 += d; s1 += d * ((v - mean) * istd); }
+            else { const float d = ldf(dy, (long long)r * p.C + c); s0 += d; s1 += d * ((v - mean) * istd); }
         }
     }
     red[0][rl][cl] = s0; red[1][rl][cl] = s1;
@@ -190,6 +211,7 @@ __global__ __launch_bounds__(256) void bn_reduce_kernel(BnParams p)
 }
 
 // y = gamma * (x - mean) * istd + beta; the blocks of chunk 0 also store mean / istd and update the running statistics
+template <typename T>
 __global__ __launch_bounds__(256) void bn_apply_fwd_kernel(BnParams p)
 {
     const int g = blockIdx.y, rep = p.order[g];
@@ -198,8 +220,8 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_kernel(BnParams p)
     const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
     const int c = cg * 64 + cl;
     if (c >= p.C) return;
-    const float* x = p.x + rep * p.x_rep;
-    float* y = p.y + rep * p.y_rep;
+    const T* x = tptr<T>(p.x, rep, p.x_rep);
+    T* y = tptr<T>(p.y, rep, p.y_rep);
     const float* part = p.partial + g * p.partial_rep;
     float* row = p.params + rep * p.row_stride;
     float s = 0.f, q = 0.f;
@@ -218,12 +240,13 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_kernel(BnParams p)
     const int r0 = chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
     for (int r = r0 + rl; r < r1; r += 4) {
         const long long i = (long long)r * p.C + c;
-        const float v = gamma * ((x[i] - mean) * istd) + beta;
-        y[i] = p.relu ? fmaxf(v, 0.f) : v;
+        const float v = gamma * ((ldf(x, i) - mean) * istd) + beta;
+        stf(y, i, p.relu ? fmaxf(v, 0.f) : v);
     }
 }
 
 // dx = gamma*istd*(dy - sum(dy)/n - xhat*sum(dy*xhat)/n); chunk-0 blocks write dgamma, dbeta
+template <typename T>
 __global__ __launch_bounds__(256) void bn_apply_bwd_kernel(BnParams p)
 {
     const int g = blockIdx.y, rep = p.order[g];
@@ -232,9 +255,10 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_kernel(BnParams p)
     const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
     const int c = cg * 64 + cl;
     if (c >= p.C) return;
-    const float* x = p.x + rep * p.x_rep;
-    const float* dy = p.dy + rep * p.dy_rep;
-    float* dx = p.y + rep * p.y_rep;
+    const T* x = tptr<T>(p.x, rep, p.x_rep);
+    const T* dy = tptr<T>(p.dy, rep, p.dy_rep);
+    T* dx = tptr<T>(p.y, rep, p.y_rep);
+    const T* mask = p.mask ? tptr<T>(p.mask, rep, p.mask_rep) : nullptr;
     const float* part = p.partial + g * p.partial_rep;
     const float* sv = p.saved + rep * p.saved_rep;
     float db = 0.f, dg = 0.f;
@@ -249,14 +273,15 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_kernel(BnParams p)
     const int r0 = chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
     for (int r = r0 + rl; r < r1; r += 4) {
         const long long i = (long long)r * p.C + c;
-        const float xh = (x[i] - mean) * istd;
-        float v = k1 * (dy[i] - db * inv_n - xh * dg * inv_n);
-        if (p.mask && !(p.mask[rep * p.mask_rep + i] > 0.f)) v = 0.f;
-        dx[i] = p.accumulate ? dx[i] + v : v;
+        const float xh = (ldf(x, i) - mean) * istd;
+        float v = k1 * (ldf(dy, i) - db * inv_n - xh * dg * inv_n);
+        if (mask && !(ldf(mask, i) > 0.f)) v = 0.f;
+        stf(dx, i, p.accumulate ? ldf(dx, i) + v : v);
     }
 }
 
 // One workgroup per replica, one thread per sample: softmax, loss, d(loss)/d(logits); loss summed by an LDS tree.
+template <typename T>
 __global__ __launch_bounds__(1024) void softmax_ce_kernel(LossParams p)
 {
     __shared__ float red[1024];
@@ -266,16 +291,16 @@ __global__ __launch_bounds__(1024) void softmax_ce_kernel(LossParams p)
     if (b < p.batch) {
         const long long first = (p.cursor[rep] * (long long)p.batch) % p.n_samples;
         const int label = p.y[(long long)rep * p.n_samples + first + b];
-        const float* z = p.logits + rep * p.logits_rep + (long long)b * p.n_classes;
-        float* dz = p.dlogits + rep * p.dlogits_rep + (long long)b * p.n_classes;
-        float m = z[0];
-        for (int j = 1; j < p.n_classes; ++j) m = fmaxf(m, z[j]);
+        const T* z = tptr<T>(p.logits, rep, p.logits_rep) + (long long)b * p.n_classes;
+        T* dz = tptr<T>(p.dlogits, rep, p.dlogits_rep) + (long long)b * p.n_classes;
+        float m = ldf(z, 0);
+        for (int j = 1; j < p.n_classes; ++j) m = fmaxf(m, ldf(z, j));
         float s = 0.f;
-        for (int j = 0; j < p.n_classes; ++j) s += expf(z[j] - m);
-        li = (logf(s) + m - z[label]) / (float)p.batch;
+        for (int j = 0; j < p.n_classes; ++j) s += expf(ldf(z, j) - m);
+        li = (logf(s) + m - ldf(z, label)) / (float)p.batch;
         const float inv = 1.0f / s;
         for (int j = 0; j < p.n_classes; ++j)
-            dz[j] = (expf(z[j] - m) * inv - (j == label ? 1.f : 0.f)) / (float)p.batch;
+            stf(dz, j, (expf(ldf(z, j) - m) * inv - (j == label ? 1.f : 0.f)) / (float)p.batch);
     }
     red[b] = li;
     __syncthreads();
@@ -307,23 +332,24 @@ __global__ __launch_bounds__(256) void sgd_kernel(SgdParams p)
 // Narrow dense layer (the classifier: out <= 16): one workgroup per sample row; threads stride over the input
 // features, keep `out` partial sums each and combine them with a fixed butterfly and a fixed LDS order.  Too small
 // for the matrix cores.
-template <int NMAX>
+template <int NMAX, typename T>
 __global__ __launch_bounds__(256) void dense_small_fwd_kernel(DenseSmallParams p)
 {
     __shared__ float red[4][NMAX];
     const int rep = p.order[blockIdx.y];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = blockIdx.x;
-    const float* x = p.x + rep * p.x_rep + (long long)m * p.K;
+    const T* x = tptr<T>(p.x, rep, p.x_rep) + (long long)m * p.K;
     const float* w = p.w + rep * p.w_rep;
+    constexpr bool kRoundW = sizeof(T) == 2;      // bf16 configuration: weights take part rounded to bf16
     float acc[NMAX];
 #pragma unroll
     for (int n = 0; n < NMAX; ++n) acc[n] = 0.f;
     for (int k = threadIdx.x; k < p.K; k += 256) {
-        const float xv = x[k];
+        const float xv = ldf(x, k);
         const float* wr = w + (long long)k * p.N;
 #pragma unroll
-        for (int n = 0; n < NMAX; ++n) if (n < p.N) acc[n] += xv * wr[n];
+        for (int n = 0; n < NMAX; ++n) if (n < p.N) acc[n] += xv * (kRoundW ? (float)(__bf16)wr[n] : wr[n]);
     }
 #pragma unroll
     for (int n = 0; n < NMAX; ++n) {
@@ -335,8 +361,8 @@ __global__ __launch_bounds__(256) void dense_small_fwd_kernel(DenseSmallParams p
     __syncthreads();
     if (threadIdx.x < p.N) {
         const int n = threadIdx.x;
-        float* o = p.out + rep * p.out_rep + (long long)m * p.N;
-        o[n] = ((red[0][n] + red[1][n]) + (red[2][n] + red[3][n])) + (p.has_bias ? w[(long long)p.K * p.N + n] : 0.f);
+        T* o = tptr<T>(p.out, rep, p.out_rep) + (long long)m * p.N;
+        stf(o, n, ((red[0][n] + red[1][n]) + (red[2][n] + red[3][n])) + (p.has_bias ? w[(long long)p.K * p.N + n] : 0.f));
     }
 }
 
@@ -353,7 +379,8 @@ dim3 ew_grid(long long count, int n_active)
 #define HADFL_EW_LAUNCH(fn, kern) \
     hipError_t fn(const EwParams& p, int n_active, hipStream_t s) { \
         if (n_active < 1 || p.count < 1) return hipSuccess; \
-        hipLaunchKernelGGL(kern, ew_grid(p.count, n_active), dim3(256), 0, s, p); \
+        if (p.bf16) hipLaunchKernelGGL(kern<__bf16>, ew_grid(p.count, n_active), dim3(256), 0, s, p); \
+        else hipLaunchKernelGGL(kern<float>, ew_grid(p.count, n_active), dim3(256), 0, s, p); \
         return hipGetLastError(); }
 HADFL_EW_LAUNCH(launch_relu_fwd, relu_fwd_kernel)
 HADFL_EW_LAUNCH(launch_relu_bwd, relu_bwd_kernel)
@@ -368,7 +395,8 @@ HADFL_EW_LAUNCH(launch_gap_bwd, gap_bwd_kernel)
 hipError_t launch_dense_small_fwd(const DenseSmallParams& p, int n_active, hipStream_t s)
 {
     if (n_active < 1 || p.rows < 1) return hipSuccess;
-    hipLaunchKernelGGL(dense_small_fwd_kernel<16>, dim3((unsigned)p.rows, (unsigned)n_active), dim3(256), 0, s, p);
+    if (p.bf16) hipLaunchKernelGGL((dense_small_fwd_kernel<16, __bf16>), dim3((unsigned)p.rows, (unsigned)n_active), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((dense_small_fwd_kernel<16, float>), dim3((unsigned)p.rows, (unsigned)n_active), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
@@ -376,9 +404,15 @@ hipError_t launch_bn_fwd(const BnParams& p, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
     const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active), block(256);
-    hipLaunchKernelGGL(bn_reduce_kernel<0>, grid, block, 0, s, p);
-    hipLaunchKernelGGL(bn_reduce_kernel<1>, grid, block, 0, s, p);
-    hipLaunchKernelGGL(bn_apply_fwd_kernel, grid, block, 0, s, p);
+    if (p.bf16) {
+        hipLaunchKernelGGL((bn_reduce_kernel<0, __bf16>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((bn_reduce_kernel<1, __bf16>), grid, block, 0, s, p);
+        hipLaunchKernelGGL(bn_apply_fwd_kernel<__bf16>, grid, block, 0, s, p);
+    } else {
+        hipLaunchKernelGGL((bn_reduce_kernel<0, float>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((bn_reduce_kernel<1, float>), grid, block, 0, s, p);
+        hipLaunchKernelGGL(bn_apply_fwd_kernel<float>, grid, block, 0, s, p);
+    }
     return hipGetLastError();
 }
 
@@ -386,8 +420,13 @@ hipError_t launch_bn_bwd(const BnParams& p, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
     const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active), block(256);
-    hipLaunchKernelGGL(bn_reduce_kernel<2>, grid, block, 0, s, p);
-    hipLaunchKernelGGL(bn_apply_bwd_kernel, grid, block, 0, s, p);
+    if (p.bf16) {
+        hipLaunchKernelGGL((bn_reduce_kernel<2, __bf16>), grid, block, 0, s, p);
+        hipLaunchKernelGGL(bn_apply_bwd_kernel<__bf16>, grid, block, 0, s, p);
+    } else {
+        hipLaunchKernelGGL((bn_reduce_kernel<2, float>), grid, block, 0, s, p);
+        hipLaunchKernelGGL(bn_apply_bwd_kernel<float>, grid, block, 0, s, p);
+    }
     return hipGetLastError();
 }
 
@@ -396,7 +435,8 @@ hipError_t launch_softmax_ce(const LossParams& p, int n_active, hipStream_t s)
     if (n_active < 1) return hipSuccess;
     int threads = 64;
     while (threads < p.batch) threads *= 2;      // power of two for the tree; batch <= 1024 is checked at init
-    hipLaunchKernelGGL(softmax_ce_kernel, dim3((unsigned)n_active), dim3((unsigned)threads), 0, s, p);
+    if (p.bf16) hipLaunchKernelGGL(softmax_ce_kernel<__bf16>, dim3((unsigned)n_active), dim3((unsigned)threads), 0, s, p);
+    else hipLaunchKernelGGL(softmax_ce_kernel<float>, dim3((unsigned)n_active), dim3((unsigned)threads), 0, s, p);
     return hipGetLastError();
 }
 

@@ -102,7 +102,6 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
                           TrainEngine** out, std::string& err)
 {
     (void)order;
-    if (cfg.bf16) { err = "the bf16 path is not built yet"; return HADFL_EUNSUPPORTED; }
     TrainEngine* e = new TrainEngine();
     e->cfg = cfg; e->plan = plan; e->buf = buf; e->steps = steps;
     e->e_max = *std::max_element(steps.begin(), steps.end());
@@ -170,6 +169,7 @@ struct Runner {
         if (rc != hipSuccess) failed = name;
     }
 
+    hipError_t gemm(const GemmParams& p) const { return e.cfg.bf16 ? launch_gemm_bf16(p, na, s) : launch_gemm(p, na, s); }
     static double gemm_flops(const GemmParams& p) { return 2.0 * p.B * p.Ho * p.Wo * p.R * p.S * (double)p.Cin * p.Cout; }
     static double gemm_bytes(const GemmParams& p)
     {
@@ -207,7 +207,7 @@ struct Runner {
         const int64_t B = e.cfg.batch;
         const int ot = e.out_tensor[i];
         EwParams q{};
-        q.order = e.buf.order; q.B = (int)B; q.H = a.h; q.W = a.w; q.C = a.c;
+        q.order = e.buf.order; q.B = (int)B; q.H = a.h; q.W = a.w; q.C = a.c; q.bf16 = e.cfg.bf16;
         q.in = act(l.in0); q.in_rep = e.rep_block;
         q.out = actw(ot); q.out_rep = e.rep_block;
         q.relu = e.fused_relu[i];
@@ -220,17 +220,18 @@ struct Runner {
             p.M = (int)(B * p.Ho * p.Wo); p.N = p.Cout; p.K = p.R * p.S * p.Cin;
             p.a = act(l.in0); p.a_rep = e.rep_block;
             p.cursor = l.in0 == 0 ? e.buf.cursor : nullptr;
+            p.a_f32 = l.in0 == 0;
             p.out = actw(ot); p.out_rep = e.rep_block;
             p.relu = e.fused_relu[i];
             if (l.type == HADFL_OP_DENSE && l.cout <= 16 && l.in0 != 0 && !p.relu) {
                 DenseSmallParams d{};
                 d.x = act(l.in0); d.x_rep = e.rep_block; d.w = p.w; d.w_rep = p.w_rep;
                 d.out = actw(ot); d.out_rep = e.rep_block;
-                d.rows = (int)B; d.K = p.Cin; d.N = l.cout; d.has_bias = l.bias; d.order = e.buf.order;
+                d.rows = (int)B; d.K = p.Cin; d.N = l.cout; d.has_bias = l.bias; d.order = e.buf.order; d.bf16 = e.cfg.bf16;
                 run("dense_small_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_dense_small_fwd(d, na, s); });
                 break;
             }
-            run(l.type == HADFL_OP_CONV ? "conv_fwd" : "dense_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_gemm(p, na, s); });
+            run(l.type == HADFL_OP_CONV ? "conv_fwd" : "dense_fwd", gemm_flops(p), gemm_bytes(p), [&] { return gemm(p); });
             break; }
         case HADFL_OP_RELU: run("relu_fwd", 0, 8.0 * q.count, [&] { return launch_relu_fwd(q, na, s); }); break;
         case HADFL_OP_MAXPOOL: run("maxpool_fwd", 0, 4.0 * (B * a.numel() + q.count), [&] { return launch_maxpool_fwd(q, na, s); }); break;
@@ -261,7 +262,7 @@ struct Runner {
         b.chunks = e.bn_chunks[i];
         b.chunk_rows = (b.rows + b.chunks - 1) / b.chunks;
         b.partial = shared(); b.partial_rep = (long long)b.chunks * 2 * a.c;
-        b.order = e.buf.order;
+        b.order = e.buf.order; b.bf16 = e.cfg.bf16;
         return b;
     }
 
@@ -278,7 +279,7 @@ struct Runner {
         const int ot = e.out_tensor[i];          // d(loss)/d(this layer's pre-ReLU output) lives in grad(ot)
         const float* mask0 = (need_din && e.masked[l.in0]) ? act(l.in0) : nullptr;
         EwParams q{};
-        q.order = e.buf.order; q.B = (int)B; q.H = a.h; q.W = a.w; q.C = a.c;
+        q.order = e.buf.order; q.B = (int)B; q.H = a.h; q.W = a.w; q.C = a.c; q.bf16 = e.cfg.bf16;
         q.accumulate = acc0;
         q.mask = mask0; q.mask_rep = e.rep_block;
         if (need_din) { q.out = grad(l.in0); q.out_rep = e.rep_block; }
@@ -291,6 +292,7 @@ struct Runner {
             p.M = p.R * p.S * p.Cin + (l.bias ? 1 : 0); p.N = p.Cout; p.K = (int)(B * p.Ho * p.Wo);
             p.a = act(l.in0); p.a_rep = e.rep_block;
             p.cursor = l.in0 == 0 ? e.buf.cursor : nullptr;
+            p.a_f32 = l.in0 == 0;
             p.dy = grad(ot); p.dy_rep = e.rep_block;
             p.splits = e.splits[i];
             const int64_t mn = (int64_t)p.M * p.N;
@@ -302,7 +304,7 @@ struct Runner {
             } else {
                 p.out = e.buf.grad + l.w_off; p.out_rep = e.plan.row_stride;
             }
-            run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return launch_gemm(p, na, s); });
+            run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return gemm(p); });
             if (p.splits > 1)
                 run("splitk_reduce", 0, 4.0 * mn * (p.splits + 1), [&] { return launch_splitk_reduce(shared(), p.out_split, p.splits, e.buf.grad + l.w_off,
                                                                        e.plan.row_stride, mn, e.buf.order, na, s); });
@@ -314,7 +316,7 @@ struct Runner {
                 d.out = grad(l.in0); d.out_rep = e.rep_block;
                 d.accumulate = acc0;
                 d.mask = mask0; d.mask_rep = e.rep_block;
-                run(l.type == HADFL_OP_CONV ? "conv_dgrad" : "dense_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return launch_gemm(d, na, s); });
+                run(l.type == HADFL_OP_CONV ? "conv_dgrad" : "dense_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return gemm(d); });
             }
             break; }
         case HADFL_OP_RELU:
@@ -369,7 +371,7 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
         lp.logits = r.act(T - 1); lp.logits_rep = e->rep_block;
         lp.dlogits = r.grad(T - 1); lp.dlogits_rep = e->rep_block;
         lp.y = e->buf.y; lp.cursor = e->buf.cursor; lp.n_samples = e->cfg.n_samples; lp.batch = e->cfg.batch;
-        lp.n_classes = e->cfg.n_classes; lp.loss = e->buf.loss; lp.order = e->buf.order;
+        lp.n_classes = e->cfg.n_classes; lp.loss = e->buf.loss; lp.order = e->buf.order; lp.bf16 = e->cfg.bf16;
         r.run("softmax_ce", 0, 8.0 * e->cfg.batch * e->cfg.n_classes, [&] { return launch_softmax_ce(lp, r.na, s); });
         e->grad_written.assign(T, 0);
         e->grad_written[T - 1] = 1;

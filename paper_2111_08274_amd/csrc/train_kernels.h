@@ -29,9 +29,13 @@ struct GemmParams {
     // kDgrad: when set, the written gradient is zeroed where mask <= 0 (mask = the ReLU output stored in the tensor
     // whose gradient is being produced, so the result is the gradient before that fused ReLU)
     const float* mask; long long mask_rep;
+    int a_f32;                    // bf16 kernel only: the activation-side source is the fp32 data set
     const int* order;
 };
 hipError_t launch_gemm(const GemmParams& p, int n_active, hipStream_t s);
+// Same problems with bf16 activations / activation gradients (pointers still typed float*: they are byte bases whose
+// offsets and strides are counted in 4-byte units), fp32 weights rounded to bf16 on the fly, fp32 weight gradients.
+hipError_t launch_gemm_bf16(const GemmParams& p, int n_active, hipStream_t s);
 // out[rep][i] = sum_s partial[g][s][i], s ascending
 hipError_t launch_splitk_reduce(const float* partial, long long split_stride, int splits, float* out, long long out_rep,
                                 long long count, const int* order, int n_active, hipStream_t s);
@@ -41,6 +45,7 @@ struct DenseSmallParams {     // out[m][n] = sum_k x[m][k] w[k][n] + bias[n], N 
     const float* w; long long w_rep;     // weights [K][N] followed by bias [N]
     float* out; long long out_rep;
     int rows, K, N, has_bias;
+    int bf16;
     const int* order;
 };
 hipError_t launch_dense_small_fwd(const DenseSmallParams& p, int n_active, hipStream_t s);
@@ -54,6 +59,7 @@ struct EwParams {     // element-wise / pooling kernels
     int accumulate;
     int relu;                     // forward kernels: apply max(., 0) to the result
     const float* mask; long long mask_rep;   // backward kernels: zero the written gradient where mask <= 0
+    int bf16;                     // tensors are bf16 (strides still in 4-byte units)
     const int* order;
 };
 hipError_t launch_relu_fwd(const EwParams& p, int n_active, hipStream_t s);
@@ -81,6 +87,7 @@ struct BnParams {
     int accumulate;
     int relu;                              // forward: y = max(bn(x), 0)
     const float* mask; long long mask_rep; // backward: zero dx where mask <= 0
+    int bf16;
     const int* order;
 };
 hipError_t launch_bn_fwd(const BnParams& p, int n_active, hipStream_t s);
@@ -91,6 +98,7 @@ struct LossParams {
     float* dlogits; long long dlogits_rep;
     const int* y; const long long* cursor; int n_samples, batch, n_classes;
     float* loss;
+    int bf16;
     const int* order;
 };
 hipError_t launch_softmax_ce(const LossParams& p, int n_active, hipStream_t s);

@@ -12,11 +12,11 @@ def oracle_ops_to_custom(ops):
 
 class Pair:
     def __init__(self, ops, in_shape, n_replicas, n_select, x, y, batch, lr, momentum, ratio, net_name=None,
-                 seed=synth.SELECT_SEED, t_sync=1, init_seed=0, weight_mode=0):
-        self.net = oracle.Net(ops, in_shape)
+                 seed=synth.SELECT_SEED, t_sync=1, init_seed=0, weight_mode=0, bf16=False):
+        self.net = oracle.Net(ops, in_shape, bf16=bf16)
         n_classes = self.net.n_out
         kw = dict(batch=batch, n_samples=x.shape[1], in_shape=in_shape, n_classes=n_classes, lr=lr,
-                  momentum=momentum, t_sync=t_sync, seed=seed, weight_mode=weight_mode)
+                  momentum=momentum, t_sync=t_sync, seed=seed, weight_mode=weight_mode, bf16=int(bf16))
         if net_name is None:
             self.hc = hadfl.make_config(n_replicas, n_select, net="custom", custom_ops=oracle_ops_to_custom(ops), **kw)
         else:
@@ -34,6 +34,15 @@ class Pair:
         d = 0.0
         for k in range(self.N):
             d = max(d, float(np.abs(self.gpu.params(k)[:n].astype(np.float64) - self.cpu.params[k][:n]).max()))
+        return d
+
+    def max_rel_diff(self):
+        """max over replicas of max|w_gpu - w_oracle| / max|w_oracle| over the trainable vector."""
+        n = self.net.m_train
+        d = 0.0
+        for k in range(self.N):
+            ref = self.cpu.params[k][:n]
+            d = max(d, float(np.abs(self.gpu.params(k)[:n].astype(np.float64) - ref).max() / np.abs(ref).max()))
         return d
 
     def local_steps(self):
