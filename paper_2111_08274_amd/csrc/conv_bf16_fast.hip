@@ -1,0 +1,387 @@
+// Lean bf16 kernels for the regular convolution layers of the bf16 configuration (3x3-style "same" convolutions,
+// stride 1, channel counts that are multiples of 32/64): the bulk of the network's multiply-adds.
+//
+// The generic kernel spends ~20 vector-ALU instructions per MFMA on address arithmetic, conversions and a scalar
+// epilogue, which caps the matrix cores near 10 %.  Here everything that does not change along K is computed once:
+//   * weights are kept as two bf16 matrices per layer, refreshed from the fp32 master before every forward pass:
+//       Wf[co][(tap, ci)]  for the forward pass and  Wb[ci][(flipped tap, co)]  for the data gradient, both
+//       K-contiguous, so forward and data gradient are the SAME kernel (a stride-1 data gradient is a convolution
+//       of dY with the flipped, transposed filter) and no conversion or transposition happens in the K loop;
+//   * a thread's pixel offset and its 9-bit tap-validity mask are fixed; per slab only a wave-uniform tap delta is
+//     added; all offsets are 32-bit;
+//   * the MFMA operands are swapped (C^T = B^T A^T), which leaves 4 consecutive output channels in each lane, so
+//     the epilogue stores 8 bytes (bf16) or 16 bytes (fp32) per lane instead of single elements.
+// The weight gradient transposes both operands (pixels are the contraction index) while staging them: a thread
+// takes two consecutive pixels of 8 channels and writes eight 32-bit (k, k+1) pairs.
+#include "train_kernels.h"
+
+namespace hadfl {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef float f16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+
+constexpr int BK = 32;
+constexpr int LDP = 40;      // LDS row pitch in bf16 elements (80 bytes: conflict-free 16-byte operand reads)
+constexpr int BM = 128;
+
+__device__ __forceinline__ u4 ldg16(const char* base, unsigned off) { return *reinterpret_cast<const u4*>(base + off); }
+
+// ---------------------------------------------------------------------------------------------------------------
+// Forward / data-gradient: out[m][n] = sum_k act[pixel(m) + tap(k)][c(k)] * wmat[n][k]
+// ---------------------------------------------------------------------------------------------------------------
+template <int BN, int EPI>     // EPI 0: + bias, optional ReLU, store bf16;  1: optional mask, optional accumulate
+__global__ __launch_bounds__(256) void conv_fast_kernel(FastConvParams p)
+{
+    constexpr int TN = BN / 64;                 // wave grid 2 x 2, wave tile 64 x (BN/2)
+    constexpr int NQB = BN / 64;                // B slots per thread (BN rows x 4 groups of 8 k over 256 threads)
+    __shared__ __attribute__((aligned(16))) __bf16 sA[2][BM][LDP];
+    __shared__ __attribute__((aligned(16))) __bf16 sB[2][BN][LDP];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int rep = p.order[blockIdx.z];
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const char* abase = (const char*)p.a + (long long)rep * p.a_rep * 4;
+    const char* wbase = (const char*)(p.wmat + (long long)rep * p.wmat_rep);
+
+    // ---- loop-invariant addressing ----
+    const int arow = tid & (BM - 1);
+    const int m = m0 + arow;
+    const bool a_ok = m < p.M;
+    const int hw = p.H * p.W;
+    const int bimg = m / hw, rem = m - bimg * hw, y = rem / p.W, x = rem - y * p.W;
+    unsigned tapmask = 0;
+    for (int t = 0; t < p.R * p.S; ++t) {
+        const int r = t / p.S, s = t - r * p.S;
+        const int yy = y + r - p.pad, xx = x + s - p.pad;
+        if (a_ok && yy >= 0 && yy < p.H && xx >= 0 && xx < p.W) tapmask |= 1u << t;
+    }
+    unsigned aoff[2], boff[NQB];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) aoff[q] = (unsigned)(m * p.C + ((tid >> 7) + 2 * q) * 8) * 2u;
+#pragma unroll
+    for (int q = 0; q < NQB; ++q) {
+        const int i = tid + q * 256;
+        boff[q] = (unsigned)((n0 + i % BN) * p.K + (i / BN) * 8) * 2u;
+    }
+    // LDS store offsets (bytes inside one buffer) and operand read bases
+    unsigned sa_st[2], sb_st[NQB];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) sa_st[q] = (unsigned)(arow * LDP + ((tid >> 7) + 2 * q) * 8) * 2u;
+#pragma unroll
+    for (int q = 0; q < NQB; ++q) { const int i = tid + q * 256; sb_st[q] = (unsigned)((i % BN) * LDP + (i / BN) * 8) * 2u; }
+    char* const sAc = reinterpret_cast<char*>(&sA[0][0][0]);
+    char* const sBc = reinterpret_cast<char*>(&sB[0][0][0]);
+    constexpr unsigned A_BUF = BM * LDP * 2, B_BUF = BN * LDP * 2;
+    const unsigned a_rd = (unsigned)((wm * 64 + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
+    const unsigned b_rd = (unsigned)((wn * (BN / 2) + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
+
+    u4 ra[2], rb[NQB];
+    int tap = 0, c0 = 0;                         // wave-uniform position of the next slab to load
+    auto load_tiles = [&]() {
+        const int r = tap / p.S, s = tap - r * p.S;
+        const int delta = (((r - p.pad) * p.W + (s - p.pad)) * p.C + c0) * 2;       // bytes, may be negative
+        const bool valid = (tapmask >> tap) & 1u;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            u4 v = {0u, 0u, 0u, 0u};
+            if (valid) v = ldg16(abase, aoff[q] + (unsigned)delta);
+            ra[q] = v;
+        }
+        const unsigned kb = (unsigned)(tap * p.C + c0) * 2u;
+#pragma unroll
+        for (int q = 0; q < NQB; ++q) rb[q] = ldg16(wbase, boff[q] + kb);
+        c0 += BK;
+        if (c0 == p.C) { c0 = 0; ++tap; }
+    };
+    auto store_tiles = [&](int buf) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) *reinterpret_cast<u4*>(sAc + buf * A_BUF + sa_st[q]) = ra[q];
+#pragma unroll
+        for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sBc + buf * B_BUF + sb_st[q]) = rb[q];
+    };
+
+    f16 acc[2][TN];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nslab = p.K / BK;
+    load_tiles();
+    store_tiles(0);
+    __syncthreads();
+    for (int t = 0; t < nslab; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < nslab) load_tiles();
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 a[2], b[TN];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sAc + buf * A_BUF + a_rd + (i * 32 * LDP + ks * 16) * 2);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sBc + buf * B_BUF + b_rd + (j * 32 * LDP + ks * 16) * 2);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)      // operands swapped: the accumulator holds the transposed tile
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+        }
+        if (t + 1 < nslab) store_tiles(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane holds output pixel (lane & 31) and channels 8*g + 4*(lane >> 5) + {0..3}, g = 0..3 ----
+    char* obase = (char*)p.out + (long long)rep * p.out_rep * 4;
+    const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
+    const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int mm = m0 + wm * 64 + i * 32 + (lane & 31);
+        if (mm >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + wn * (BN / 2) + j * 32 + 8 * g + 4 * (lane >> 5);
+                const unsigned o = (unsigned)(mm * p.N + n) * 2u;
+                f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                if (EPI == 0) {
+                    if (bias) v += *reinterpret_cast<const f4*>(bias + n);
+                    if (p.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
+                } else {
+                    if (mask) {
+                        const bf16x4 mk = *reinterpret_cast<const bf16x4*>(mask + o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) if (!((float)mk[e] > 0.f)) v[e] = 0.f;
+                    }
+                    if (p.accumulate) {
+                        const bf16x4 old = *reinterpret_cast<const bf16x4*>(obase + o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += (float)old[e];
+                    }
+                }
+                bf16x4 r;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) r[e] = (__bf16)v[e];
+                *reinterpret_cast<bf16x4*>(obase + o) = r;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Weight gradient: dW[m = (tap, ci) | bias row][n = co] = sum over pixels k of x[k + tap][ci] * dy[k][co]
+// ---------------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned perm_lo(unsigned a, unsigned b) { return (a & 0xffffu) | (b << 16); }
+__device__ __forceinline__ unsigned perm_hi(unsigned a, unsigned b) { return (a >> 16) | (b & 0xffff0000u); }
+
+template <int BN>
+__global__ __launch_bounds__(256) void wgrad_fast_kernel(FastWgradParams p)
+{
+    constexpr int TN = BN / 64;
+    constexpr int NQB = BN / 128 > 0 ? BN / 128 : 1;     // B octet slots per thread: 16 k-pairs x BN/8 octets over 256 threads
+    constexpr bool B_HALF = BN == 64;                    // BN = 64: only half of the threads stage B
+    __shared__ __attribute__((aligned(16))) __bf16 sA[2][BM][LDP];
+    __shared__ __attribute__((aligned(16))) __bf16 sB[2][BN][LDP];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int g = blockIdx.z;
+    const int rep = p.order[g];
+    const int tiles_n = p.N / BN;
+    const int m0 = (blockIdx.x / tiles_n) * BM, n0 = (blockIdx.x % tiles_n) * BN;
+    const int split = blockIdx.y;
+    const int kbeg = split * p.kchunk, kend = min(p.K, kbeg + p.kchunk);
+    const char* xbase = (const char*)p.x + (long long)rep * p.x_rep * 4;
+    const char* dbase = (const char*)p.dy + (long long)rep * p.dy_rep * 4;
+
+    // A slot of this thread: k pair kp, 8 rows starting at am (one filter tap, 8 consecutive input channels)
+    const int kp = tid & 15, oct = tid >> 4;
+    const int am = m0 + oct * 8;
+    const int mw = p.R * p.S * p.C;
+    const int atap = am / p.C, aci = am - atap * p.C;
+    const int ar = atap / p.S, as = atap - ar * p.S;
+    const int ady = ar - p.pad, adx = as - p.pad;
+    const int a_kind = am < mw ? 0 : (am == mw && p.has_bias ? 1 : 2);      // 0 data, 1 bias row of ones, 2 nothing
+    const int a_shift = ((ady * p.W + adx) * p.C + aci) * 2;                // byte offset of the tap relative to pixel k
+    const unsigned sa_st = (unsigned)((oct * 8) * LDP + 2 * kp) * 2u;
+    unsigned sb_st[NQB], bnoff[NQB];
+#pragma unroll
+    for (int q = 0; q < NQB; ++q) {
+        const int o = (tid >> 4) + q * 16;
+        sb_st[q] = (unsigned)((o * 8) * LDP + 2 * kp) * 2u;
+        bnoff[q] = (unsigned)(n0 + o * 8) * 2u;
+    }
+    char* const sAc = reinterpret_cast<char*>(&sA[0][0][0]);
+    char* const sBc = reinterpret_cast<char*>(&sB[0][0][0]);
+    constexpr unsigned A_BUF = BM * LDP * 2, B_BUF = BN * LDP * 2;
+    const unsigned a_rd = (unsigned)((wm * 64 + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
+    const unsigned b_rd = (unsigned)((wn * (BN / 2) + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
+
+    u4 ra[2], rb[NQB][2];          // rows k and k+1 of the slot
+    auto load_tiles = [&](int k0) {
+        const int k = k0 + 2 * kp;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int kk = k + h;
+            u4 v = {0u, 0u, 0u, 0u};
+            if (kk < kend) {
+                if (a_kind == 0) {
+                    const int yy = ((kk >> p.w_shift) & (p.H - 1)) + ady, xx = (kk & (p.W - 1)) + adx;
+                    if (yy >= 0 && yy < p.H && xx >= 0 && xx < p.W)
+                        v = ldg16(xbase, (unsigned)(kk * p.C * 2 + a_shift));
+                } else if (a_kind == 1) {
+                    v[0] = 0x3f80u;                 // bf16 1.0 in the first of the 8 rows
+                }
+            }
+            ra[h] = v;
+#pragma unroll
+            for (int q = 0; q < NQB; ++q) {
+                u4 w = {0u, 0u, 0u, 0u};
+                if (kk < kend && (!B_HALF || tid < 128)) w = ldg16(dbase, (unsigned)(kk * p.N) * 2u + bnoff[q]);
+                rb[q][h] = w;
+            }
+        }
+    };
+    auto store_tiles = [&](int buf) {
+        // element e of row k sits in the low half, of row k+1 in the high half of one 32-bit word
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            *reinterpret_cast<unsigned*>(sAc + buf * A_BUF + sa_st + (2 * e) * LDP * 2) = perm_lo(ra[0][e], ra[1][e]);
+            *reinterpret_cast<unsigned*>(sAc + buf * A_BUF + sa_st + (2 * e + 1) * LDP * 2) = perm_hi(ra[0][e], ra[1][e]);
+        }
+        if (!B_HALF || tid < 128) {
+#pragma unroll
+            for (int q = 0; q < NQB; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    *reinterpret_cast<unsigned*>(sBc + buf * B_BUF + sb_st[q] + (2 * e) * LDP * 2) = perm_lo(rb[q][0][e], rb[q][1][e]);
+                    *reinterpret_cast<unsigned*>(sBc + buf * B_BUF + sb_st[q] + (2 * e + 1) * LDP * 2) = perm_hi(rb[q][0][e], rb[q][1][e]);
+                }
+        }
+    };
+
+    f16 acc[2][TN];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nslab = (kend - kbeg + BK - 1) / BK;
+    if (nslab > 0) { load_tiles(kbeg); store_tiles(0); }
+    __syncthreads();
+    for (int t = 0; t < nslab; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < nslab) load_tiles(kbeg + (t + 1) * BK);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 a[2], b[TN];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sAc + buf * A_BUF + a_rd + (i * 32 * LDP + ks * 16) * 2);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sBc + buf * B_BUF + b_rd + (j * 32 * LDP + ks * 16) * 2);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+        }
+        if (t + 1 < nslab) store_tiles(buf ^ 1);
+        __syncthreads();
+    }
+
+    float* obase = (p.splits > 1) ? p.out + (long long)g * p.out_rep + (long long)split * p.out_split
+                                  : p.out + (long long)rep * p.out_rep;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int mm = m0 + wm * 64 + i * 32 + (lane & 31);
+        if (mm >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * (BN / 2) + j * 32 + 8 * q + 4 * (lane >> 5);
+                const f4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                *reinterpret_cast<f4*>(obase + (long long)mm * p.N + n) = v;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// Weight preparation: fp32 master W[tap][ci][co] -> Wf[co][tap*C + ci] and Wb[ci][(T-1-tap)*N + co], both bf16.
+// Block (32, 8) handles one tap and a 32 x 32 (ci, co) tile.
+// ---------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void weight_prep_kernel(WeightPrepParams p)
+{
+    __shared__ float tile[32][33];
+    const int rep = p.order[blockIdx.z];
+    const int taps = p.taps;
+    const int tap = blockIdx.y % taps, cot = blockIdx.y / taps;
+    const int ci0 = blockIdx.x * 32, co0 = cot * 32;
+    const float* w = p.w + (long long)rep * p.w_rep + ((long long)tap * p.C) * p.N;
+    __bf16* wf = p.wf + (long long)rep * p.wbf_rep;
+    __bf16* wb = p.wb + (long long)rep * p.wbf_rep;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int K = taps * p.C, Kb = taps * p.N;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int ci = ci0 + ty + 8 * r;
+        const float v = w[(long long)ci * p.N + co0 + tx];
+        tile[ty + 8 * r][tx] = v;
+        wb[(long long)ci * Kb + (taps - 1 - tap) * p.N + co0 + tx] = (__bf16)v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int co = co0 + ty + 8 * r;
+        wf[(long long)co * K + tap * p.C + ci0 + tx] = (__bf16)tile[tx][ty + 8 * r];
+    }
+}
+
+}  // namespace
+
+hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s)
+{
+    if (n_active < 1) return hipSuccess;
+    const int bn = (p.N % 128 == 0) ? 128 : 64;
+    const dim3 grid((unsigned)((p.M + BM - 1) / BM), (unsigned)(p.N / bn), (unsigned)n_active), block(256);
+    if (bn == 128) {
+        if (epi == 0) hipLaunchKernelGGL((conv_fast_kernel<128, 0>), grid, block, 0, s, p);
+        else hipLaunchKernelGGL((conv_fast_kernel<128, 1>), grid, block, 0, s, p);
+    } else {
+        if (epi == 0) hipLaunchKernelGGL((conv_fast_kernel<64, 0>), grid, block, 0, s, p);
+        else hipLaunchKernelGGL((conv_fast_kernel<64, 1>), grid, block, 0, s, p);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_wgrad_fast(const FastWgradParams& p, int n_active, hipStream_t s)
+{
+    if (n_active < 1) return hipSuccess;
+    const int bn = (p.N % 128 == 0) ? 128 : 64;
+    const dim3 grid((unsigned)(((p.M + BM - 1) / BM) * (p.N / bn)), (unsigned)p.splits, (unsigned)n_active), block(256);
+    if (bn == 128) hipLaunchKernelGGL(wgrad_fast_kernel<128>, grid, block, 0, s, p);
+    else hipLaunchKernelGGL(wgrad_fast_kernel<64>, grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_weight_prep(const WeightPrepParams& p, int n_active, hipStream_t s)
+{
+    if (n_active < 1) return hipSuccess;
+    const dim3 grid((unsigned)(p.C / 32), (unsigned)(p.taps * (p.N / 32)), (unsigned)n_active), block(256);
+    hipLaunchKernelGGL(weight_prep_kernel, grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace hadfl

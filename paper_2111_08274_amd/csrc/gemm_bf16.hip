@@ -156,9 +156,35 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_bf16_kernel(GemmParams p)
         if (MODE == kDgrad) { a_y = a_y * p.stride + g.d_ph; a_x = a_x * p.stride + g.d_pw; }
     }
 
+    // when the channel count is a multiple of the slab, a slab lies inside one filter tap and the tap arithmetic is
+    // wave-uniform (done once per slab, not per slot)
+    const bool slab_tap = (MODE == kFwd) ? (p.Cin % BK == 0) : (MODE == kDgrad) ? (p.Cout % BK == 0) : false;
+    // weight-gradient A rows of this thread's pair slots: (tap, channel) of the first of 4 rows, fixed over the K loop
+    int wa_r[NQA], wa_s[NQA], wa_c[NQA];
+    if (MODE == kWgrad) {
+#pragma unroll
+        for (int q = 0; q < NQA; ++q) {
+            const int m = m0 + ((tid + q * NT) / 16) * 4;
+            const int tap = m / p.Cin;
+            wa_c[q] = m - tap * p.Cin; wa_r[q] = tap / p.S; wa_s[q] = tap - wa_r[q] * p.S;
+        }
+    }
+
     u4 ra[NQA], rb[NQB];      // staged slot contents: 8 bf16 each
 
     auto load_tiles = [&](int k0) {
+        int u_c0 = 0, u_dy = 0, u_dx = 0, u_tap = 0;      // slab-uniform tap (valid when slab_tap)
+        if (slab_tap) {
+            if (MODE == kFwd) {
+                const int tap = k0 / p.Cin; u_c0 = k0 - tap * p.Cin;
+                const int r = tap / p.S; u_dy = r - p.pad; u_dx = tap - r * p.S - p.pad;
+            } else {
+                const int t = k0 / p.Cout; u_c0 = k0 - t * p.Cout;
+                const int ir = t / g.d_ns, is = t - ir * g.d_ns;
+                u_dy = p.pad - (g.d_r0 + ir * p.stride); u_dx = p.pad - (g.d_s0 + is * p.stride);
+                u_tap = (g.d_r0 + ir * p.stride) * p.S + g.d_s0 + is * p.stride;
+            }
+        }
         // ------------------------------------------------ A ------------------------------------------------
 #pragma unroll
         for (int q = 0; q < NQA; ++q) {
@@ -170,13 +196,23 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_bf16_kernel(GemmParams p)
                     if (vecA) {
                         if (a_ok && k < g.kend) {
                             if (MODE == kFwd) {
-                                const int tap = k / p.Cin, c = k - tap * p.Cin, r = tap / p.S, s = tap - r * p.S;
-                                const int yy = a_y * p.stride - p.pad + r, xx = a_x * p.stride - p.pad + s;
+                                int c, dy, dx;
+                                if (slab_tap) { c = u_c0 + kq * 8; dy = u_dy; dx = u_dx; }
+                                else {
+                                    const int tap = k / p.Cin, r = tap / p.S;
+                                    c = k - tap * p.Cin; dy = r - p.pad; dx = tap - r * p.S - p.pad;
+                                }
+                                const int yy = a_y * p.stride + dy, xx = a_x * p.stride + dx;
                                 if (yy >= 0 && yy < p.H && xx >= 0 && xx < p.W)
                                     v = *reinterpret_cast<const u4*>((const __bf16*)abase + (((long long)a_b * p.H + yy) * p.W + xx) * p.Cin + c);
                             } else {
-                                const int t = k / p.Cout, c = k - t * p.Cout, ir = t / g.d_ns, is = t - ir * g.d_ns;
-                                const int ty = a_y + p.pad - (g.d_r0 + ir * p.stride), tx = a_x + p.pad - (g.d_s0 + is * p.stride);
+                                int c, dy, dx;
+                                if (slab_tap) { c = u_c0 + kq * 8; dy = u_dy; dx = u_dx; }
+                                else {
+                                    const int t = k / p.Cout, ir = t / g.d_ns, is = t - ir * g.d_ns;
+                                    c = k - t * p.Cout; dy = p.pad - (g.d_r0 + ir * p.stride); dx = p.pad - (g.d_s0 + is * p.stride);
+                                }
+                                const int ty = a_y + dy, tx = a_x + dx;
                                 const int yo = ty / p.stride, xo = tx / p.stride;
                                 if (ty >= 0 && tx >= 0 && yo < p.Ho && xo < p.Wo)
                                     v = *reinterpret_cast<const u4*>((const __bf16*)abase + (((long long)a_b * p.Ho + yo) * p.Wo + xo) * p.Cout + c);
@@ -193,7 +229,7 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_bf16_kernel(GemmParams p)
                     const int kp = i % 16, rq = i / 16, k = k0 + 2 * kp, m = m0 + rq * 4;
                     const int mw = p.R * p.S * p.Cin;
                     if (vecA && m < mw) {
-                        const int tap = m / p.Cin, c = m - tap * p.Cin, r = tap / p.S, s = tap - r * p.S;
+                        const int c = wa_c[q], r = wa_r[q], s = wa_s[q];
                         bf16x4 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
 #pragma unroll
                         for (int h = 0; h < 2; ++h) {
@@ -238,8 +274,12 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_bf16_kernel(GemmParams p)
                     const int nl = i % BN, kq = i / BN, k = k0 + kq * 8, n = n0 + nl;
                     if (vecB) {
                         if (n < p.N && k < g.kend) {
-                            const int t = k / p.Cout, c = k - t * p.Cout, ir = t / g.d_ns, is = t - ir * g.d_ns;
-                            const int tap = (g.d_r0 + ir * p.stride) * p.S + g.d_s0 + is * p.stride;
+                            int c, tap;
+                            if (slab_tap) { c = u_c0 + kq * 8; tap = u_tap; }
+                            else {
+                                const int t = k / p.Cout, ir = t / g.d_ns, is = t - ir * g.d_ns;
+                                c = k - t * p.Cout; tap = (g.d_r0 + ir * p.stride) * p.S + g.d_s0 + is * p.stride;
+                            }
                             const float* src = wbase + ((long long)tap * p.Cin + n) * p.Cout + c;
                             const f4 x0 = *reinterpret_cast<const f4*>(src), x1 = *reinterpret_cast<const f4*>(src + 4);
                             v = u4{pack2(x0[0], x0[1]), pack2(x0[2], x0[3]), pack2(x1[0], x1[1]), pack2(x1[2], x1[3])};

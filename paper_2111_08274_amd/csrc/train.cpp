@@ -35,6 +35,11 @@ public:
     std::vector<char> skip;               // per layer: fused away
     std::vector<char> fused_relu;         // per layer: applies max(., 0) in its store
     std::vector<char> masked;             // per tensor: gradient writers must apply the (value > 0) mask
+    // bf16 configuration: regular convolution layers keep two bf16 weight matrices (forward / data-gradient order)
+    std::vector<char> fast;               // per layer: the lean bf16 kernels apply
+    std::vector<int64_t> wf_off, wb_off;  // per layer: offsets (bf16 elements) inside one replica's bf16 weight block
+    int64_t wbf_rep = 0;                  // bf16 elements per replica
+    int64_t wbf_off = 0;                  // start of the bf16 weight region inside `work` (floats)
 };
 
 namespace {
@@ -45,7 +50,12 @@ struct Layout {
     std::vector<int64_t> act_off, grad_off, saved_off;
     std::vector<int> splits, bn_chunks;
     int64_t rep_block = 0, shared_floats = 0;
+    std::vector<char> fast;
+    std::vector<int64_t> wf_off, wb_off;
+    int64_t wbf_rep = 0;
 };
+
+bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
 int64_t up64(int64_t v) { return (v + 63) / 64 * 64; }
 
@@ -85,6 +95,21 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
     }
     L.rep_block = up64(off);
     L.shared_floats = up64(shared);
+    L.fast.assign(plan.layers.size(), 0); L.wf_off.assign(plan.layers.size(), -1); L.wb_off.assign(plan.layers.size(), -1);
+    if (cfg.bf16) {
+        int64_t woff = 0;
+        for (size_t i = 0; i < plan.layers.size(); ++i) {
+            const Layer& l = plan.layers[i];
+            if (l.type != HADFL_OP_CONV || l.in0 == 0) continue;
+            const TensorShape a = plan.tensors[l.in0];
+            if (l.stride != 1 || 2 * l.pad != l.k - 1 || l.k * l.k > 32) continue;
+            if (a.c % 64 != 0 || l.cout % 64 != 0 || !is_pow2(a.h) || !is_pow2(a.w)) continue;
+            L.fast[i] = 1;
+            L.wf_off[i] = woff; woff += up64(l.w_count);
+            L.wb_off[i] = woff; woff += up64(l.w_count);
+        }
+        L.wbf_rep = woff;
+    }
     return L;
 }
 
@@ -94,7 +119,7 @@ int64_t train_work_floats(const hadfl_config& cfg, const NetPlan& plan)
 {
     if (cfg.net == HADFL_NET_NONE) return 0;
     const Layout L = make_layout(cfg, plan);
-    return L.rep_block * cfg.n_replicas + L.shared_floats;
+    return L.rep_block * cfg.n_replicas + L.shared_floats + up64(L.wbf_rep * cfg.n_replicas / 2 + 64);
 }
 
 hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const TrainBuffers& buf,
@@ -114,6 +139,8 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
     e->rep_block = L.rep_block;
     e->shared_off = L.rep_block * cfg.n_replicas;
     e->shared_floats = L.shared_floats;
+    e->fast = L.fast; e->wf_off = L.wf_off; e->wb_off = L.wb_off; e->wbf_rep = L.wbf_rep;
+    e->wbf_off = e->shared_off + L.shared_floats;
     {
         const int nl = (int)plan.layers.size(), T = (int)plan.tensors.size();
         e->out_tensor.resize(nl); e->skip.assign(nl, 0); e->fused_relu.assign(nl, 0); e->masked.assign(T, 0);
@@ -150,6 +177,22 @@ struct Runner {
     float* actw(int t) const { return e.buf.work + e.act_off[t]; }
     float* grad(int t) const { return e.buf.work + e.grad_off[t]; }
     float* shared() const { return e.buf.work + e.shared_off; }
+    __bf16* wbf() const { return reinterpret_cast<__bf16*>(e.buf.work + e.wbf_off); }
+
+    // bf16 configuration: refresh the bf16 weight matrices of the regular convolution layers from the fp32 master
+    void prepare_weights()
+    {
+        for (size_t i = 0; i < e.plan.layers.size(); ++i) {
+            if (!e.fast[i]) continue;
+            cur_layer = (int)i;
+            const Layer& l = e.plan.layers[i];
+            WeightPrepParams w{};
+            w.w = e.buf.replicas + l.w_off; w.w_rep = e.plan.row_stride;
+            w.wf = wbf() + e.wf_off[i]; w.wb = wbf() + e.wb_off[i]; w.wbf_rep = e.wbf_rep;
+            w.C = e.plan.tensors[l.in0].c; w.N = l.cout; w.taps = l.k * l.k; w.order = e.buf.order;
+            run("weight_prep", 0, 8.0 * l.w_count, [&] { return launch_weight_prep(w, na, s); });
+        }
+    }
 
     // flops / bytes: algorithmic work of the launch for all active replicas (reported by the profiler)
     template <typename F> void run(const char* name, double flops, double bytes, F&& f)
@@ -223,6 +266,18 @@ struct Runner {
             p.a_f32 = l.in0 == 0;
             p.out = actw(ot); p.out_rep = e.rep_block;
             p.relu = e.fused_relu[i];
+            if (e.fast[i]) {
+                FastConvParams f{};
+                f.B = p.B; f.H = p.H; f.W = p.W; f.C = p.Cin; f.N = p.Cout; f.R = p.R; f.S = p.S; f.pad = p.pad;
+                f.M = p.M; f.K = p.K;
+                f.a = act(l.in0); f.a_rep = e.rep_block;
+                f.wmat = wbf() + e.wf_off[i]; f.wmat_rep = e.wbf_rep;
+                f.out = actw(ot); f.out_rep = e.rep_block;
+                f.bias = l.bias ? e.buf.replicas + l.b_off : nullptr; f.bias_rep = e.plan.row_stride;
+                f.relu = p.relu; f.order = e.buf.order;
+                run("conv_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_conv_fast(f, 0, na, s); });
+                break;
+            }
             if (l.type == HADFL_OP_DENSE && l.cout <= 16 && l.in0 != 0 && !p.relu) {
                 DenseSmallParams d{};
                 d.x = act(l.in0); d.x_rep = e.rep_block; d.w = p.w; d.w_rep = p.w_rep;
@@ -304,6 +359,14 @@ struct Runner {
             } else {
                 p.out = e.buf.grad + l.w_off; p.out_rep = e.plan.row_stride;
             }
+            if (e.fast[i]) {
+                FastWgradParams f{};
+                f.B = p.B; f.H = p.H; f.W = p.W; f.C = p.Cin; f.N = p.Cout; f.R = p.R; f.S = p.S; f.pad = p.pad;
+                f.M = p.M; f.K = p.K; f.kchunk = p.kchunk; f.splits = p.splits; f.w_shift = p.w_shift; f.has_bias = l.bias;
+                f.x = act(l.in0); f.x_rep = e.rep_block; f.dy = grad(ot); f.dy_rep = e.rep_block;
+                f.out = p.out; f.out_rep = p.out_rep; f.out_split = p.out_split; f.order = e.buf.order;
+                run("conv_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return launch_wgrad_fast(f, na, s); });
+            } else
             run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return gemm(p); });
             if (p.splits > 1)
                 run("splitk_reduce", 0, 4.0 * mn * (p.splits + 1), [&] { return launch_splitk_reduce(shared(), p.out_split, p.splits, e.buf.grad + l.w_off,
@@ -316,6 +379,16 @@ struct Runner {
                 d.out = grad(l.in0); d.out_rep = e.rep_block;
                 d.accumulate = acc0;
                 d.mask = mask0; d.mask_rep = e.rep_block;
+                if (e.fast[i]) {
+                    FastConvParams f{};
+                    f.B = d.B; f.H = d.H; f.W = d.W; f.C = d.Cout; f.N = d.Cin; f.R = d.R; f.S = d.S; f.pad = d.R - 1 - d.pad;
+                    f.M = d.M; f.K = d.K;
+                    f.a = grad(ot); f.a_rep = e.rep_block;
+                    f.wmat = wbf() + e.wb_off[i]; f.wmat_rep = e.wbf_rep;
+                    f.out = grad(l.in0); f.out_rep = e.rep_block;
+                    f.mask = mask0; f.mask_rep = e.rep_block; f.accumulate = acc0; f.order = e.buf.order;
+                    run("conv_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return launch_conv_fast(f, 1, na, s); });
+                } else
                 run(l.type == HADFL_OP_CONV ? "conv_dgrad" : "dense_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return gemm(d); });
             }
             break; }
@@ -366,6 +439,7 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
     const int T = (int)e->plan.tensors.size();
     for (int step = 0; step < e->e_max && r.rc == hipSuccess; ++step) {
         r.na = e->n_active[step];
+        if (e->cfg.bf16) r.prepare_weights();
         for (size_t i = 0; i < e->plan.layers.size(); ++i) r.forward_layer(i);
         LossParams lp{};
         lp.logits = r.act(T - 1); lp.logits_rep = e->rep_block;

@@ -40,6 +40,37 @@ hipError_t launch_gemm_bf16(const GemmParams& p, int n_active, hipStream_t s);
 hipError_t launch_splitk_reduce(const float* partial, long long split_stride, int splits, float* out, long long out_rep,
                                 long long count, const int* order, int n_active, hipStream_t s);
 
+// ---- lean bf16 kernels for regular stride-1 "same" convolutions (conv_bf16_fast.hip) ----
+struct FastConvParams {      // out[m][n] = sum_k act[pixel(m) + tap(k)][c(k)] * wmat[n][k]; M = B*H*W, K = R*S*C
+    int B, H, W, C, N, R, S, pad, M, K;
+    const void* a; long long a_rep;            // bf16 activations (forward) or output gradient (data gradient)
+    const __bf16* wmat; long long wmat_rep;    // bf16 [N][K], per-replica stride in elements
+    void* out; long long out_rep;              // bf16 [M][N]
+    const float* bias; long long bias_rep;     // forward: fp32 bias inside the replica rows, or null
+    int relu;
+    const void* mask; long long mask_rep; int accumulate;   // data gradient
+    const int* order;
+};
+// epi 0: forward (+bias, ReLU); epi 1: data gradient (mask, accumulate).  Needs C % 32 == 0 and N % 64 == 0.
+hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s);
+
+struct FastWgradParams {     // dW[(tap, ci) | bias row][co] over pixels; needs C % 8 == 0, N % 64 == 0, H, W powers of two
+    int B, H, W, C, N, R, S, pad, M, K, kchunk, splits, w_shift, has_bias;
+    const void* x; long long x_rep;
+    const void* dy; long long dy_rep;
+    float* out; long long out_rep, out_split;
+    const int* order;
+};
+hipError_t launch_wgrad_fast(const FastWgradParams& p, int n_active, hipStream_t s);
+
+struct WeightPrepParams {    // fp32 W[tap][C][N] -> bf16 Wf[N][tap*C + ci] and Wb[C][(taps-1-tap)*N + co]
+    const float* w; long long w_rep;
+    __bf16* wf; __bf16* wb; long long wbf_rep;
+    int C, N, taps;
+    const int* order;
+};
+hipError_t launch_weight_prep(const WeightPrepParams& p, int n_active, hipStream_t s);
+
 struct DenseSmallParams {     // out[m][n] = sum_k x[m][k] w[k][n] + bias[n], N <= 16
     const float* x; long long x_rep;
     const float* w; long long w_rep;     // weights [K][N] followed by bias [N]

@@ -41,6 +41,51 @@ def test_layer_kinds_bf16(name):
     p.close()
 
 
+def _regular_cases():
+    """Layers wide enough (channels multiple of 64, power-of-two images) for the lean bf16 convolution kernels."""
+    c = {}
+    b = nets._Builder()
+    t = b.relu(b.conv(0, 64))
+    b.dense(b.relu(b.conv(t, 64)), 5)
+    c["conv64_bias_relu"] = (b.array(), (8, 8, 3), 8)
+    b = nets._Builder()
+    t = b.relu(b.bn(b.conv(0, 64)))
+    t = b.maxpool(b.relu(b.bn(b.conv(t, 64))))
+    t = b.maxpool(b.relu(b.bn(b.conv(t, 128))))
+    b.dense(t, 5)
+    c["vgg_block_64_128"] = (b.array(), (8, 8, 3), 8)
+    b = nets._Builder()
+    t = b.relu(b.bn(b.conv(0, 64, bias=False)))
+    u = b.bn(b.conv(b.relu(b.bn(b.conv(t, 64, bias=False))), 64, bias=False))
+    b.dense(b.gap(b.relu(b.add(u, t))), 5)
+    c["residual64"] = (b.array(), (4, 8, 3), 6)
+    b = nets._Builder()
+    t = b.relu(b.conv(0, 128, k=1, pad=0))
+    b.dense(b.relu(b.conv(t, 192, k=1, pad=0)), 5)          # 1x1 "same" convolution, N = 192 -> 64-wide tiles
+    c["conv1x1_128_192"] = (b.array(), (4, 4, 3), 10)
+    return c
+
+
+REGULAR = _regular_cases()
+
+
+@pytest.mark.parametrize("name", sorted(REGULAR))
+def test_regular_layers_bf16_lean_kernels(name):
+    ops, shape, batch = REGULAR[name]
+    N, n = 3, batch * 3
+    net = oracle.Net(ops, shape)
+    x, y = _data(N, n, shape, net.n_out, seed=len(name))
+    p = Pair(ops, shape, N, 2, x, y, batch, 0.01, 0.9, [1, 3, 2], bf16=True)
+    p.local_steps()
+    d = p.max_rel_diff()
+    print(name, "bf16 rel", d, "loss", p.gpu.losses(), p.cpu.loss, flush=True)
+    assert d <= REL, (name, d)
+    p.select_aggregate(0)
+    p.local_steps()
+    assert p.max_rel_diff() <= REL
+    p.close()
+
+
 def _narrow_vgg():
     b = nets._Builder()
     t = 0
