@@ -35,23 +35,24 @@ __device__ __forceinline__ u4 ldg16(const char* base, unsigned off) { return *re
 // ---------------------------------------------------------------------------------------------------------------
 // Forward / data-gradient: out[m][n] = sum_k act[pixel(m) + tap(k)][c(k)] * wmat[n][k]
 // ---------------------------------------------------------------------------------------------------------------
-template <int BN, int EPI>     // EPI 0: + bias, optional ReLU, store bf16;  1: optional mask, optional accumulate
-__global__ __launch_bounds__(256) void conv_fast_kernel(FastConvParams p)
+template <int BMT, int BN, int EPI>     // EPI 0: + bias, optional ReLU, store bf16;  1: optional mask, optional accumulate
+__global__ __launch_bounds__(256, 2) void conv_fast_kernel(FastConvParams p)
 {
-    constexpr int TN = BN / 64;                 // wave grid 2 x 2, wave tile 64 x (BN/2)
-    constexpr int NQB = BN / 64;                // B slots per thread (BN rows x 4 groups of 8 k over 256 threads)
-    __shared__ __attribute__((aligned(16))) __bf16 sA[2][BM][LDP];
+    constexpr int TM = BMT / 64, TN = BN / 64;  // wave grid 2 x 2, wave tile (BMT/2) x (BN/2)
+    constexpr int NQA = BMT / 64;               // A slots per thread (BMT rows x 4 groups of 8 k over 256 threads)
+    constexpr int NQB = BN / 64;
+    __shared__ __attribute__((aligned(16))) __bf16 sA[2][BMT][LDP];
     __shared__ __attribute__((aligned(16))) __bf16 sB[2][BN][LDP];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int rep = p.order[blockIdx.z];
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int m0 = blockIdx.x * BMT, n0 = blockIdx.y * BN;
     const char* abase = (const char*)p.a + (long long)rep * p.a_rep * 4;
     const char* wbase = (const char*)(p.wmat + (long long)rep * p.wmat_rep);
 
-    // ---- loop-invariant addressing ----
-    const int arow = tid & (BM - 1);
+    // ---- loop-invariant addressing (every A slot of a thread lies in the same row) ----
+    const int arow = tid % BMT;
     const int m = m0 + arow;
     const bool a_ok = m < p.M;
     const int hw = p.H * p.W;
@@ -62,34 +63,33 @@ __global__ __launch_bounds__(256) void conv_fast_kernel(FastConvParams p)
         const int yy = y + r - p.pad, xx = x + s - p.pad;
         if (a_ok && yy >= 0 && yy < p.H && xx >= 0 && xx < p.W) tapmask |= 1u << t;
     }
-    unsigned aoff[2], boff[NQB];
+    unsigned aoff[NQA], boff[NQB], sa_st[NQA], sb_st[NQB];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) aoff[q] = (unsigned)(m * p.C + ((tid >> 7) + 2 * q) * 8) * 2u;
+    for (int q = 0; q < NQA; ++q) {
+        const int kq = (tid + q * 256) / BMT;
+        aoff[q] = (unsigned)(m * p.C + kq * 8) * 2u;
+        sa_st[q] = (unsigned)(arow * LDP + kq * 8) * 2u;
+    }
 #pragma unroll
     for (int q = 0; q < NQB; ++q) {
         const int i = tid + q * 256;
         boff[q] = (unsigned)((n0 + i % BN) * p.K + (i / BN) * 8) * 2u;
+        sb_st[q] = (unsigned)((i % BN) * LDP + (i / BN) * 8) * 2u;
     }
-    // LDS store offsets (bytes inside one buffer) and operand read bases
-    unsigned sa_st[2], sb_st[NQB];
-#pragma unroll
-    for (int q = 0; q < 2; ++q) sa_st[q] = (unsigned)(arow * LDP + ((tid >> 7) + 2 * q) * 8) * 2u;
-#pragma unroll
-    for (int q = 0; q < NQB; ++q) { const int i = tid + q * 256; sb_st[q] = (unsigned)((i % BN) * LDP + (i / BN) * 8) * 2u; }
     char* const sAc = reinterpret_cast<char*>(&sA[0][0][0]);
     char* const sBc = reinterpret_cast<char*>(&sB[0][0][0]);
-    constexpr unsigned A_BUF = BM * LDP * 2, B_BUF = BN * LDP * 2;
-    const unsigned a_rd = (unsigned)((wm * 64 + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
+    constexpr unsigned A_BUF = BMT * LDP * 2, B_BUF = BN * LDP * 2;
+    const unsigned a_rd = (unsigned)((wm * (BMT / 2) + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
     const unsigned b_rd = (unsigned)((wn * (BN / 2) + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
 
-    u4 ra[2], rb[NQB];
+    u4 ra[NQA], rb[NQB];
     int tap = 0, c0 = 0;                         // wave-uniform position of the next slab to load
     auto load_tiles = [&]() {
         const int r = tap / p.S, s = tap - r * p.S;
         const int delta = (((r - p.pad) * p.W + (s - p.pad)) * p.C + c0) * 2;       // bytes, may be negative
         const bool valid = (tapmask >> tap) & 1u;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
+        for (int q = 0; q < NQA; ++q) {
             u4 v = {0u, 0u, 0u, 0u};
             if (valid) v = ldg16(abase, aoff[q] + (unsigned)delta);
             ra[q] = v;
@@ -102,14 +102,14 @@ __global__ __launch_bounds__(256) void conv_fast_kernel(FastConvParams p)
     };
     auto store_tiles = [&](int buf) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) *reinterpret_cast<u4*>(sAc + buf * A_BUF + sa_st[q]) = ra[q];
+        for (int q = 0; q < NQA; ++q) *reinterpret_cast<u4*>(sAc + buf * A_BUF + sa_st[q]) = ra[q];
 #pragma unroll
         for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sBc + buf * B_BUF + sb_st[q]) = rb[q];
     };
 
-    f16 acc[2][TN];
+    f16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -124,13 +124,13 @@ __global__ __launch_bounds__(256) void conv_fast_kernel(FastConvParams p)
         if (t + 1 < nslab) load_tiles();
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            bf16x8 a[2], b[TN];
+            bf16x8 a[TM], b[TN];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sAc + buf * A_BUF + a_rd + (i * 32 * LDP + ks * 16) * 2);
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sAc + buf * A_BUF + a_rd + (i * 32 * LDP + ks * 16) * 2);
 #pragma unroll
             for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sBc + buf * B_BUF + b_rd + (j * 32 * LDP + ks * 16) * 2);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)      // operands swapped: the accumulator holds the transposed tile
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
@@ -144,8 +144,8 @@ __global__ __launch_bounds__(256) void conv_fast_kernel(FastConvParams p)
     const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
     const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int mm = m0 + wm * 64 + i * 32 + (lane & 31);
+    for (int i = 0; i < TM; ++i) {
+        const int mm = m0 + wm * (BMT / 2) + i * 32 + (lane & 31);
         if (mm >= p.M) continue;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
@@ -349,20 +349,24 @@ __global__ __launch_bounds__(256) void weight_prep_kernel(WeightPrepParams p)
     }
 }
 
+template <int BMT, int BN>
+void launch_conv_fast_t(const FastConvParams& p, int epi, int n_active, hipStream_t s)
+{
+    const dim3 grid((unsigned)((p.M + BMT - 1) / BMT), (unsigned)(p.N / BN), (unsigned)n_active), block(256);
+    if (epi == 0) hipLaunchKernelGGL((conv_fast_kernel<BMT, BN, 0>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((conv_fast_kernel<BMT, BN, 1>), grid, block, 0, s, p);
+}
+
 }  // namespace
 
 hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
     const int bn = (p.N % 128 == 0) ? 128 : 64;
-    const dim3 grid((unsigned)((p.M + BM - 1) / BM), (unsigned)(p.N / bn), (unsigned)n_active), block(256);
-    if (bn == 128) {
-        if (epi == 0) hipLaunchKernelGGL((conv_fast_kernel<128, 0>), grid, block, 0, s, p);
-        else hipLaunchKernelGGL((conv_fast_kernel<128, 1>), grid, block, 0, s, p);
-    } else {
-        if (epi == 0) hipLaunchKernelGGL((conv_fast_kernel<64, 0>), grid, block, 0, s, p);
-        else hipLaunchKernelGGL((conv_fast_kernel<64, 1>), grid, block, 0, s, p);
-    }
+    // tall tiles halve the weight traffic and double the MFMA work per barrier; use them when they still fill the chip
+    const bool tall = (long long)(p.M / 256) * (p.N / bn) * n_active >= 512;
+    if (bn == 128) { if (tall) launch_conv_fast_t<256, 128>(p, epi, n_active, s); else launch_conv_fast_t<128, 128>(p, epi, n_active, s); }
+    else { if (tall) launch_conv_fast_t<256, 64>(p, epi, n_active, s); else launch_conv_fast_t<128, 64>(p, epi, n_active, s); }
     return hipGetLastError();
 }
 

@@ -86,6 +86,23 @@ def test_regular_layers_bf16_lean_kernels(name):
     p.close()
 
 
+def test_regular_layer_bf16_tall_tiles():
+    """Enough output rows (12 x 64 x 64 per replica, 3 replicas) that the lean kernels pick their 256-row tiles."""
+    b = nets._Builder()
+    t = b.relu(b.conv(0, 64))
+    t = b.relu(b.conv(t, 64))
+    b.dense(b.gap(t), 5)
+    ops, shape, batch = b.array(), (64, 64, 3), 12
+    N = 3
+    x, y = _data(N, batch, shape, 5, seed=77)
+    p = Pair(ops, shape, N, 2, x, y, batch, 0.01, 0.9, [1, 1, 1], bf16=True)
+    p.local_steps()
+    d = p.max_rel_diff()
+    print("tall tiles bf16 rel", d, "loss", p.gpu.losses(), p.cpu.loss, flush=True)
+    assert d <= REL
+    p.close()
+
+
 def _narrow_vgg():
     b = nets._Builder()
     t = 0
