@@ -280,6 +280,215 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_kernel(BnParams p)
     }
 }
 
+// ------------------------------------------------------------------------------------------------------
+// Vectorised batch-norm kernels (channel count a multiple of 16 bytes' worth of elements): a thread owns a vector of
+// VEC consecutive channels (one 16-byte access per row) and strides over rows; a workgroup is CVB channel vectors x
+// 256/CVB row lanes.  The forward statistics take ONE pass: sums of d = x - x0 and d^2 with x0 the tensor's first
+// row (a shift close to the mean keeps  E[d^2] - E[d]^2  well conditioned), so forward is 2 passes and backward 2.
+// ------------------------------------------------------------------------------------------------------
+template <typename T> struct VecOf { static constexpr int n = 16 / (int)sizeof(T); };
+typedef float f4v __attribute__((ext_vector_type(4)));
+typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ void ldv(const float* p, long long i, float (&o)[4])
+{
+    const f4v v = *reinterpret_cast<const f4v*>(p + i);
+    o[0] = v[0]; o[1] = v[1]; o[2] = v[2]; o[3] = v[3];
+}
+__device__ __forceinline__ void ldv(const __bf16* p, long long i, float (&o)[8])
+{
+    const bf8v v = *reinterpret_cast<const bf8v*>(p + i);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (float)v[e];
+}
+__device__ __forceinline__ void stv(float* p, long long i, const float (&o)[4])
+{
+    f4v v = {o[0], o[1], o[2], o[3]};
+    *reinterpret_cast<f4v*>(p + i) = v;
+}
+__device__ __forceinline__ void stv(__bf16* p, long long i, const float (&o)[8])
+{
+    bf8v v;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (__bf16)o[e];
+    *reinterpret_cast<bf8v*>(p + i) = v;
+}
+
+struct BnGeo { int cvb, rl_count, cgroups, chunk, cv, rl, c; bool live; };
+__device__ __forceinline__ BnGeo bn_geo(const BnParams& p, int vec)
+{
+    BnGeo g;
+    const int CV = p.C / vec;
+    g.cvb = p.cvb; g.rl_count = 256 / g.cvb;
+    g.cgroups = (CV + g.cvb - 1) / g.cvb;
+    g.chunk = blockIdx.x / g.cgroups;
+    g.cv = (blockIdx.x % g.cgroups) * g.cvb + (threadIdx.x % g.cvb);
+    g.rl = threadIdx.x / g.cvb;
+    g.c = g.cv * vec;
+    g.live = g.cv < CV;
+    return g;
+}
+
+// MODE 0 (forward): partial[chunk][0] = sum(x - x0), [1] = sum((x - x0)^2)
+// MODE 1 (backward): partial[chunk][0] = sum(dy), [1] = sum(dy * xhat)
+template <int MODE, typename T>
+__global__ __launch_bounds__(256) void bn_sums_vec_kernel(BnParams p)
+{
+    constexpr int VEC = VecOf<T>::n;
+    __shared__ float red[256][2 * VEC + 1];
+    const int gi = blockIdx.y, rep = p.order[gi];
+    const BnGeo g = bn_geo(p, VEC);
+    const T* x = tptr<T>(p.x, rep, p.x_rep);
+    const T* dy = (MODE == 1) ? tptr<T>(p.dy, rep, p.dy_rep) : nullptr;
+    float s0[VEC], s1[VEC], a[VEC], b[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { s0[e] = 0.f; s1[e] = 0.f; a[e] = 0.f; b[e] = 1.f; }
+    if (g.live) {
+        if (MODE == 0) ldv(x, g.c, a);                       // the shift: first row of the tensor
+        else {
+            const float* sv = p.saved + rep * p.saved_rep;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) { a[e] = sv[g.c + e]; b[e] = sv[p.C + g.c + e]; }
+        }
+        const int r0 = g.chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
+        for (int r = r0 + g.rl; r < r1; r += g.rl_count) {
+            float v[VEC];
+            ldv(x, (long long)r * p.C + g.c, v);
+            if (MODE == 0) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) { const float d = v[e] - a[e]; s0[e] += d; s1[e] += d * d; }
+            } else {
+                float d[VEC];
+                ldv(dy, (long long)r * p.C + g.c, d);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) { s0[e] += d[e]; s1[e] += d[e] * ((v[e] - a[e]) * b[e]); }
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { red[threadIdx.x][e] = s0[e]; red[threadIdx.x][VEC + e] = s1[e]; }
+    __syncthreads();
+    for (int w = g.rl_count / 2; w > 0; w >>= 1) {           // fixed-order tree over the row lanes
+        if (g.rl < w) {
+#pragma unroll
+            for (int e = 0; e < 2 * VEC; ++e) red[threadIdx.x][e] += red[threadIdx.x + w * g.cvb][e];
+        }
+        __syncthreads();
+    }
+    if (g.rl == 0 && g.live) {
+        float* part = p.partial + gi * p.partial_rep + (long long)g.chunk * 2 * p.C;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { part[g.c + e] = red[threadIdx.x][e]; part[p.C + g.c + e] = red[threadIdx.x][VEC + e]; }
+    }
+}
+
+// One thread per channel adds the per-chunk partial sums in chunk order.
+// MODE 0: mean and 1/sqrt(var+eps) -> saved, running statistics updated.  x0 is the shift used by the sums pass.
+// MODE 1: totals of dy and dy*xhat -> gradient of beta and gamma, and into chunk 0 of the partial buffer.
+template <int MODE, typename T>
+__global__ __launch_bounds__(256) void bn_finalize_kernel(BnParams p)
+{
+    const int gi = blockIdx.y, rep = p.order[gi];
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= p.C) return;
+    float* part = p.partial + gi * p.partial_rep;
+    float s = 0.f, q = 0.f;
+    for (int k = 0; k < p.chunks; ++k) { s += part[(long long)k * 2 * p.C + c]; q += part[(long long)k * 2 * p.C + p.C + c]; }
+    if (MODE == 0) {
+        const float n = (float)p.rows;
+        const float x0 = ldf(tptr<T>(p.x, rep, p.x_rep), c);
+        const float md = s / n;                               // mean of the shifted values
+        const float cen = fmaxf(q - s * md, 0.f);             // sum of squared deviations from the mean
+        const float mean = x0 + md, var = cen / n;
+        float* sv = p.saved + rep * p.saved_rep;
+        sv[c] = mean; sv[p.C + c] = 1.0f / sqrtf(var + kBnEps);
+        const float unb = p.rows > 1 ? cen / (n - 1.f) : var;
+        float* rm = p.params + rep * p.row_stride + p.stat_off;
+        rm[c] = (1.f - kBnStatMomentum) * rm[c] + kBnStatMomentum * mean;
+        rm[p.C + c] = (1.f - kBnStatMomentum) * rm[p.C + c] + kBnStatMomentum * unb;
+    } else {
+        float* gr = p.grads + rep * p.row_stride + p.w_off;
+        gr[c] = q; gr[p.C + c] = s;
+        part[c] = s; part[p.C + c] = q;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bn_apply_fwd_vec_kernel(BnParams p)
+{
+    constexpr int VEC = VecOf<T>::n;
+    const int gi = blockIdx.y, rep = p.order[gi];
+    const BnGeo g = bn_geo(p, VEC);
+    if (!g.live) return;
+    const T* x = tptr<T>(p.x, rep, p.x_rep);
+    T* y = tptr<T>(p.y, rep, p.y_rep);
+    const float* row = p.params + rep * p.row_stride;
+    float sc[VEC], sh[VEC];
+    const float* sv = p.saved + rep * p.saved_rep;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const int c = g.c + e;
+        const float mean = sv[c], istd = sv[p.C + c];
+        const float gamma = row[p.w_off + c], beta = row[p.w_off + p.C + c];
+        sc[e] = gamma * istd; sh[e] = beta - mean * gamma * istd;
+    }
+    const int r0 = g.chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
+    for (int r = r0 + g.rl; r < r1; r += g.rl_count) {
+        float v[VEC];
+        const long long i = (long long)r * p.C + g.c;
+        ldv(x, i, v);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { const float t = v[e] * sc[e] + sh[e]; v[e] = p.relu ? fmaxf(t, 0.f) : t; }
+        stv(y, i, v);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bn_apply_bwd_vec_kernel(BnParams p)
+{
+    constexpr int VEC = VecOf<T>::n;
+    const int gi = blockIdx.y, rep = p.order[gi];
+    const BnGeo g = bn_geo(p, VEC);
+    if (!g.live) return;
+    const T* x = tptr<T>(p.x, rep, p.x_rep);
+    const T* dy = tptr<T>(p.dy, rep, p.dy_rep);
+    T* dx = tptr<T>(p.y, rep, p.y_rep);
+    const T* mask = p.mask ? tptr<T>(p.mask, rep, p.mask_rep) : nullptr;
+    const float* part = p.partial + gi * p.partial_rep;
+    const float* sv = p.saved + rep * p.saved_rep;
+    const float inv_n = 1.0f / (float)p.rows;
+    float mean[VEC], istd[VEC], k1[VEC], kb[VEC], kg[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const int c = g.c + e;
+        const float db = part[c], dg = part[p.C + c];       // totals left in chunk 0 by bn_finalize_kernel<1>
+        mean[e] = sv[c]; istd[e] = sv[p.C + c];
+        k1[e] = p.params[rep * p.row_stride + p.w_off + c] * istd[e];
+        kb[e] = db * inv_n; kg[e] = dg * inv_n;
+    }
+    const int r0 = g.chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
+    for (int r = r0 + g.rl; r < r1; r += g.rl_count) {
+        const long long i = (long long)r * p.C + g.c;
+        float v[VEC], d[VEC], o[VEC];
+        ldv(x, i, v); ldv(dy, i, d);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) o[e] = k1[e] * (d[e] - kb[e] - ((v[e] - mean[e]) * istd[e]) * kg[e]);
+        if (mask) {
+            float mk[VEC];
+            ldv(mask, i, mk);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) if (!(mk[e] > 0.f)) o[e] = 0.f;
+        }
+        if (p.accumulate) {
+            float old[VEC];
+            ldv(dx, i, old);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) o[e] += old[e];
+        }
+        stv(dx, i, o);
+    }
+}
+
 // One workgroup per replica, one thread per sample: softmax, loss, d(loss)/d(logits); loss summed by an LDS tree.
 template <typename T>
 __global__ __launch_bounds__(1024) void softmax_ce_kernel(LossParams p)
@@ -400,10 +609,33 @@ hipError_t launch_dense_small_fwd(const DenseSmallParams& p, int n_active, hipSt
     return hipGetLastError();
 }
 
-hipError_t launch_bn_fwd(const BnParams& p, int n_active, hipStream_t s)
+namespace {
+// channel vectors per workgroup: the largest power of two that is at most min(C / vec, 32)
+int bn_cvb(int C, int vec) { int cv = C / vec, b = 1; while (b * 2 <= cv && b * 2 <= 32) b *= 2; return b; }
+}  // namespace
+
+hipError_t launch_bn_fwd(const BnParams& p0, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
-    const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active), block(256);
+    BnParams p = p0;
+    const int vec = p.bf16 ? 8 : 4;
+    const dim3 block(256);
+    if (p.C % vec == 0) {
+        p.cvb = bn_cvb(p.C, vec);
+        const int cgroups = (p.C / vec + p.cvb - 1) / p.cvb;
+        const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 255) / 256), (unsigned)n_active);
+        if (p.bf16) {
+            hipLaunchKernelGGL((bn_sums_vec_kernel<0, __bf16>), grid, block, 0, s, p);
+            hipLaunchKernelGGL((bn_finalize_kernel<0, __bf16>), fgrid, block, 0, s, p);
+            hipLaunchKernelGGL(bn_apply_fwd_vec_kernel<__bf16>, grid, block, 0, s, p);
+        } else {
+            hipLaunchKernelGGL((bn_sums_vec_kernel<0, float>), grid, block, 0, s, p);
+            hipLaunchKernelGGL((bn_finalize_kernel<0, float>), fgrid, block, 0, s, p);
+            hipLaunchKernelGGL(bn_apply_fwd_vec_kernel<float>, grid, block, 0, s, p);
+        }
+        return hipGetLastError();
+    }
+    const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active);
     if (p.bf16) {
         hipLaunchKernelGGL((bn_reduce_kernel<0, __bf16>), grid, block, 0, s, p);
         hipLaunchKernelGGL((bn_reduce_kernel<1, __bf16>), grid, block, 0, s, p);
@@ -416,10 +648,28 @@ hipError_t launch_bn_fwd(const BnParams& p, int n_active, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_bn_bwd(const BnParams& p, int n_active, hipStream_t s)
+hipError_t launch_bn_bwd(const BnParams& p0, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
-    const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active), block(256);
+    BnParams p = p0;
+    const int vec = p.bf16 ? 8 : 4;
+    const dim3 block(256);
+    if (p.C % vec == 0) {
+        p.cvb = bn_cvb(p.C, vec);
+        const int cgroups = (p.C / vec + p.cvb - 1) / p.cvb;
+        const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 255) / 256), (unsigned)n_active);
+        if (p.bf16) {
+            hipLaunchKernelGGL((bn_sums_vec_kernel<1, __bf16>), grid, block, 0, s, p);
+            hipLaunchKernelGGL((bn_finalize_kernel<1, __bf16>), fgrid, block, 0, s, p);
+            hipLaunchKernelGGL(bn_apply_bwd_vec_kernel<__bf16>, grid, block, 0, s, p);
+        } else {
+            hipLaunchKernelGGL((bn_sums_vec_kernel<1, float>), grid, block, 0, s, p);
+            hipLaunchKernelGGL((bn_finalize_kernel<1, float>), fgrid, block, 0, s, p);
+            hipLaunchKernelGGL(bn_apply_bwd_vec_kernel<float>, grid, block, 0, s, p);
+        }
+        return hipGetLastError();
+    }
+    const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active);
     if (p.bf16) {
         hipLaunchKernelGGL((bn_reduce_kernel<2, __bf16>), grid, block, 0, s, p);
         hipLaunchKernelGGL(bn_apply_bwd_kernel<__bf16>, grid, block, 0, s, p);

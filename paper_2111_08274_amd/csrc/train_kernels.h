@@ -115,6 +115,7 @@ struct BnParams {
     float* saved; long long saved_rep;     // [2][C]: mean, 1/sqrt(var+eps)
     float* partial; long long partial_rep; // [chunks][2][C]
     int rows, C, chunks, chunk_rows;
+    int cvb;                               // set by the launcher: channel vectors per workgroup (vector kernels)
     int accumulate;
     int relu;                              // forward: y = max(bn(x), 0)
     const float* mask; long long mask_rep; // backward: zero dx where mask <= 0
