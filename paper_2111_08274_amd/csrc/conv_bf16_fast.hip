@@ -51,30 +51,34 @@ __global__ __launch_bounds__(256, 2) void conv_fast_kernel(FastConvParams p)
     const char* abase = (const char*)p.a + (long long)rep * p.a_rep * 4;
     const char* wbase = (const char*)(p.wmat + (long long)rep * p.wmat_rep);
 
-    // ---- loop-invariant addressing (every A slot of a thread lies in the same row) ----
-    const int arow = tid % BMT;
-    const int m = m0 + arow;
-    const bool a_ok = m < p.M;
+    // ---- loop-invariant addressing ----
+    // Slot i of the tile = (row i / 4, k-group i % 4): four neighbouring lanes read the 64 contiguous bytes one row
+    // contributes to a slab, so a wave-wide load touches 16 rows x 64 bytes instead of 64 rows x 16 bytes and does
+    // not depend on the vector cache keeping partly used lines alive.
+    unsigned aoff[NQA], boff[NQB], sa_st[NQA], sb_st[NQB], tapmask[NQA];
     const int hw = p.H * p.W;
-    const int bimg = m / hw, rem = m - bimg * hw, y = rem / p.W, x = rem - y * p.W;
-    unsigned tapmask = 0;
-    for (int t = 0; t < p.R * p.S; ++t) {
-        const int r = t / p.S, s = t - r * p.S;
-        const int yy = y + r - p.pad, xx = x + s - p.pad;
-        if (a_ok && yy >= 0 && yy < p.H && xx >= 0 && xx < p.W) tapmask |= 1u << t;
-    }
-    unsigned aoff[NQA], boff[NQB], sa_st[NQA], sb_st[NQB];
 #pragma unroll
     for (int q = 0; q < NQA; ++q) {
-        const int kq = (tid + q * 256) / BMT;
+        const int i = tid + q * 256;
+        const int arow = i >> 2, kq = i & 3;
+        const int m = m0 + arow;
+        const bool a_ok = m < p.M;
+        const int bimg = m / hw, rem = m - bimg * hw, y = rem / p.W, x = rem - y * p.W;
+        unsigned mask = 0;
+        for (int t = 0; t < p.R * p.S; ++t) {
+            const int r = t / p.S, s = t - r * p.S;
+            const int yy = y + r - p.pad, xx = x + s - p.pad;
+            if (a_ok && yy >= 0 && yy < p.H && xx >= 0 && xx < p.W) mask |= 1u << t;
+        }
+        tapmask[q] = mask;
         aoff[q] = (unsigned)(m * p.C + kq * 8) * 2u;
         sa_st[q] = (unsigned)(arow * LDP + kq * 8) * 2u;
     }
 #pragma unroll
     for (int q = 0; q < NQB; ++q) {
         const int i = tid + q * 256;
-        boff[q] = (unsigned)((n0 + i % BN) * p.K + (i / BN) * 8) * 2u;
-        sb_st[q] = (unsigned)((i % BN) * LDP + (i / BN) * 8) * 2u;
+        boff[q] = (unsigned)((n0 + (i >> 2)) * p.K + (i & 3) * 8) * 2u;
+        sb_st[q] = (unsigned)((i >> 2) * LDP + (i & 3) * 8) * 2u;
     }
     char* const sAc = reinterpret_cast<char*>(&sA[0][0][0]);
     char* const sBc = reinterpret_cast<char*>(&sB[0][0][0]);
@@ -82,16 +86,17 @@ __global__ __launch_bounds__(256, 2) void conv_fast_kernel(FastConvParams p)
     const unsigned a_rd = (unsigned)((wm * (BMT / 2) + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
     const unsigned b_rd = (unsigned)((wn * (BN / 2) + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
 
-    u4 ra[NQA], rb[NQB];
+    // Two register sets: the loads of slab t+2 are issued before slab t is multiplied, and slab t+1 (loaded one
+    // iteration earlier) is written to LDS after it, so a global load has two full iterations to arrive.
+    u4 ra0[NQA], rb0[NQB], ra1[NQA], rb1[NQB];
     int tap = 0, c0 = 0;                         // wave-uniform position of the next slab to load
-    auto load_tiles = [&]() {
+    auto load_tiles = [&](u4 (&ra)[NQA], u4 (&rb)[NQB]) {
         const int r = tap / p.S, s = tap - r * p.S;
         const int delta = (((r - p.pad) * p.W + (s - p.pad)) * p.C + c0) * 2;       // bytes, may be negative
-        const bool valid = (tapmask >> tap) & 1u;
 #pragma unroll
         for (int q = 0; q < NQA; ++q) {
             u4 v = {0u, 0u, 0u, 0u};
-            if (valid) v = ldg16(abase, aoff[q] + (unsigned)delta);
+            if ((tapmask[q] >> tap) & 1u) v = ldg16(abase, aoff[q] + (unsigned)delta);
             ra[q] = v;
         }
         const unsigned kb = (unsigned)(tap * p.C + c0) * 2u;
@@ -100,7 +105,7 @@ __global__ __launch_bounds__(256, 2) void conv_fast_kernel(FastConvParams p)
         c0 += BK;
         if (c0 == p.C) { c0 = 0; ++tap; }
     };
-    auto store_tiles = [&](int buf) {
+    auto store_tiles = [&](int buf, const u4 (&ra)[NQA], const u4 (&rb)[NQB]) {
 #pragma unroll
         for (int q = 0; q < NQA; ++q) *reinterpret_cast<u4*>(sAc + buf * A_BUF + sa_st[q]) = ra[q];
 #pragma unroll
@@ -115,13 +120,7 @@ __global__ __launch_bounds__(256, 2) void conv_fast_kernel(FastConvParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nslab = p.K / BK;
-    load_tiles();
-    store_tiles(0);
-    __syncthreads();
-    for (int t = 0; t < nslab; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < nslab) load_tiles();
+    auto compute = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             bf16x8 a[TM], b[TN];
@@ -135,8 +134,162 @@ __global__ __launch_bounds__(256, 2) void conv_fast_kernel(FastConvParams p)
                 for (int j = 0; j < TN; ++j)      // operands swapped: the accumulator holds the transposed tile
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
         }
-        if (t + 1 < nslab) store_tiles(buf ^ 1);
+    };
+
+    const int nslab = p.K / BK;
+    load_tiles(ra0, rb0);
+    store_tiles(0, ra0, rb0);
+    if (nslab > 1) load_tiles(ra0, rb0);          // slab 1 in flight in set 0
+    __syncthreads();
+    for (int t = 0; t < nslab; t += 2) {
+        if (t + 2 < nslab) load_tiles(ra1, rb1);  // slab t+2 -> set 1
+        compute(0);
+        if (t + 1 < nslab) store_tiles(1, ra0, rb0);
         __syncthreads();
+        if (t + 1 < nslab) {
+            if (t + 3 < nslab) load_tiles(ra0, rb0);   // slab t+3 -> set 0
+            compute(1);
+            if (t + 2 < nslab) store_tiles(0, ra1, rb1);
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: lane holds output pixel (lane & 31) and channels 8*g + 4*(lane >> 5) + {0..3}, g = 0..3 ----
+    char* obase = (char*)p.out + (long long)rep * p.out_rep * 4;
+    const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
+    const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int mm = m0 + wm * (BMT / 2) + i * 32 + (lane & 31);
+        if (mm >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + wn * (BN / 2) + j * 32 + 8 * g + 4 * (lane >> 5);
+                const unsigned o = (unsigned)(mm * p.N + n) * 2u;
+                f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                if (EPI == 0) {
+                    if (bias) v += *reinterpret_cast<const f4*>(bias + n);
+                    if (p.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
+                } else {
+                    if (mask) {
+                        const bf16x4 mk = *reinterpret_cast<const bf16x4*>(mask + o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) if (!((float)mk[e] > 0.f)) v[e] = 0.f;
+                    }
+                    if (p.accumulate) {
+                        const bf16x4 old = *reinterpret_cast<const bf16x4*>(obase + o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += (float)old[e];
+                    }
+                }
+                bf16x4 r;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) r[e] = (__bf16)v[e];
+                *reinterpret_cast<bf16x4*>(obase + o) = r;
+            }
+        }
+    }
+}
+
+// Same computation with slabs of 64: eight neighbouring lanes read the full 128-byte line a row contributes to a slab.
+// One LDS buffer (rows padded to 72 elements), the next slab waits in registers while the current one is multiplied.
+template <int BMT, int BN, int EPI>
+__global__ __launch_bounds__(256, 2) void conv_fast64_kernel(FastConvParams p)
+{
+    constexpr int BK2 = 64, LDQ = 72;
+    constexpr int TM = BMT / 64, TN = BN / 64;
+    constexpr int NQA = BMT / 32, NQB = BN / 32;      // slots per thread: rows x 8 groups of 8 k over 256 threads
+    __shared__ __attribute__((aligned(16))) __bf16 sA[BMT][LDQ];
+    __shared__ __attribute__((aligned(16))) __bf16 sB[BN][LDQ];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int rep = p.order[blockIdx.z];
+    const int m0 = blockIdx.x * BMT, n0 = blockIdx.y * BN;
+    const char* abase = (const char*)p.a + (long long)rep * p.a_rep * 4;
+    const char* wbase = (const char*)(p.wmat + (long long)rep * p.wmat_rep);
+
+    unsigned aoff[NQA], boff[NQB], sa_st[NQA], sb_st[NQB], tapmask[NQA];
+    const int hw = p.H * p.W;
+#pragma unroll
+    for (int q = 0; q < NQA; ++q) {
+        const int i = tid + q * 256;
+        const int arow = i >> 3, kq = i & 7;
+        const int m = m0 + arow;
+        const bool a_ok = m < p.M;
+        const int bimg = m / hw, rem = m - bimg * hw, y = rem / p.W, x = rem - y * p.W;
+        unsigned mask = 0;
+        for (int t = 0; t < p.R * p.S; ++t) {
+            const int r = t / p.S, s = t - r * p.S;
+            const int yy = y + r - p.pad, xx = x + s - p.pad;
+            if (a_ok && yy >= 0 && yy < p.H && xx >= 0 && xx < p.W) mask |= 1u << t;
+        }
+        tapmask[q] = mask;
+        aoff[q] = (unsigned)(m * p.C + kq * 8) * 2u;
+        sa_st[q] = (unsigned)(arow * LDQ + kq * 8) * 2u;
+    }
+#pragma unroll
+    for (int q = 0; q < NQB; ++q) {
+        const int i = tid + q * 256;
+        boff[q] = (unsigned)((n0 + (i >> 3)) * p.K + (i & 7) * 8) * 2u;
+        sb_st[q] = (unsigned)((i >> 3) * LDQ + (i & 7) * 8) * 2u;
+    }
+    char* const sAc = reinterpret_cast<char*>(&sA[0][0]);
+    char* const sBc = reinterpret_cast<char*>(&sB[0][0]);
+    const unsigned a_rd = (unsigned)((wm * (BMT / 2) + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
+    const unsigned b_rd = (unsigned)((wn * (BN / 2) + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
+
+    u4 ra[NQA], rb[NQB];
+    int tap = 0, c0 = 0;
+    auto load_tiles = [&]() {
+        const int r = tap / p.S, s = tap - r * p.S;
+        const int delta = (((r - p.pad) * p.W + (s - p.pad)) * p.C + c0) * 2;
+#pragma unroll
+        for (int q = 0; q < NQA; ++q) {
+            u4 v = {0u, 0u, 0u, 0u};
+            if ((tapmask[q] >> tap) & 1u) v = ldg16(abase, aoff[q] + (unsigned)delta);
+            ra[q] = v;
+        }
+        const unsigned kb = (unsigned)(tap * p.C + c0) * 2u;
+#pragma unroll
+        for (int q = 0; q < NQB; ++q) rb[q] = ldg16(wbase, boff[q] + kb);
+        c0 += BK2;
+        if (c0 == p.C) { c0 = 0; ++tap; }
+    };
+
+    f16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nslab = p.K / BK2;
+    load_tiles();
+    for (int t = 0; t < nslab; ++t) {
+        __syncthreads();                                   // every wave is done reading the previous slab
+#pragma unroll
+        for (int q = 0; q < NQA; ++q) *reinterpret_cast<u4*>(sAc + sa_st[q]) = ra[q];
+#pragma unroll
+        for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sBc + sb_st[q]) = rb[q];
+        __syncthreads();
+        if (t + 1 < nslab) load_tiles();
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sAc + a_rd + (i * 32 * LDQ + ks * 16) * 2);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sBc + b_rd + (j * 32 * LDQ + ks * 16) * 2);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+        }
     }
 
     // ---- epilogue: lane holds output pixel (lane & 31) and channels 8*g + 4*(lane >> 5) + {0..3}, g = 0..3 ----
@@ -350,6 +503,14 @@ __global__ __launch_bounds__(256) void weight_prep_kernel(WeightPrepParams p)
 }
 
 template <int BMT, int BN>
+void launch_conv_fast64_t(const FastConvParams& p, int epi, int n_active, hipStream_t s)
+{
+    const dim3 grid((unsigned)((p.M + BMT - 1) / BMT), (unsigned)(p.N / BN), (unsigned)n_active), block(256);
+    if (epi == 0) hipLaunchKernelGGL((conv_fast64_kernel<BMT, BN, 0>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((conv_fast64_kernel<BMT, BN, 1>), grid, block, 0, s, p);
+}
+
+template <int BMT, int BN>
 void launch_conv_fast_t(const FastConvParams& p, int epi, int n_active, hipStream_t s)
 {
     const dim3 grid((unsigned)((p.M + BMT - 1) / BMT), (unsigned)(p.N / BN), (unsigned)n_active), block(256);
@@ -365,8 +526,18 @@ hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipS
     const int bn = (p.N % 128 == 0) ? 128 : 64;
     // tall tiles halve the weight traffic and double the MFMA work per barrier; use them when they still fill the chip
     const bool tall = (long long)(p.M / 256) * (p.N / bn) * n_active >= 512;
-    if (bn == 128) { if (tall) launch_conv_fast_t<256, 128>(p, epi, n_active, s); else launch_conv_fast_t<128, 128>(p, epi, n_active, s); }
-    else { if (tall) launch_conv_fast_t<256, 64>(p, epi, n_active, s); else launch_conv_fast_t<128, 64>(p, epi, n_active, s); }
+    const bool k64 = p.C % 64 == 0;
+    if (bn == 128) {
+        if (tall && k64) launch_conv_fast64_t<256, 128>(p, epi, n_active, s);
+        else if (tall) launch_conv_fast_t<256, 128>(p, epi, n_active, s);
+        else if (k64) launch_conv_fast64_t<128, 128>(p, epi, n_active, s);
+        else launch_conv_fast_t<128, 128>(p, epi, n_active, s);
+    } else {
+        if (tall && k64) launch_conv_fast64_t<256, 64>(p, epi, n_active, s);
+        else if (tall) launch_conv_fast_t<256, 64>(p, epi, n_active, s);
+        else if (k64) launch_conv_fast64_t<128, 64>(p, epi, n_active, s);
+        else launch_conv_fast_t<128, 64>(p, epi, n_active, s);
+    }
     return hipGetLastError();
 }
 

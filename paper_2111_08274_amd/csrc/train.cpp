@@ -214,9 +214,11 @@ struct Runner {
 
     hipError_t gemm(const GemmParams& p) const { return e.cfg.bf16 ? launch_gemm_bf16(p, na, s) : launch_gemm(p, na, s); }
     static double gemm_flops(const GemmParams& p) { return 2.0 * p.B * p.Ho * p.Wo * p.R * p.S * (double)p.Cin * p.Cout; }
-    static double gemm_bytes(const GemmParams& p)
+    // activations are 2 bytes in the bf16 configuration, weights and their gradients 4
+    double asz() const { return e.cfg.bf16 ? 0.5 : 1.0; }
+    double gemm_bytes(const GemmParams& p) const
     {
-        return 4.0 * ((double)p.B * p.H * p.W * p.Cin + (double)p.R * p.S * p.Cin * p.Cout + (double)p.B * p.Ho * p.Wo * p.Cout);
+        return 4.0 * (asz() * ((double)p.B * p.H * p.W * p.Cin + (double)p.B * p.Ho * p.Wo * p.Cout) + (double)p.R * p.S * p.Cin * p.Cout);
     }
 
     GemmParams gemm_base(const Layer& l) const
@@ -288,17 +290,17 @@ struct Runner {
             }
             run(l.type == HADFL_OP_CONV ? "conv_fwd" : "dense_fwd", gemm_flops(p), gemm_bytes(p), [&] { return gemm(p); });
             break; }
-        case HADFL_OP_RELU: run("relu_fwd", 0, 8.0 * q.count, [&] { return launch_relu_fwd(q, na, s); }); break;
-        case HADFL_OP_MAXPOOL: run("maxpool_fwd", 0, 4.0 * (B * a.numel() + q.count), [&] { return launch_maxpool_fwd(q, na, s); }); break;
+        case HADFL_OP_RELU: run("relu_fwd", 0, asz() * (8.0 * q.count), [&] { return launch_relu_fwd(q, na, s); }); break;
+        case HADFL_OP_MAXPOOL: run("maxpool_fwd", 0, asz() * (4.0 * (B * a.numel() + q.count)), [&] { return launch_maxpool_fwd(q, na, s); }); break;
         case HADFL_OP_ADD:
             q.in2 = act(l.in1); q.in2_rep = e.rep_block;
-            run("add_fwd", 0, 12.0 * q.count, [&] { return launch_add_fwd(q, na, s); });
+            run("add_fwd", 0, asz() * (12.0 * q.count), [&] { return launch_add_fwd(q, na, s); });
             break;
-        case HADFL_OP_GAP: run("gap_fwd", 0, 4.0 * (B * a.numel() + q.count), [&] { return launch_gap_fwd(q, na, s); }); break;
+        case HADFL_OP_GAP: run("gap_fwd", 0, asz() * (4.0 * (B * a.numel() + q.count)), [&] { return launch_gap_fwd(q, na, s); }); break;
         case HADFL_OP_BN: {
             BnParams b = bn_params(i);
             b.y = actw(ot); b.relu = e.fused_relu[i];
-            run("bn_fwd", 0, 8.0 * B * a.numel(), [&] { return launch_bn_fwd(b, na, s); });
+            run("bn_fwd", 0, asz() * (8.0 * B * a.numel()), [&] { return launch_bn_fwd(b, na, s); });
             break; }
         }
     }
@@ -395,26 +397,26 @@ struct Runner {
         case HADFL_OP_RELU:
             q.in = act(l.in0); q.in_rep = e.rep_block; q.in2 = grad(l.out); q.in2_rep = e.rep_block;
             q.count = B * a.numel();
-            run("relu_bwd", 0, 12.0 * q.count, [&] { return launch_relu_bwd(q, na, s); });
+            run("relu_bwd", 0, asz() * (12.0 * q.count), [&] { return launch_relu_bwd(q, na, s); });
             break;
         case HADFL_OP_MAXPOOL:
             q.in = act(l.in0); q.in_rep = e.rep_block; q.in2 = grad(l.out); q.in2_rep = e.rep_block;
             q.count = B * r.numel();
-            run("maxpool_bwd", 0, 4.0 * (2 * B * a.numel() + q.count), [&] { return launch_maxpool_bwd(q, na, s); });
+            run("maxpool_bwd", 0, asz() * (4.0 * (2 * B * a.numel() + q.count)), [&] { return launch_maxpool_bwd(q, na, s); });
             break;
         case HADFL_OP_ADD: {
             q.in = grad(ot); q.in_rep = e.rep_block; q.count = B * a.numel();
-            run("add_bwd", 0, 8.0 * q.count, [&] { return launch_pass_grad(q, na, s); });
+            run("add_bwd", 0, asz() * (8.0 * q.count), [&] { return launch_pass_grad(q, na, s); });
             EwParams q2 = q;
             if (l.in1 == l.in0) q2.accumulate = 1; else q2.accumulate = e.grad_written[l.in1] ? 1 : 0;
             q2.out = grad(l.in1);
             q2.mask = e.masked[l.in1] ? act(l.in1) : nullptr;
-            run("add_bwd", 0, 8.0 * q.count, [&] { return launch_pass_grad(q2, na, s); });
+            run("add_bwd", 0, asz() * (8.0 * q.count), [&] { return launch_pass_grad(q2, na, s); });
             e.grad_written[l.in1] = 1;
             break; }
         case HADFL_OP_GAP:
             q.in = grad(l.out); q.in_rep = e.rep_block; q.count = B * a.numel();
-            run("gap_bwd", 0, 4.0 * (q.count + B * a.c), [&] { return launch_gap_bwd(q, na, s); });
+            run("gap_bwd", 0, asz() * (4.0 * (q.count + B * a.c)), [&] { return launch_gap_bwd(q, na, s); });
             break;
         case HADFL_OP_BN: {
             BnParams b = bn_params(i);
@@ -422,7 +424,7 @@ struct Runner {
             b.y = grad(l.in0); b.y_rep = e.rep_block;
             b.accumulate = acc0;
             b.mask = mask0; b.mask_rep = e.rep_block;
-            run("bn_bwd", 0, 12.0 * B * a.numel(), [&] { return launch_bn_bwd(b, na, s); });
+            run("bn_bwd", 0, asz() * (12.0 * B * a.numel()), [&] { return launch_bn_bwd(b, na, s); });
             break; }
         }
         if (need_din) e.grad_written[l.in0] = 1;
@@ -446,7 +448,7 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
         lp.dlogits = r.grad(T - 1); lp.dlogits_rep = e->rep_block;
         lp.y = e->buf.y; lp.cursor = e->buf.cursor; lp.n_samples = e->cfg.n_samples; lp.batch = e->cfg.batch;
         lp.n_classes = e->cfg.n_classes; lp.loss = e->buf.loss; lp.order = e->buf.order; lp.bf16 = e->cfg.bf16;
-        r.run("softmax_ce", 0, 8.0 * e->cfg.batch * e->cfg.n_classes, [&] { return launch_softmax_ce(lp, r.na, s); });
+        r.run("softmax_ce", 0, r.asz() * 8.0 * e->cfg.batch * e->cfg.n_classes, [&] { return launch_softmax_ce(lp, r.na, s); });
         e->grad_written.assign(T, 0);
         e->grad_written[T - 1] = 1;
         for (size_t i = e->plan.layers.size(); i-- > 0;) r.backward_layer(i);
