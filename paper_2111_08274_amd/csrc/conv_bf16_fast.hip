@@ -334,17 +334,32 @@ __global__ __launch_bounds__(256, 2) void conv_fast64_kernel(FastConvParams p)
 // ---------------------------------------------------------------------------------------------------------------
 // Weight gradient: dW[m = (tap, ci) | bias row][n = co] = sum over pixels k of x[k + tap][ci] * dy[k][co]
 // ---------------------------------------------------------------------------------------------------------------
-__device__ __forceinline__ unsigned perm_lo(unsigned a, unsigned b) { return (a & 0xffffu) | (b << 16); }
-__device__ __forceinline__ unsigned perm_hi(unsigned a, unsigned b) { return (a >> 16) | (b & 0xffff0000u); }
+// Both operands are contiguous along their row index (channels) and the contraction runs over pixels, so the tiles
+// are stored in LDS as they arrive, [k][row] with 16-byte stores, and transposed on the way OUT of LDS with
+// ds_read_b64_tr_b16: within a group of 16 lanes, lane i receives element (i % 4) of the 8 bytes addressed by lane
+// 4*j + i/4, for j = 0..3.  Pointing lane L at row k0 + L/4, columns 4*(L%4).. of a 16-column block therefore hands
+// lane i the four consecutive k of column i -- half of an MFMA operand.
+typedef short s4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s4v lds_s4v;
+
+__device__ __forceinline__ bf16x8 lds_read_tr8(const char* base, unsigned off, unsigned row_pitch_bytes)
+{
+    // base + off addresses this lane's 8 bytes in row k0; rows k0+4.. supply the upper four k
+    const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v*)(base + off));
+    const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v*)(base + off + 4 * row_pitch_bytes));
+    typedef short s8v __attribute__((ext_vector_type(8)));
+    const s8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+}
 
 template <int BN>
-__global__ __launch_bounds__(256) void wgrad_fast_kernel(FastWgradParams p)
+__global__ __launch_bounds__(256, 2) void wgrad_fast_kernel(FastWgradParams p)
 {
     constexpr int TN = BN / 64;
-    constexpr int NQB = BN / 128 > 0 ? BN / 128 : 1;     // B octet slots per thread: 16 k-pairs x BN/8 octets over 256 threads
-    constexpr bool B_HALF = BN == 64;                    // BN = 64: only half of the threads stage B
-    __shared__ __attribute__((aligned(16))) __bf16 sA[2][BM][LDP];
-    __shared__ __attribute__((aligned(16))) __bf16 sB[2][BN][LDP];
+    constexpr int PA = (BM + 16) * 2, PB = (BN + 16) * 2;   // row pitches in bytes: 4 rows x 32 bytes land in distinct banks
+    constexpr int NQB = BN / 64;                            // B octet slots per thread: 32 k x BN/8 octets over 256 threads
+    __shared__ __attribute__((aligned(16))) char sA[2][BK * PA];
+    __shared__ __attribute__((aligned(16))) char sB[2][BK * PB];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -357,35 +372,31 @@ __global__ __launch_bounds__(256) void wgrad_fast_kernel(FastWgradParams p)
     const char* xbase = (const char*)p.x + (long long)rep * p.x_rep * 4;
     const char* dbase = (const char*)p.dy + (long long)rep * p.dy_rep * 4;
 
-    // A slot of this thread: k pair kp, 8 rows starting at am (one filter tap, 8 consecutive input channels)
-    const int kp = tid & 15, oct = tid >> 4;
+    // A slots of this thread: octet of rows (tid % 16) at pixels k0 + tid/16 and k0 + tid/16 + 16
+    const int oct = tid & 15, krow = tid >> 4;
     const int am = m0 + oct * 8;
     const int mw = p.R * p.S * p.C;
     const int atap = am / p.C, aci = am - atap * p.C;
     const int ar = atap / p.S, as = atap - ar * p.S;
     const int ady = ar - p.pad, adx = as - p.pad;
     const int a_kind = am < mw ? 0 : (am == mw && p.has_bias ? 1 : 2);      // 0 data, 1 bias row of ones, 2 nothing
-    const int a_shift = ((ady * p.W + adx) * p.C + aci) * 2;                // byte offset of the tap relative to pixel k
-    const unsigned sa_st = (unsigned)((oct * 8) * LDP + 2 * kp) * 2u;
-    unsigned sb_st[NQB], bnoff[NQB];
-#pragma unroll
-    for (int q = 0; q < NQB; ++q) {
-        const int o = (tid >> 4) + q * 16;
-        sb_st[q] = (unsigned)((o * 8) * LDP + 2 * kp) * 2u;
-        bnoff[q] = (unsigned)(n0 + o * 8) * 2u;
-    }
-    char* const sAc = reinterpret_cast<char*>(&sA[0][0][0]);
-    char* const sBc = reinterpret_cast<char*>(&sB[0][0][0]);
-    constexpr unsigned A_BUF = BM * LDP * 2, B_BUF = BN * LDP * 2;
-    const unsigned a_rd = (unsigned)((wm * 64 + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
-    const unsigned b_rd = (unsigned)((wn * (BN / 2) + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
+    const int a_shift = ((ady * p.W + adx) * p.C + aci) * 2;
+    const unsigned sa_st = (unsigned)(krow * PA + oct * 16);
+    // B slots: BN = 128: octet tid % 16, rows tid/16 and +16;  BN = 64: octet tid % 8, row tid/8
+    constexpr int BOCT = BN / 8;
+    const int boct = tid % BOCT, bkrow = tid / BOCT;
+    const unsigned sb_st = (unsigned)(bkrow * PB + boct * 16);
+    const unsigned bnoff = (unsigned)(n0 + boct * 8) * 2u;
+    // operand read offsets (see lds_read_tr8): lane L of a 16-lane group points at row L/4, columns 4*(L%4)
+    const unsigned rd_lane = (unsigned)(((lane >> 5) * 8 + ((lane & 15) >> 2)));
+    const unsigned a_rd = rd_lane * PA + (unsigned)(wm * 64 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2u;
+    const unsigned b_rd = rd_lane * PB + (unsigned)(wn * (BN / 2) + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2u;
 
-    u4 ra[2], rb[NQB][2];          // rows k and k+1 of the slot
+    u4 ra[2], rb[NQB];
     auto load_tiles = [&](int k0) {
-        const int k = k0 + 2 * kp;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const int kk = k + h;
+            const int kk = k0 + krow + 16 * h;
             u4 v = {0u, 0u, 0u, 0u};
             if (kk < kend) {
                 if (a_kind == 0) {
@@ -397,30 +408,20 @@ __global__ __launch_bounds__(256) void wgrad_fast_kernel(FastWgradParams p)
                 }
             }
             ra[h] = v;
+        }
 #pragma unroll
-            for (int q = 0; q < NQB; ++q) {
-                u4 w = {0u, 0u, 0u, 0u};
-                if (kk < kend && (!B_HALF || tid < 128)) w = ldg16(dbase, (unsigned)(kk * p.N) * 2u + bnoff[q]);
-                rb[q][h] = w;
-            }
+        for (int q = 0; q < NQB; ++q) {
+            const int kk = k0 + bkrow + (BK / NQB) * q;
+            u4 w = {0u, 0u, 0u, 0u};
+            if (kk < kend) w = ldg16(dbase, (unsigned)(kk * p.N) * 2u + bnoff);
+            rb[q] = w;
         }
     };
     auto store_tiles = [&](int buf) {
-        // element e of row k sits in the low half, of row k+1 in the high half of one 32-bit word
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            *reinterpret_cast<unsigned*>(sAc + buf * A_BUF + sa_st + (2 * e) * LDP * 2) = perm_lo(ra[0][e], ra[1][e]);
-            *reinterpret_cast<unsigned*>(sAc + buf * A_BUF + sa_st + (2 * e + 1) * LDP * 2) = perm_hi(ra[0][e], ra[1][e]);
-        }
-        if (!B_HALF || tid < 128) {
+        for (int h = 0; h < 2; ++h) *reinterpret_cast<u4*>(&sA[buf][sa_st + 16 * h * PA]) = ra[h];
 #pragma unroll
-            for (int q = 0; q < NQB; ++q)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    *reinterpret_cast<unsigned*>(sBc + buf * B_BUF + sb_st[q] + (2 * e) * LDP * 2) = perm_lo(rb[q][0][e], rb[q][1][e]);
-                    *reinterpret_cast<unsigned*>(sBc + buf * B_BUF + sb_st[q] + (2 * e + 1) * LDP * 2) = perm_hi(rb[q][0][e], rb[q][1][e]);
-                }
-        }
+        for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(&sB[buf][sb_st + (BK / NQB) * q * PB]) = rb[q];
     };
 
     f16 acc[2][TN];
@@ -441,9 +442,9 @@ __global__ __launch_bounds__(256) void wgrad_fast_kernel(FastWgradParams p)
         for (int ks = 0; ks < 2; ++ks) {
             bf16x8 a[2], b[TN];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sAc + buf * A_BUF + a_rd + (i * 32 * LDP + ks * 16) * 2);
+            for (int i = 0; i < 2; ++i) a[i] = lds_read_tr8(&sA[buf][0], a_rd + ks * 16 * PA + i * 64, PA);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sBc + buf * B_BUF + b_rd + (j * 32 * LDP + ks * 16) * 2);
+            for (int j = 0; j < TN; ++j) b[j] = lds_read_tr8(&sB[buf][0], b_rd + ks * 16 * PB + j * 64, PB);
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
