@@ -25,11 +25,11 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
     constexpr int A_SLOTS = BM * BK / 4, B_SLOTS = BN * BK / 4;
     constexpr int NQA = (A_SLOTS + NT - 1) / NT, NQB = (B_SLOTS + NT - 1) / NT;
     static_assert(TM >= 1 && TN >= 1, "tile too small for the wave grid");
-    static_assert(NT % BM == 0 || A_SLOTS <= NT, "A slots of a thread must share one row");
-    static_assert(NT % BN == 0 || B_SLOTS <= NT, "B slots of a thread must share one column");
-
-    __shared__ __attribute__((aligned(16))) float sA[2][BK][BM];
-    __shared__ __attribute__((aligned(16))) float sB[2][BK][BN];
+    // Operands read along K are staged as slot i = (row i / 4, k-group i % 4): four neighbouring lanes read the 64
+    // contiguous bytes one row contributes to a slab.  The +4 pitch keeps their transposing LDS writes (4 k-rows x
+    // 16 columns per wave instruction) in distinct banks.
+    __shared__ __attribute__((aligned(16))) float sA[2][BK][BM + 4];
+    __shared__ __attribute__((aligned(16))) float sB[2][BK][BN + 4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
     }
     // ---------------- per-thread, loop-invariant parts of the operand addresses ----------------
     // kFwd / kDgrad: A is read along K for one fixed row m.
-    int a_m = 0, a_b = 0, a_y = 0, a_x = 0; bool a_ok = false;
+    int a_b[NQA], a_y[NQA], a_x[NQA]; bool a_ok[NQA];
     // kWgrad: A is read along M for a fixed group of 4 rows m..m+3.
     int wa_m = 0, wa_r = 0, wa_s = 0, wa_c = 0;
     if (MODE == kWgrad) {
@@ -75,14 +75,17 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
         wa_c = wa_m - tap * p.Cin;
         wa_r = tap / p.S; wa_s = tap - wa_r * p.S;
     } else {
-        a_m = m0 + (tid % BM);
-        a_ok = a_m < ((MODE == kFwd) ? p.M : d_m);
         const int hw = (MODE == kFwd) ? p.Ho * p.Wo : d_hc * d_wc;
         const int ww = (MODE == kFwd) ? p.Wo : d_wc;
-        a_b = a_m / hw;
-        const int rem = a_m - a_b * hw;
-        a_y = rem / ww; a_x = rem - a_y * ww;
-        if (MODE == kDgrad) { a_y = a_y * p.stride + d_ph; a_x = a_x * p.stride + d_pw; }
+#pragma unroll
+        for (int q = 0; q < NQA; ++q) {
+            const int a_m = m0 + ((tid + q * NT) >> 2);
+            a_ok[q] = a_m < ((MODE == kFwd) ? p.M : d_m);
+            a_b[q] = a_m / hw;
+            const int rem = a_m - a_b[q] * hw;
+            a_y[q] = rem / ww; a_x[q] = rem - a_y[q] * ww;
+            if (MODE == kDgrad) { a_y[q] = a_y[q] * p.stride + d_ph; a_x[q] = a_x[q] * p.stride + d_pw; }
+        }
     }
     const bool fastA = (MODE == kFwd) ? (p.Cin % BK == 0) : (MODE == kDgrad) ? (p.Cout % BK == 0) : (p.Cin % 4 == 0);
     const bool vecN = (p.N % 4 == 0);
@@ -97,23 +100,23 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
                 const int i = tid + q * NT;
                 f4 v = {0.f, 0.f, 0.f, 0.f};
                 if (i < A_SLOTS) {
-                    const int kq = i / BM;
+                    const int kq = i & 3;
                     if (fastA) {
                         const int tap = k0 / p.Cin, c0 = k0 - tap * p.Cin;
                         const int r = tap / p.S, s = tap - r * p.S;
-                        const int yy = a_y * p.stride - p.pad + r, xx = a_x * p.stride - p.pad + s;
-                        if (a_ok && yy >= 0 && yy < p.H && xx >= 0 && xx < p.W)
-                            v = ld4(abase + (((long long)a_b * p.H + yy) * p.W + xx) * p.Cin + c0 + kq * 4);
+                        const int yy = a_y[q] * p.stride - p.pad + r, xx = a_x[q] * p.stride - p.pad + s;
+                        if (a_ok[q] && yy >= 0 && yy < p.H && xx >= 0 && xx < p.W)
+                            v = ld4(abase + (((long long)a_b[q] * p.H + yy) * p.W + xx) * p.Cin + c0 + kq * 4);
                     } else {
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             const int k = k0 + kq * 4 + j;
-                            if (a_ok && k < kend) {
+                            if (a_ok[q] && k < kend) {
                                 const int tap = k / p.Cin, c = k - tap * p.Cin;
                                 const int r = tap / p.S, s = tap - r * p.S;
-                                const int yy = a_y * p.stride - p.pad + r, xx = a_x * p.stride - p.pad + s;
+                                const int yy = a_y[q] * p.stride - p.pad + r, xx = a_x[q] * p.stride - p.pad + s;
                                 if (yy >= 0 && yy < p.H && xx >= 0 && xx < p.W)
-                                    v[j] = abase[(((long long)a_b * p.H + yy) * p.W + xx) * p.Cin + c];
+                                    v[j] = abase[(((long long)a_b[q] * p.H + yy) * p.W + xx) * p.Cin + c];
                             }
                         }
                     }
@@ -126,25 +129,25 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
                 const int i = tid + q * NT;
                 f4 v = {0.f, 0.f, 0.f, 0.f};
                 if (i < A_SLOTS) {
-                    const int kq = i / BM;
+                    const int kq = i & 3;
                     if (fastA) {
                         const int tap = k0 / p.Cout, c0 = k0 - tap * p.Cout;
                         const int ir = tap / d_ns, is = tap - ir * d_ns;
-                        const int ty = a_y + p.pad - (d_r0 + ir * p.stride), tx = a_x + p.pad - (d_s0 + is * p.stride);
+                        const int ty = a_y[q] + p.pad - (d_r0 + ir * p.stride), tx = a_x[q] + p.pad - (d_s0 + is * p.stride);
                         const int yo = ty / p.stride, xo = tx / p.stride;      // exact: the class fixes the residue
-                        if (a_ok && ty >= 0 && tx >= 0 && yo < p.Ho && xo < p.Wo)
-                            v = ld4(abase + (((long long)a_b * p.Ho + yo) * p.Wo + xo) * p.Cout + c0 + kq * 4);
+                        if (a_ok[q] && ty >= 0 && tx >= 0 && yo < p.Ho && xo < p.Wo)
+                            v = ld4(abase + (((long long)a_b[q] * p.Ho + yo) * p.Wo + xo) * p.Cout + c0 + kq * 4);
                     } else {
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
                             const int k = k0 + kq * 4 + j;
-                            if (a_ok && k < kend) {
+                            if (a_ok[q] && k < kend) {
                                 const int tap = k / p.Cout, c = k - tap * p.Cout;
                                 const int ir = tap / d_ns, is = tap - ir * d_ns;
-                                const int ty = a_y + p.pad - (d_r0 + ir * p.stride), tx = a_x + p.pad - (d_s0 + is * p.stride);
+                                const int ty = a_y[q] + p.pad - (d_r0 + ir * p.stride), tx = a_x[q] + p.pad - (d_s0 + is * p.stride);
                                 const int yo = ty / p.stride, xo = tx / p.stride;
                                 if (ty >= 0 && tx >= 0 && yo < p.Ho && xo < p.Wo)
-                                    v[j] = abase[(((long long)a_b * p.Ho + yo) * p.Wo + xo) * p.Cout + c];
+                                    v[j] = abase[(((long long)a_b[q] * p.Ho + yo) * p.Wo + xo) * p.Cout + c];
                             }
                         }
                     }
@@ -207,7 +210,7 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
                 const int i = tid + q * NT;
                 f4 v = {0.f, 0.f, 0.f, 0.f};
                 if (i < B_SLOTS) {
-                    const int n = n0 + i % BN, kq = i / BN;
+                    const int n = n0 + (i >> 2), kq = i & 3;
                     if (n < p.N) {
                         if (fastB) {
                             const int t = k0 / p.Cout, c0 = k0 - t * p.Cout;
@@ -260,7 +263,7 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
                 if (MODE == kWgrad) {
                     *reinterpret_cast<f4*>(&sA[buf][i / (BM / 4)][(i % (BM / 4)) * 4]) = ra[q];
                 } else {
-                    const int ml = i % BM, kq = i / BM;
+                    const int ml = i >> 2, kq = i & 3;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) sA[buf][kq * 4 + j][ml] = ra[q][j];
                 }
@@ -271,7 +274,7 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
             const int i = tid + q * NT;
             if (i < B_SLOTS) {
                 if (MODE == kDgrad) {
-                    const int nl = i % BN, kq = i / BN;
+                    const int nl = i >> 2, kq = i & 3;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) sB[buf][kq * 4 + j][nl] = rb[q][j];
                 } else {
