@@ -23,21 +23,30 @@ PAPER_CONTEXT = {"speedup_vs_decentralized_fedavg": 3.15, "speedup_vs_pytorch_di
                  "hardware": "4x V100, PCIe 3.0 x8, CIFAR-10, time-to-max-accuracy (Table 1, Sec. 4.2)"}
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a plain copy of known size; see profiles/),
 # valid only while the kernel's source file is unchanged: (source file, sha256 at measurement, workload, bytes)
-TRAFFIC = {"aggregate": ("paper_2111_08274_amd/csrc/aggregate.hip",
-                         "82d23ef5563a057ede8300c4f42727e1f09a1ffe25e76238a46006f416269703", "agg-stress-n64",
-                         (174613.6 * 2.0 + 43648.5 * 1.0) * 1024.0)}
+TRAFFIC = {
+    ("aggregate", "agg-stress-n64"): (("paper_2111_08274_amd/csrc/aggregate.hip",),
+                                      "82d23ef5563a057ede8300c4f42727e1f09a1ffe25e76238a46006f416269703",
+                                      (174613.6 * 2.0 + 43648.5 * 1.0) * 1024.0),
+}
+
+
+def source_digest(files):
+    import hashlib
+    h = hashlib.sha256()
+    for f in files:
+        h.update(open(os.path.join(ROOT, f), "rb").read())
+    return h.hexdigest()
 
 
 def measured_traffic(kernel, workload):
-    import hashlib
-    ent = TRAFFIC.get(kernel)
-    if not ent or ent[2] != workload:
+    ent = TRAFFIC.get((kernel, workload))
+    if not ent:
         return None
     try:
-        digest = hashlib.sha256(open(os.path.join(ROOT, ent[0]), "rb").read()).hexdigest()
+        digest = source_digest(ent[0])
     except OSError:
         return None
-    return ent[3] if digest == ent[1] else None
+    return ent[2] if digest == ent[1] else None
 
 
 GEMM_KERNELS = ("conv_fwd", "conv_dgrad", "conv_wgrad", "dense_fwd", "dense_dgrad", "dense_wgrad")
@@ -234,11 +243,11 @@ def main():
     if dom in GEMM_KERNELS:
         ach = kd["flops"] / kd["launches"] / (avg_ms * 1e-3) / 1e12
         roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
-                "frac": ach / MFMA_PEAK_TFLOPS[dtype], "traffic": None}
+                "frac": ach / MFMA_PEAK_TFLOPS[dtype], "traffic": measured_traffic(dom, cfg["name"])}
     else:
         ach = kd["bytes"] / kd["launches"] / (avg_ms * 1e-3) / 1e9
         roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": None}
+                "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(dom, cfg["name"])}
     roof["avg_launch_ms"] = avg_ms
     roof["share_of_kernel_time"] = kd["ms"] / total_ms
     gemm_flops = sum(v["flops"] for n, v in prof.items() if n in GEMM_KERNELS) / n_prof
