@@ -29,6 +29,7 @@ typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 constexpr int BK = 32;
 constexpr int LDP = 40;      // LDS row pitch in bf16 elements (80 bytes: conflict-free 16-byte operand reads)
 constexpr int BM = 128;
+constexpr int kBigLds = 2 * (256 + 256) * 72 * 2;   // dynamic LDS of the 256 x 256 kernel: two buffers of both operands
 
 __device__ __forceinline__ u4 ldg16(const char* base, unsigned off) { return *reinterpret_cast<const u4*>(base + off); }
 
@@ -331,6 +332,151 @@ __global__ __launch_bounds__(256, 2) void conv_fast64_kernel(FastConvParams p)
     }
 }
 
+// 256 x 256 tile, 512 threads (wave grid 2 x 4, wave tile 128 x 64), slabs of 64, two LDS buffers (144 KiB dynamic LDS):
+// one barrier per slab; the next slab is written to the other buffer before the current one is multiplied.
+template <int EPI>
+__global__ __launch_bounds__(512, 1) void conv_big_kernel(FastConvParams p)
+{
+    constexpr int BMT = 256, BN = 256, BK2 = 64, LDQ = 72;
+    constexpr int TM = 4, TN = 2;
+    constexpr int NQA = 4, NQB = 4;                   // 256 rows x 8 chunks over 512 threads
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr unsigned A_BUF = BMT * LDQ * 2, B_BUF = BN * LDQ * 2;
+    char* const sAc = smem;                           // [2][BMT][LDQ]
+    char* const sBc = smem + 2 * A_BUF;               // [2][BN][LDQ]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int rep = p.order[blockIdx.z];
+    const int m0 = blockIdx.x * BMT, n0 = blockIdx.y * BN;
+    const char* abase = (const char*)p.a + (long long)rep * p.a_rep * 4;
+    const char* wbase = (const char*)(p.wmat + (long long)rep * p.wmat_rep);
+
+    unsigned aoff[NQA], boff[NQB], sa_st[NQA], sb_st[NQB], tapmask[NQA];
+    const int hw = p.H * p.W;
+#pragma unroll
+    for (int q = 0; q < NQA; ++q) {
+        const int i = tid + q * 512;
+        const int arow = i >> 3, kq = i & 7;
+        const int m = m0 + arow;
+        const bool a_ok = m < p.M;
+        const int bimg = m / hw, rem = m - bimg * hw, y = rem / p.W, x = rem - y * p.W;
+        unsigned mask = 0;
+        for (int t = 0; t < p.R * p.S; ++t) {
+            const int r = t / p.S, s = t - r * p.S;
+            const int yy = y + r - p.pad, xx = x + s - p.pad;
+            if (a_ok && yy >= 0 && yy < p.H && xx >= 0 && xx < p.W) mask |= 1u << t;
+        }
+        tapmask[q] = mask;
+        aoff[q] = (unsigned)(m * p.C + kq * 8) * 2u;
+        sa_st[q] = (unsigned)(arow * LDQ + kq * 8) * 2u;
+    }
+#pragma unroll
+    for (int q = 0; q < NQB; ++q) {
+        const int i = tid + q * 512;
+        boff[q] = (unsigned)((n0 + (i >> 3)) * p.K + (i & 7) * 8) * 2u;
+        sb_st[q] = (unsigned)((i >> 3) * LDQ + (i & 7) * 8) * 2u;
+    }
+    const unsigned a_rd = (unsigned)((wm * 128 + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
+    const unsigned b_rd = (unsigned)((wn * 64 + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
+
+    u4 ra[NQA], rb[NQB];
+    int tap = 0, c0 = 0;
+    auto load_tiles = [&]() {
+        const int r = tap / p.S, s = tap - r * p.S;
+        const int delta = (((r - p.pad) * p.W + (s - p.pad)) * p.C + c0) * 2;
+#pragma unroll
+        for (int q = 0; q < NQA; ++q) {
+            u4 v = {0u, 0u, 0u, 0u};
+            if ((tapmask[q] >> tap) & 1u) v = ldg16(abase, aoff[q] + (unsigned)delta);
+            ra[q] = v;
+        }
+        const unsigned kb = (unsigned)(tap * p.C + c0) * 2u;
+#pragma unroll
+        for (int q = 0; q < NQB; ++q) rb[q] = ldg16(wbase, boff[q] + kb);
+        c0 += BK2;
+        if (c0 == p.C) { c0 = 0; ++tap; }
+    };
+    auto store_tiles = [&](int buf) {
+#pragma unroll
+        for (int q = 0; q < NQA; ++q) *reinterpret_cast<u4*>(sAc + buf * A_BUF + sa_st[q]) = ra[q];
+#pragma unroll
+        for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sBc + buf * B_BUF + sb_st[q]) = rb[q];
+    };
+
+    f16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nslab = p.K / BK2;
+    load_tiles();
+    store_tiles(0);
+    if (nslab > 1) load_tiles();
+    __syncthreads();
+    for (int t = 0; t < nslab; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < nslab) {
+            store_tiles(buf ^ 1);                          // slab t+1 (in registers since the previous iteration)
+            if (t + 2 < nslab) load_tiles();               // slab t+2 travels while slab t is multiplied
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sAc + buf * A_BUF + a_rd + (i * 32 * LDQ + ks * 16) * 2);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sBc + buf * B_BUF + b_rd + (j * 32 * LDQ + ks * 16) * 2);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    char* obase = (char*)p.out + (long long)rep * p.out_rep * 4;
+    const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
+    const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int mm = m0 + wm * 128 + i * 32 + (lane & 31);
+        if (mm >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
+                const unsigned o = (unsigned)(mm * p.N + n) * 2u;
+                f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                if (EPI == 0) {
+                    if (bias) v += *reinterpret_cast<const f4*>(bias + n);
+                    if (p.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
+                } else {
+                    if (mask) {
+                        const bf16x4 mk = *reinterpret_cast<const bf16x4*>(mask + o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) if (!((float)mk[e] > 0.f)) v[e] = 0.f;
+                    }
+                    if (p.accumulate) {
+                        const bf16x4 old = *reinterpret_cast<const bf16x4*>(obase + o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += (float)old[e];
+                    }
+                }
+                bf16x4 r;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) r[e] = (__bf16)v[e];
+                *reinterpret_cast<bf16x4*>(obase + o) = r;
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------------
 // Weight gradient: dW[m = (tap, ci) | bias row][n = co] = sum over pixels k of x[k + tap][ci] * dy[k][co]
 // ---------------------------------------------------------------------------------------------------------------
@@ -519,11 +665,41 @@ void launch_conv_fast_t(const FastConvParams& p, int epi, int n_active, hipStrea
     else hipLaunchKernelGGL((conv_fast_kernel<BMT, BN, 1>), grid, block, 0, s, p);
 }
 
+struct BigTileInfo { int n_cu; bool lds_ok; };
+BigTileInfo query_big_tile()
+{
+    BigTileInfo b{256, false};
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) {
+        if (prop.multiProcessorCount > 0) b.n_cu = prop.multiProcessorCount;
+        b.lds_ok =
+            hipFuncSetAttribute((const void*)conv_big_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds) == hipSuccess &&
+            hipFuncSetAttribute((const void*)conv_big_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds) == hipSuccess;
+    }
+    (void)hipGetLastError();
+    return b;
+}
+
 }  // namespace
 
 hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
+    if (p.N % 256 == 0 && p.C % 64 == 0) {
+        // One 256 x 256 workgroup per compute unit at a time: worth it when the last round of workgroups is nearly full.
+        static const BigTileInfo big = query_big_tile();     // once per process (one GPU per process)
+        const int n_cu = big.n_cu;
+        const bool lds_ok = big.lds_ok;
+        const long long blocks = (long long)((p.M + 255) / 256) * (p.N / 256) * n_active;
+        const long long rounds = (blocks + n_cu - 1) / n_cu;
+        if (lds_ok && (p.tile_hint == 1 || blocks * 5 >= rounds * n_cu * 4)) {
+            const dim3 grid((unsigned)((p.M + 255) / 256), (unsigned)(p.N / 256), (unsigned)n_active), block(512);
+            if (epi == 0) hipLaunchKernelGGL(conv_big_kernel<0>, grid, block, kBigLds, s, p);
+            else hipLaunchKernelGGL(conv_big_kernel<1>, grid, block, kBigLds, s, p);
+            return hipGetLastError();
+        }
+    }
     const int bn = (p.N % 128 == 0) ? 128 : 64;
     // tall tiles halve the weight traffic and double the MFMA work per barrier; use them when they still fill the chip
     const bool tall = (long long)(p.M / 256) * (p.N / bn) * n_active >= 512;

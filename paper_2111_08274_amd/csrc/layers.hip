@@ -382,18 +382,30 @@ __global__ __launch_bounds__(256) void bn_sums_vec_kernel(BnParams p)
     }
 }
 
-// One thread per channel adds the per-chunk partial sums in chunk order.
+// A workgroup takes 32 channels; eight threads per channel add the per-chunk partial sums (chunks k, k+8, ..) and a
+// fixed-order tree over the eight joins them.
 // MODE 0: mean and 1/sqrt(var+eps) -> saved, running statistics updated.  x0 is the shift used by the sums pass.
 // MODE 1: totals of dy and dy*xhat -> gradient of beta and gamma, and into chunk 0 of the partial buffer.
 template <int MODE, typename T>
 __global__ __launch_bounds__(256) void bn_finalize_kernel(BnParams p)
 {
+    __shared__ float red[8][32][2];
     const int gi = blockIdx.y, rep = p.order[gi];
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= p.C) return;
+    const int cl = threadIdx.x & 31, kl = threadIdx.x >> 5;
+    const int c = blockIdx.x * 32 + cl;
+    const bool live = c < p.C;
     float* part = p.partial + gi * p.partial_rep;
     float s = 0.f, q = 0.f;
-    for (int k = 0; k < p.chunks; ++k) { s += part[(long long)k * 2 * p.C + c]; q += part[(long long)k * 2 * p.C + p.C + c]; }
+    if (live)
+        for (int k = kl; k < p.chunks; k += 8) { s += part[(long long)k * 2 * p.C + c]; q += part[(long long)k * 2 * p.C + p.C + c]; }
+    red[kl][cl][0] = s; red[kl][cl][1] = q;
+    __syncthreads();
+    for (int w = 4; w > 0; w >>= 1) {
+        if (kl < w) { red[kl][cl][0] += red[kl + w][cl][0]; red[kl][cl][1] += red[kl + w][cl][1]; }
+        __syncthreads();
+    }
+    if (kl != 0 || !live) return;
+    s = red[0][cl][0]; q = red[0][cl][1];
     if (MODE == 0) {
         const float n = (float)p.rows;
         const float x0 = ldf(tptr<T>(p.x, rep, p.x_rep), c);
@@ -623,7 +635,7 @@ hipError_t launch_bn_fwd(const BnParams& p0, int n_active, hipStream_t s)
     if (p.C % vec == 0) {
         p.cvb = bn_cvb(p.C, vec);
         const int cgroups = (p.C / vec + p.cvb - 1) / p.cvb;
-        const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 255) / 256), (unsigned)n_active);
+        const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 31) / 32), (unsigned)n_active);
         if (p.bf16) {
             hipLaunchKernelGGL((bn_sums_vec_kernel<0, __bf16>), grid, block, 0, s, p);
             hipLaunchKernelGGL((bn_finalize_kernel<0, __bf16>), fgrid, block, 0, s, p);
@@ -657,7 +669,7 @@ hipError_t launch_bn_bwd(const BnParams& p0, int n_active, hipStream_t s)
     if (p.C % vec == 0) {
         p.cvb = bn_cvb(p.C, vec);
         const int cgroups = (p.C / vec + p.cvb - 1) / p.cvb;
-        const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 255) / 256), (unsigned)n_active);
+        const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 31) / 32), (unsigned)n_active);
         if (p.bf16) {
             hipLaunchKernelGGL((bn_sums_vec_kernel<1, __bf16>), grid, block, 0, s, p);
             hipLaunchKernelGGL((bn_finalize_kernel<1, __bf16>), fgrid, block, 0, s, p);

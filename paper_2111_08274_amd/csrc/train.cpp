@@ -3,6 +3,7 @@
 // memory).  There is no host loop over replicas and no host read-back inside a cycle.
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 
 #include "train.h"
 #include "kernels.h"
@@ -40,6 +41,9 @@ public:
     std::vector<int64_t> wf_off, wb_off;  // per layer: offsets (bf16 elements) inside one replica's bf16 weight block
     int64_t wbf_rep = 0;                  // bf16 elements per replica
     int64_t wbf_off = 0;                  // start of the bf16 weight region inside `work` (floats)
+    // Environment variable HADFL_TILE_HINT, read when the engine is created: 1 makes the lean kernels take their
+    // 256 x 256 tiles wherever the layer shape allows, whatever the launch size (lets small problems exercise them).
+    int tile_hint = 0;
 };
 
 namespace {
@@ -141,6 +145,7 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
     e->shared_floats = L.shared_floats;
     e->fast = L.fast; e->wf_off = L.wf_off; e->wb_off = L.wb_off; e->wbf_rep = L.wbf_rep;
     e->wbf_off = e->shared_off + L.shared_floats;
+    if (const char* h = std::getenv("HADFL_TILE_HINT")) e->tile_hint = std::atoi(h);
     {
         const int nl = (int)plan.layers.size(), T = (int)plan.tensors.size();
         e->out_tensor.resize(nl); e->skip.assign(nl, 0); e->fused_relu.assign(nl, 0); e->masked.assign(T, 0);
@@ -276,7 +281,7 @@ struct Runner {
                 f.wmat = wbf() + e.wf_off[i]; f.wmat_rep = e.wbf_rep;
                 f.out = actw(ot); f.out_rep = e.rep_block;
                 f.bias = l.bias ? e.buf.replicas + l.b_off : nullptr; f.bias_rep = e.plan.row_stride;
-                f.relu = p.relu; f.order = e.buf.order;
+                f.relu = p.relu; f.order = e.buf.order; f.tile_hint = e.tile_hint;
                 run("conv_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_conv_fast(f, 0, na, s); });
                 break;
             }
@@ -388,7 +393,7 @@ struct Runner {
                     f.a = grad(ot); f.a_rep = e.rep_block;
                     f.wmat = wbf() + e.wb_off[i]; f.wmat_rep = e.wbf_rep;
                     f.out = grad(l.in0); f.out_rep = e.rep_block;
-                    f.mask = mask0; f.mask_rep = e.rep_block; f.accumulate = acc0; f.order = e.buf.order;
+                    f.mask = mask0; f.mask_rep = e.rep_block; f.accumulate = acc0; f.order = e.buf.order; f.tile_hint = e.tile_hint;
                     run("conv_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return launch_conv_fast(f, 1, na, s); });
                 } else
                 run(l.type == HADFL_OP_CONV ? "conv_dgrad" : "dense_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return gemm(d); });

@@ -50,6 +50,7 @@ struct FastConvParams {      // out[m][n] = sum_k act[pixel(m) + tap(k)][c(k)] *
     int relu;
     const void* mask; long long mask_rep; int accumulate;   // data gradient
     const int* order;
+    int tile_hint;                             // 1: take the 256 x 256 tiles whenever the shape allows (N % 256 == 0, C % 64 == 0)
 };
 // epi 0: forward (+bias, ReLU); epi 1: data gradient (mask, accumulate).  Needs C % 32 == 0 and N % 64 == 0.
 hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s);

@@ -144,3 +144,23 @@ def test_vgg16_full_width_bf16_against_oracle():
     print("vgg16 bf16 rel", d, flush=True)
     assert d <= REL
     p.close()
+
+
+def test_regular_layer_bf16_256_tiles(monkeypatch):
+    """Forward and data-gradient kernels with 256 x 256 tiles (one workgroup of eight waves per compute unit).  The
+    launcher only picks them when a launch fills the chip; the hint makes this small problem take them."""
+    monkeypatch.setenv("HADFL_TILE_HINT", "1")
+    b = nets._Builder()
+    t = b.relu(b.conv(0, 64))
+    t = b.relu(b.conv(t, 256))
+    t = b.relu(b.conv(t, 256))
+    b.dense(b.gap(t), 5)
+    ops, shape, batch = b.array(), (8, 8, 3), 5          # 320 rows per replica: one full and one ragged 256-row tile
+    N = 3
+    x, y = _data(N, batch, shape, 5, seed=78)
+    p = Pair(ops, shape, N, 2, x, y, batch, 0.01, 0.9, [2, 1, 1], bf16=True)
+    p.local_steps()
+    d = p.max_rel_diff()
+    print("256 tiles bf16 rel", d, "loss", p.gpu.losses(), p.cpu.loss, flush=True)
+    assert d <= REL
+    p.close()
