@@ -36,62 +36,90 @@ __device__ __forceinline__ u4 ldg16(const char* base, unsigned off) { return *re
 // ---------------------------------------------------------------------------------------------------------------
 // Forward / data-gradient: out[m][n] = sum_k act[pixel(m) + tap(k)][c(k)] * wmat[n][k]
 // ---------------------------------------------------------------------------------------------------------------
-template <int BMT, int BN, int EPI>     // EPI 0: + bias, optional ReLU, store bf16;  1: optional mask, optional accumulate
-__global__ __launch_bounds__(256, 2) void conv_fast_kernel(FastConvParams p)
+// Row order.  With a position table (p.perm) GEMM row m' = ps * B + b is image b at pixel position perm[ps], the
+// positions sorted by their set of in-bounds taps.  A tile then holds one or two positions of many images instead of
+// whole images, and the taps that are out of bounds for every row of the tile -- 5 of 9 in a corner -- are left out of
+// the K loop: their products are exact zeros.  Without a table rows are pixels in memory order and all taps are visited.
+struct RowGeo { int pix; unsigned tapmask; };
+__device__ __forceinline__ RowGeo row_geo(const FastConvParams& p, int m)
 {
-    constexpr int TM = BMT / 64, TN = BN / 64;  // wave grid 2 x 2, wave tile (BMT/2) x (BN/2)
-    constexpr int NQA = BMT / 64;               // A slots per thread (BMT rows x 4 groups of 8 k over 256 threads)
-    constexpr int NQB = BN / 64;
-    __shared__ __attribute__((aligned(16))) __bf16 sA[2][BMT][LDP];
-    __shared__ __attribute__((aligned(16))) __bf16 sB[2][BN][LDP];
+    RowGeo g; g.pix = 0; g.tapmask = 0;
+    if (m >= p.M) return g;
+    const int hw = p.H * p.W;
+    int pos;
+    if (p.perm) { const int ps = m / p.B, b = m - ps * p.B; pos = p.perm[ps]; g.pix = b * hw + pos; }
+    else { const int b = m / hw; pos = m - b * hw; g.pix = m; }
+    const int y = pos / p.W, x = pos - y * p.W;
+    for (int t = 0; t < p.R * p.S; ++t) {
+        const int r = t / p.S, s = t - r * p.S;
+        const int yy = y + r - p.pad, xx = x + s - p.pad;
+        if (yy >= 0 && yy < p.H && xx >= 0 && xx < p.W) g.tapmask |= 1u << t;
+    }
+    return g;
+}
+
+// Taps some row of the tile [m0, m0 + rows) can reach
+__device__ __forceinline__ unsigned tile_taps(const FastConvParams& p, int m0, int rows)
+{
+    const unsigned all = (p.R * p.S >= 32) ? 0xffffffffu : ((1u << (p.R * p.S)) - 1u);
+    if (!p.perm) return all;
+    const int last = min(m0 + rows, p.M) - 1;
+    unsigned u = 0;
+    for (int ps = m0 / p.B; ps <= last / p.B; ++ps) u |= p.posmask[ps];
+    return u & all;
+}
+
+// Tile BMT x BN, slabs of 64 along K, WGM x WGN waves (wave tile BMT/WGM x BN/WGN).  Eight neighbouring lanes read the
+// full 128-byte line a row contributes to a slab.  NBUF = 1: one LDS buffer, the next slab waits in registers while the
+// current one is multiplied, two barriers per slab.  NBUF = 2: the next slab is written to the other buffer before the
+// current one is multiplied, one barrier per slab.  LDS rows are padded to 72 elements (conflict-free 16-byte reads).
+// EPI 0: + bias, optional ReLU, store bf16;  EPI 1: optional mask, optional accumulate.
+template <int BMT, int BN, int WGM, int WGN, int NBUF, int EPI>
+__global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2) void conv_kernel(FastConvParams p)
+{
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int BK2 = 64, LDQ = 72;
+    constexpr int TM = BMT / WGM / 32, TN = BN / WGN / 32;
+    constexpr int NQA = BMT * 8 / NT, NQB = BN * 8 / NT;      // 16-byte slots per thread: rows x 8 groups of 8 k
+    static_assert(NQA >= 1 && NQB >= 1 && TM >= 1 && TN >= 1, "tile too small for the thread count");
+    constexpr unsigned A_BUF = BMT * LDQ * 2, B_BUF = BN * LDQ * 2;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* const sAc = smem;                           // [NBUF][BMT][LDQ]
+    char* const sBc = smem + NBUF * A_BUF;            // [NBUF][BN][LDQ]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int rep = p.order[blockIdx.z];
     const int m0 = blockIdx.x * BMT, n0 = blockIdx.y * BN;
     const char* abase = (const char*)p.a + (long long)rep * p.a_rep * 4;
     const char* wbase = (const char*)(p.wmat + (long long)rep * p.wmat_rep);
 
-    // ---- loop-invariant addressing ----
-    // Slot i of the tile = (row i / 4, k-group i % 4): four neighbouring lanes read the 64 contiguous bytes one row
-    // contributes to a slab, so a wave-wide load touches 16 rows x 64 bytes instead of 64 rows x 16 bytes and does
-    // not depend on the vector cache keeping partly used lines alive.
     unsigned aoff[NQA], boff[NQB], sa_st[NQA], sb_st[NQB], tapmask[NQA];
-    const int hw = p.H * p.W;
 #pragma unroll
     for (int q = 0; q < NQA; ++q) {
-        const int i = tid + q * 256;
-        const int arow = i >> 2, kq = i & 3;
-        const int m = m0 + arow;
-        const bool a_ok = m < p.M;
-        const int bimg = m / hw, rem = m - bimg * hw, y = rem / p.W, x = rem - y * p.W;
-        unsigned mask = 0;
-        for (int t = 0; t < p.R * p.S; ++t) {
-            const int r = t / p.S, s = t - r * p.S;
-            const int yy = y + r - p.pad, xx = x + s - p.pad;
-            if (a_ok && yy >= 0 && yy < p.H && xx >= 0 && xx < p.W) mask |= 1u << t;
-        }
-        tapmask[q] = mask;
-        aoff[q] = (unsigned)(m * p.C + kq * 8) * 2u;
-        sa_st[q] = (unsigned)(arow * LDP + kq * 8) * 2u;
+        const int i = tid + q * NT;
+        const int arow = i >> 3, kq = i & 7;
+        const RowGeo g = row_geo(p, m0 + arow);
+        tapmask[q] = g.tapmask;
+        aoff[q] = (unsigned)(g.pix * p.C + kq * 8) * 2u;
+        sa_st[q] = (unsigned)(arow * LDQ + kq * 8) * 2u;
     }
 #pragma unroll
     for (int q = 0; q < NQB; ++q) {
-        const int i = tid + q * 256;
-        boff[q] = (unsigned)((n0 + (i >> 2)) * p.K + (i & 3) * 8) * 2u;
-        sb_st[q] = (unsigned)((i >> 2) * LDP + (i & 3) * 8) * 2u;
+        const int i = tid + q * NT;
+        boff[q] = (unsigned)((n0 + (i >> 3)) * p.K + (i & 7) * 8) * 2u;
+        sb_st[q] = (unsigned)((i >> 3) * LDQ + (i & 7) * 8) * 2u;
     }
-    char* const sAc = reinterpret_cast<char*>(&sA[0][0][0]);
-    char* const sBc = reinterpret_cast<char*>(&sB[0][0][0]);
-    constexpr unsigned A_BUF = BMT * LDP * 2, B_BUF = BN * LDP * 2;
-    const unsigned a_rd = (unsigned)((wm * (BMT / 2) + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
-    const unsigned b_rd = (unsigned)((wn * (BN / 2) + (lane & 31)) * LDP + (lane >> 5) * 8) * 2u;
+    const unsigned a_rd = (unsigned)((wm * (BMT / WGM) + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
+    const unsigned b_rd = (unsigned)((wn * (BN / WGN) + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
 
-    // Two register sets: the loads of slab t+2 are issued before slab t is multiplied, and slab t+1 (loaded one
-    // iteration earlier) is written to LDS after it, so a global load has two full iterations to arrive.
-    u4 ra0[NQA], rb0[NQB], ra1[NQA], rb1[NQB];
-    int tap = 0, c0 = 0;                         // wave-uniform position of the next slab to load
-    auto load_tiles = [&](u4 (&ra)[NQA], u4 (&rb)[NQB]) {
+    // slabs: (tap, 64 channels) for the taps of this tile, taps ascending
+    const unsigned taps = tile_taps(p, m0, BMT);
+    const int nslab = __builtin_popcount(taps) * (p.C / BK2);
+    unsigned taps_left = taps;
+    int tap = taps ? __builtin_ctz(taps) : 0, c0 = 0;
+    u4 ra[NQA], rb[NQB];
+    auto load_tiles = [&]() {
         const int r = tap / p.S, s = tap - r * p.S;
         const int delta = (((r - p.pad) * p.W + (s - p.pad)) * p.C + c0) * 2;       // bytes, may be negative
 #pragma unroll
@@ -103,299 +131,12 @@ __global__ __launch_bounds__(256, 2) void conv_fast_kernel(FastConvParams p)
         const unsigned kb = (unsigned)(tap * p.C + c0) * 2u;
 #pragma unroll
         for (int q = 0; q < NQB; ++q) rb[q] = ldg16(wbase, boff[q] + kb);
-        c0 += BK;
-        if (c0 == p.C) { c0 = 0; ++tap; }
-    };
-    auto store_tiles = [&](int buf, const u4 (&ra)[NQA], const u4 (&rb)[NQB]) {
-#pragma unroll
-        for (int q = 0; q < NQA; ++q) *reinterpret_cast<u4*>(sAc + buf * A_BUF + sa_st[q]) = ra[q];
-#pragma unroll
-        for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sBc + buf * B_BUF + sb_st[q]) = rb[q];
-    };
-
-    f16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    auto compute = [&](int buf) {
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            bf16x8 a[TM], b[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sAc + buf * A_BUF + a_rd + (i * 32 * LDP + ks * 16) * 2);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sBc + buf * B_BUF + b_rd + (j * 32 * LDP + ks * 16) * 2);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)      // operands swapped: the accumulator holds the transposed tile
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
-        }
-    };
-
-    const int nslab = p.K / BK;
-    load_tiles(ra0, rb0);
-    store_tiles(0, ra0, rb0);
-    if (nslab > 1) load_tiles(ra0, rb0);          // slab 1 in flight in set 0
-    __syncthreads();
-    for (int t = 0; t < nslab; t += 2) {
-        if (t + 2 < nslab) load_tiles(ra1, rb1);  // slab t+2 -> set 1
-        compute(0);
-        if (t + 1 < nslab) store_tiles(1, ra0, rb0);
-        __syncthreads();
-        if (t + 1 < nslab) {
-            if (t + 3 < nslab) load_tiles(ra0, rb0);   // slab t+3 -> set 0
-            compute(1);
-            if (t + 2 < nslab) store_tiles(0, ra1, rb1);
-            __syncthreads();
-        }
-    }
-
-    // ---- epilogue: lane holds output pixel (lane & 31) and channels 8*g + 4*(lane >> 5) + {0..3}, g = 0..3 ----
-    char* obase = (char*)p.out + (long long)rep * p.out_rep * 4;
-    const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
-    const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int mm = m0 + wm * (BMT / 2) + i * 32 + (lane & 31);
-        if (mm >= p.M) continue;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * (BN / 2) + j * 32 + 8 * g + 4 * (lane >> 5);
-                const unsigned o = (unsigned)(mm * p.N + n) * 2u;
-                f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                if (EPI == 0) {
-                    if (bias) v += *reinterpret_cast<const f4*>(bias + n);
-                    if (p.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
-                } else {
-                    if (mask) {
-                        const bf16x4 mk = *reinterpret_cast<const bf16x4*>(mask + o);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) if (!((float)mk[e] > 0.f)) v[e] = 0.f;
-                    }
-                    if (p.accumulate) {
-                        const bf16x4 old = *reinterpret_cast<const bf16x4*>(obase + o);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] += (float)old[e];
-                    }
-                }
-                bf16x4 r;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) r[e] = (__bf16)v[e];
-                *reinterpret_cast<bf16x4*>(obase + o) = r;
-            }
-        }
-    }
-}
-
-// Same computation with slabs of 64: eight neighbouring lanes read the full 128-byte line a row contributes to a slab.
-// One LDS buffer (rows padded to 72 elements), the next slab waits in registers while the current one is multiplied.
-template <int BMT, int BN, int EPI>
-__global__ __launch_bounds__(256, 2) void conv_fast64_kernel(FastConvParams p)
-{
-    constexpr int BK2 = 64, LDQ = 72;
-    constexpr int TM = BMT / 64, TN = BN / 64;
-    constexpr int NQA = BMT / 32, NQB = BN / 32;      // slots per thread: rows x 8 groups of 8 k over 256 threads
-    __shared__ __attribute__((aligned(16))) __bf16 sA[BMT][LDQ];
-    __shared__ __attribute__((aligned(16))) __bf16 sB[BN][LDQ];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int rep = p.order[blockIdx.z];
-    const int m0 = blockIdx.x * BMT, n0 = blockIdx.y * BN;
-    const char* abase = (const char*)p.a + (long long)rep * p.a_rep * 4;
-    const char* wbase = (const char*)(p.wmat + (long long)rep * p.wmat_rep);
-
-    unsigned aoff[NQA], boff[NQB], sa_st[NQA], sb_st[NQB], tapmask[NQA];
-    const int hw = p.H * p.W;
-#pragma unroll
-    for (int q = 0; q < NQA; ++q) {
-        const int i = tid + q * 256;
-        const int arow = i >> 3, kq = i & 7;
-        const int m = m0 + arow;
-        const bool a_ok = m < p.M;
-        const int bimg = m / hw, rem = m - bimg * hw, y = rem / p.W, x = rem - y * p.W;
-        unsigned mask = 0;
-        for (int t = 0; t < p.R * p.S; ++t) {
-            const int r = t / p.S, s = t - r * p.S;
-            const int yy = y + r - p.pad, xx = x + s - p.pad;
-            if (a_ok && yy >= 0 && yy < p.H && xx >= 0 && xx < p.W) mask |= 1u << t;
-        }
-        tapmask[q] = mask;
-        aoff[q] = (unsigned)(m * p.C + kq * 8) * 2u;
-        sa_st[q] = (unsigned)(arow * LDQ + kq * 8) * 2u;
-    }
-#pragma unroll
-    for (int q = 0; q < NQB; ++q) {
-        const int i = tid + q * 256;
-        boff[q] = (unsigned)((n0 + (i >> 3)) * p.K + (i & 7) * 8) * 2u;
-        sb_st[q] = (unsigned)((i >> 3) * LDQ + (i & 7) * 8) * 2u;
-    }
-    char* const sAc = reinterpret_cast<char*>(&sA[0][0]);
-    char* const sBc = reinterpret_cast<char*>(&sB[0][0]);
-    const unsigned a_rd = (unsigned)((wm * (BMT / 2) + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
-    const unsigned b_rd = (unsigned)((wn * (BN / 2) + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
-
-    u4 ra[NQA], rb[NQB];
-    int tap = 0, c0 = 0;
-    auto load_tiles = [&]() {
-        const int r = tap / p.S, s = tap - r * p.S;
-        const int delta = (((r - p.pad) * p.W + (s - p.pad)) * p.C + c0) * 2;
-#pragma unroll
-        for (int q = 0; q < NQA; ++q) {
-            u4 v = {0u, 0u, 0u, 0u};
-            if ((tapmask[q] >> tap) & 1u) v = ldg16(abase, aoff[q] + (unsigned)delta);
-            ra[q] = v;
-        }
-        const unsigned kb = (unsigned)(tap * p.C + c0) * 2u;
-#pragma unroll
-        for (int q = 0; q < NQB; ++q) rb[q] = ldg16(wbase, boff[q] + kb);
         c0 += BK2;
-        if (c0 == p.C) { c0 = 0; ++tap; }
-    };
-
-    f16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    const int nslab = p.K / BK2;
-    load_tiles();
-    for (int t = 0; t < nslab; ++t) {
-        __syncthreads();                                   // every wave is done reading the previous slab
-#pragma unroll
-        for (int q = 0; q < NQA; ++q) *reinterpret_cast<u4*>(sAc + sa_st[q]) = ra[q];
-#pragma unroll
-        for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sBc + sb_st[q]) = rb[q];
-        __syncthreads();
-        if (t + 1 < nslab) load_tiles();
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 a[TM], b[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sAc + a_rd + (i * 32 * LDQ + ks * 16) * 2);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sBc + b_rd + (j * 32 * LDQ + ks * 16) * 2);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+        if (c0 == p.C) {
+            c0 = 0;
+            taps_left &= taps_left - 1u;                 // drop the tap just finished
+            tap = taps_left ? __builtin_ctz(taps_left) : 0;
         }
-    }
-
-    // ---- epilogue: lane holds output pixel (lane & 31) and channels 8*g + 4*(lane >> 5) + {0..3}, g = 0..3 ----
-    char* obase = (char*)p.out + (long long)rep * p.out_rep * 4;
-    const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
-    const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int mm = m0 + wm * (BMT / 2) + i * 32 + (lane & 31);
-        if (mm >= p.M) continue;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * (BN / 2) + j * 32 + 8 * g + 4 * (lane >> 5);
-                const unsigned o = (unsigned)(mm * p.N + n) * 2u;
-                f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                if (EPI == 0) {
-                    if (bias) v += *reinterpret_cast<const f4*>(bias + n);
-                    if (p.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
-                } else {
-                    if (mask) {
-                        const bf16x4 mk = *reinterpret_cast<const bf16x4*>(mask + o);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) if (!((float)mk[e] > 0.f)) v[e] = 0.f;
-                    }
-                    if (p.accumulate) {
-                        const bf16x4 old = *reinterpret_cast<const bf16x4*>(obase + o);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] += (float)old[e];
-                    }
-                }
-                bf16x4 r;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) r[e] = (__bf16)v[e];
-                *reinterpret_cast<bf16x4*>(obase + o) = r;
-            }
-        }
-    }
-}
-
-// 256 x 256 tile, 512 threads (wave grid 2 x 4, wave tile 128 x 64), slabs of 64, two LDS buffers (144 KiB dynamic LDS):
-// one barrier per slab; the next slab is written to the other buffer before the current one is multiplied.
-template <int EPI>
-__global__ __launch_bounds__(512, 1) void conv_big_kernel(FastConvParams p)
-{
-    constexpr int BMT = 256, BN = 256, BK2 = 64, LDQ = 72;
-    constexpr int TM = 4, TN = 2;
-    constexpr int NQA = 4, NQB = 4;                   // 256 rows x 8 chunks over 512 threads
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    constexpr unsigned A_BUF = BMT * LDQ * 2, B_BUF = BN * LDQ * 2;
-    char* const sAc = smem;                           // [2][BMT][LDQ]
-    char* const sBc = smem + 2 * A_BUF;               // [2][BN][LDQ]
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3;
-    const int rep = p.order[blockIdx.z];
-    const int m0 = blockIdx.x * BMT, n0 = blockIdx.y * BN;
-    const char* abase = (const char*)p.a + (long long)rep * p.a_rep * 4;
-    const char* wbase = (const char*)(p.wmat + (long long)rep * p.wmat_rep);
-
-    unsigned aoff[NQA], boff[NQB], sa_st[NQA], sb_st[NQB], tapmask[NQA];
-    const int hw = p.H * p.W;
-#pragma unroll
-    for (int q = 0; q < NQA; ++q) {
-        const int i = tid + q * 512;
-        const int arow = i >> 3, kq = i & 7;
-        const int m = m0 + arow;
-        const bool a_ok = m < p.M;
-        const int bimg = m / hw, rem = m - bimg * hw, y = rem / p.W, x = rem - y * p.W;
-        unsigned mask = 0;
-        for (int t = 0; t < p.R * p.S; ++t) {
-            const int r = t / p.S, s = t - r * p.S;
-            const int yy = y + r - p.pad, xx = x + s - p.pad;
-            if (a_ok && yy >= 0 && yy < p.H && xx >= 0 && xx < p.W) mask |= 1u << t;
-        }
-        tapmask[q] = mask;
-        aoff[q] = (unsigned)(m * p.C + kq * 8) * 2u;
-        sa_st[q] = (unsigned)(arow * LDQ + kq * 8) * 2u;
-    }
-#pragma unroll
-    for (int q = 0; q < NQB; ++q) {
-        const int i = tid + q * 512;
-        boff[q] = (unsigned)((n0 + (i >> 3)) * p.K + (i & 7) * 8) * 2u;
-        sb_st[q] = (unsigned)((i >> 3) * LDQ + (i & 7) * 8) * 2u;
-    }
-    const unsigned a_rd = (unsigned)((wm * 128 + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
-    const unsigned b_rd = (unsigned)((wn * 64 + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
-
-    u4 ra[NQA], rb[NQB];
-    int tap = 0, c0 = 0;
-    auto load_tiles = [&]() {
-        const int r = tap / p.S, s = tap - r * p.S;
-        const int delta = (((r - p.pad) * p.W + (s - p.pad)) * p.C + c0) * 2;
-#pragma unroll
-        for (int q = 0; q < NQA; ++q) {
-            u4 v = {0u, 0u, 0u, 0u};
-            if ((tapmask[q] >> tap) & 1u) v = ldg16(abase, aoff[q] + (unsigned)delta);
-            ra[q] = v;
-        }
-        const unsigned kb = (unsigned)(tap * p.C + c0) * 2u;
-#pragma unroll
-        for (int q = 0; q < NQB; ++q) rb[q] = ldg16(wbase, boff[q] + kb);
-        c0 += BK2;
-        if (c0 == p.C) { c0 = 0; ++tap; }
     };
     auto store_tiles = [&](int buf) {
 #pragma unroll
@@ -412,17 +153,7 @@ __global__ __launch_bounds__(512, 1) void conv_big_kernel(FastConvParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nslab = p.K / BK2;
-    load_tiles();
-    store_tiles(0);
-    if (nslab > 1) load_tiles();
-    __syncthreads();
-    for (int t = 0; t < nslab; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < nslab) {
-            store_tiles(buf ^ 1);                          // slab t+1 (in registers since the previous iteration)
-            if (t + 2 < nslab) load_tiles();               // slab t+2 travels while slab t is multiplied
-        }
+    auto compute = [&](int buf) {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             bf16x8 a[TM], b[TN];
@@ -433,25 +164,53 @@ __global__ __launch_bounds__(512, 1) void conv_big_kernel(FastConvParams p)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j)      // operands swapped: the accumulator holds the transposed tile
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
         }
-        __syncthreads();
+    };
+
+    if (nslab > 0) {
+        load_tiles();
+        if (NBUF == 1) {
+            for (int t = 0; t < nslab; ++t) {
+                __syncthreads();                               // every wave is done reading the previous slab
+                store_tiles(0);
+                __syncthreads();
+                if (t + 1 < nslab) load_tiles();
+                compute(0);
+            }
+        } else {
+            store_tiles(0);
+            if (nslab > 1) load_tiles();
+            __syncthreads();
+            for (int t = 0; t < nslab; ++t) {
+                const int buf = t & 1;
+                if (t + 1 < nslab) {
+                    store_tiles(buf ^ 1);                      // slab t+1 (in registers since the previous iteration)
+                    if (t + 2 < nslab) load_tiles();           // slab t+2 travels while slab t is multiplied
+                }
+                compute(buf);
+                __syncthreads();
+            }
+        }
     }
 
+    // ---- epilogue: lane holds output row (lane & 31) and channels 8*g + 4*(lane >> 5) + {0..3}, g = 0..3 ----
     char* obase = (char*)p.out + (long long)rep * p.out_rep * 4;
     const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
     const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int mm = m0 + wm * 128 + i * 32 + (lane & 31);
+        const int mm = m0 + wm * (BMT / WGM) + i * 32 + (lane & 31);
         if (mm >= p.M) continue;
+        int pix = mm;
+        if (p.perm) { const int ps = mm / p.B, b = mm - ps * p.B; pix = b * p.H * p.W + p.perm[ps]; }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * 64 + j * 32 + 8 * g + 4 * (lane >> 5);
-                const unsigned o = (unsigned)(mm * p.N + n) * 2u;
+                const int n = n0 + wn * (BN / WGN) + j * 32 + 8 * g + 4 * (lane >> 5);
+                const unsigned o = (unsigned)(pix * p.N + n) * 2u;
                 f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
                 if (EPI == 0) {
                     if (bias) v += *reinterpret_cast<const f4*>(bias + n);
@@ -538,17 +297,35 @@ __global__ __launch_bounds__(256, 2) void wgrad_fast_kernel(FastWgradParams p)
     const unsigned a_rd = rd_lane * PA + (unsigned)(wm * 64 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2u;
     const unsigned b_rd = rd_lane * PB + (unsigned)(wn * (BN / 2) + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2u;
 
+    // Contraction order.  With a position table, index k' = ps * B + b is image b at pixel perm[ps] (B a multiple of
+    // 32, so a slab of 32 holds one position); a slab whose position cannot reach any tap of this row tile contributes
+    // exact zeros and is left out.  Without a table k' is the pixel index and every slab is visited.
+    const int hw = p.H * p.W;
+    unsigned tile_tapbits = 0xffffffffu;
+    if (p.perm && !(p.has_bias && m0 <= mw && mw < m0 + BM)) {
+        const int tlo = m0 / p.C, thi = min(m0 + BM - 1, mw - 1) / p.C;
+        tile_tapbits = (thi >= 31 ? 0xffffffffu : ((2u << thi) - 1u)) & ~((1u << tlo) - 1u);
+    }
+    auto next_slab = [&](int k) {
+        if (p.perm)
+            while (k < kend && !(p.posmask[k / p.B] & tile_tapbits)) k += BK;
+        return k;
+    };
     u4 ra[2], rb[NQB];
     auto load_tiles = [&](int k0) {
+        int ps = 0, bbase = 0, pos = 0;
+        if (p.perm) { ps = k0 / p.B; bbase = k0 - ps * p.B; pos = p.perm[ps]; }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int kk = k0 + krow + 16 * h;
             u4 v = {0u, 0u, 0u, 0u};
             if (kk < kend) {
                 if (a_kind == 0) {
-                    const int yy = ((kk >> p.w_shift) & (p.H - 1)) + ady, xx = (kk & (p.W - 1)) + adx;
+                    int pix = kk, ppos = kk;
+                    if (p.perm) { pix = (bbase + krow + 16 * h) * hw + pos; ppos = pos; }
+                    const int yy = ((ppos >> p.w_shift) & (p.H - 1)) + ady, xx = (ppos & (p.W - 1)) + adx;
                     if (yy >= 0 && yy < p.H && xx >= 0 && xx < p.W)
-                        v = ldg16(xbase, (unsigned)(kk * p.C * 2 + a_shift));
+                        v = ldg16(xbase, (unsigned)(pix * p.C * 2 + a_shift));
                 } else if (a_kind == 1) {
                     v[0] = 0x3f80u;                 // bf16 1.0 in the first of the 8 rows
                 }
@@ -559,7 +336,11 @@ __global__ __launch_bounds__(256, 2) void wgrad_fast_kernel(FastWgradParams p)
         for (int q = 0; q < NQB; ++q) {
             const int kk = k0 + bkrow + (BK / NQB) * q;
             u4 w = {0u, 0u, 0u, 0u};
-            if (kk < kend) w = ldg16(dbase, (unsigned)(kk * p.N) * 2u + bnoff);
+            if (kk < kend) {
+                int pix = kk;
+                if (p.perm) pix = (bbase + bkrow + (BK / NQB) * q) * hw + pos;
+                w = ldg16(dbase, (unsigned)(pix * p.N) * 2u + bnoff);
+            }
             rb[q] = w;
         }
     };
@@ -578,12 +359,12 @@ __global__ __launch_bounds__(256, 2) void wgrad_fast_kernel(FastWgradParams p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nslab = (kend - kbeg + BK - 1) / BK;
-    if (nslab > 0) { load_tiles(kbeg); store_tiles(0); }
+    int k0 = next_slab(kbeg), buf = 0;
+    if (k0 < kend) { load_tiles(k0); store_tiles(0); }
     __syncthreads();
-    for (int t = 0; t < nslab; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < nslab) load_tiles(kbeg + (t + 1) * BK);
+    while (k0 < kend) {
+        const int k1 = next_slab(k0 + BK);
+        if (k1 < kend) load_tiles(k1);
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             bf16x8 a[2], b[TN];
@@ -597,8 +378,9 @@ __global__ __launch_bounds__(256, 2) void wgrad_fast_kernel(FastWgradParams p)
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
         }
-        if (t + 1 < nslab) store_tiles(buf ^ 1);
+        if (k1 < kend) store_tiles(buf ^ 1);
         __syncthreads();
+        buf ^= 1; k0 = k1;
     }
 
     float* obase = (p.splits > 1) ? p.out + (long long)g * p.out_rep + (long long)split * p.out_split
@@ -649,22 +431,16 @@ __global__ __launch_bounds__(256) void weight_prep_kernel(WeightPrepParams p)
     }
 }
 
-template <int BMT, int BN>
-void launch_conv_fast64_t(const FastConvParams& p, int epi, int n_active, hipStream_t s)
+template <int BMT, int BN, int WGM, int WGN, int NBUF>
+void launch_conv_t(const FastConvParams& p, int epi, int n_active, hipStream_t s)
 {
-    const dim3 grid((unsigned)((p.M + BMT - 1) / BMT), (unsigned)(p.N / BN), (unsigned)n_active), block(256);
-    if (epi == 0) hipLaunchKernelGGL((conv_fast64_kernel<BMT, BN, 0>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((conv_fast64_kernel<BMT, BN, 1>), grid, block, 0, s, p);
+    constexpr size_t lds = (size_t)NBUF * (BMT + BN) * 72 * 2;
+    const dim3 grid((unsigned)((p.M + BMT - 1) / BMT), (unsigned)(p.N / BN), (unsigned)n_active), block(WGM * WGN * 64);
+    if (epi == 0) hipLaunchKernelGGL((conv_kernel<BMT, BN, WGM, WGN, NBUF, 0>), grid, block, lds, s, p);
+    else hipLaunchKernelGGL((conv_kernel<BMT, BN, WGM, WGN, NBUF, 1>), grid, block, lds, s, p);
 }
 
-template <int BMT, int BN>
-void launch_conv_fast_t(const FastConvParams& p, int epi, int n_active, hipStream_t s)
-{
-    const dim3 grid((unsigned)((p.M + BMT - 1) / BMT), (unsigned)(p.N / BN), (unsigned)n_active), block(256);
-    if (epi == 0) hipLaunchKernelGGL((conv_fast_kernel<BMT, BN, 0>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((conv_fast_kernel<BMT, BN, 1>), grid, block, 0, s, p);
-}
-
+// The 256 x 256 kernel needs 144 KiB of LDS, which a kernel has to ask for
 struct BigTileInfo { int n_cu; bool lds_ok; };
 BigTileInfo query_big_tile()
 {
@@ -674,8 +450,8 @@ BigTileInfo query_big_tile()
     if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) {
         if (prop.multiProcessorCount > 0) b.n_cu = prop.multiProcessorCount;
         b.lds_ok =
-            hipFuncSetAttribute((const void*)conv_big_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds) == hipSuccess &&
-            hipFuncSetAttribute((const void*)conv_big_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds) == hipSuccess;
+            hipFuncSetAttribute((const void*)conv_kernel<256, 256, 2, 4, 2, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds) == hipSuccess &&
+            hipFuncSetAttribute((const void*)conv_kernel<256, 256, 2, 4, 2, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, kBigLds) == hipSuccess;
     }
     (void)hipGetLastError();
     return b;
@@ -686,34 +462,26 @@ BigTileInfo query_big_tile()
 hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
-    if (p.N % 256 == 0 && p.C % 64 == 0) {
+    if (p.C % 64 != 0 || p.N % 64 != 0) return hipErrorInvalidValue;
+    if (p.N % 256 == 0) {
         // One 256 x 256 workgroup per compute unit at a time: worth it when the last round of workgroups is nearly full.
         static const BigTileInfo big = query_big_tile();     // once per process (one GPU per process)
-        const int n_cu = big.n_cu;
-        const bool lds_ok = big.lds_ok;
         const long long blocks = (long long)((p.M + 255) / 256) * (p.N / 256) * n_active;
-        const long long rounds = (blocks + n_cu - 1) / n_cu;
-        if (lds_ok && (p.tile_hint == 1 || blocks * 5 >= rounds * n_cu * 4)) {
-            const dim3 grid((unsigned)((p.M + 255) / 256), (unsigned)(p.N / 256), (unsigned)n_active), block(512);
-            if (epi == 0) hipLaunchKernelGGL(conv_big_kernel<0>, grid, block, kBigLds, s, p);
-            else hipLaunchKernelGGL(conv_big_kernel<1>, grid, block, kBigLds, s, p);
+        const long long rounds = (blocks + big.n_cu - 1) / big.n_cu;
+        if (big.lds_ok && (p.tile_hint == 1 || blocks * 5 >= rounds * big.n_cu * 4)) {
+            launch_conv_t<256, 256, 2, 4, 2>(p, epi, n_active, s);
             return hipGetLastError();
         }
     }
     const int bn = (p.N % 128 == 0) ? 128 : 64;
     // tall tiles halve the weight traffic and double the MFMA work per barrier; use them when they still fill the chip
     const bool tall = (long long)(p.M / 256) * (p.N / bn) * n_active >= 512;
-    const bool k64 = p.C % 64 == 0;
     if (bn == 128) {
-        if (tall && k64) launch_conv_fast64_t<256, 128>(p, epi, n_active, s);
-        else if (tall) launch_conv_fast_t<256, 128>(p, epi, n_active, s);
-        else if (k64) launch_conv_fast64_t<128, 128>(p, epi, n_active, s);
-        else launch_conv_fast_t<128, 128>(p, epi, n_active, s);
+        if (tall) launch_conv_t<256, 128, 2, 2, 1>(p, epi, n_active, s);
+        else launch_conv_t<128, 128, 2, 2, 1>(p, epi, n_active, s);
     } else {
-        if (tall && k64) launch_conv_fast64_t<256, 64>(p, epi, n_active, s);
-        else if (tall) launch_conv_fast_t<256, 64>(p, epi, n_active, s);
-        else if (k64) launch_conv_fast64_t<128, 64>(p, epi, n_active, s);
-        else launch_conv_fast_t<128, 64>(p, epi, n_active, s);
+        if (tall) launch_conv_t<256, 64, 2, 2, 1>(p, epi, n_active, s);
+        else launch_conv_t<128, 64, 2, 2, 1>(p, epi, n_active, s);
     }
     return hipGetLastError();
 }
@@ -721,6 +489,8 @@ hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipS
 hipError_t launch_wgrad_fast(const FastWgradParams& p, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
+    // position-sorted contraction: a slab of 32 must hold a single position
+    if (p.perm && (p.B % BK != 0 || (p.splits > 1 && p.kchunk % BK != 0))) return hipErrorInvalidValue;
     const int bn = (p.N % 128 == 0) ? 128 : 64;
     const dim3 grid((unsigned)(((p.M + BM - 1) / BM) * (p.N / bn)), (unsigned)p.splits, (unsigned)n_active), block(256);
     if (bn == 128) hipLaunchKernelGGL(wgrad_fast_kernel<128>, grid, block, 0, s, p);

@@ -44,6 +44,12 @@ public:
     // Environment variable HADFL_TILE_HINT, read when the engine is created: 1 makes the lean kernels take their
     // 256 x 256 tiles wherever the layer shape allows, whatever the launch size (lets small problems exercise them).
     int tile_hint = 0;
+    // Position tables of the regular convolution layers (see FastConvParams::perm): per layer HW sorted positions
+    // followed by HW tap masks, all layers back to back in `tables`; copied to `work` at tab_off by the first run.
+    std::vector<int64_t> tab_idx;         // per layer: start inside `tables`, or -1
+    std::vector<int32_t> tables;
+    int64_t tab_off = 0;                  // start of the table region inside `work` (floats)
+    bool tables_uploaded = false;
 };
 
 namespace {
@@ -57,11 +63,17 @@ struct Layout {
     std::vector<char> fast;
     std::vector<int64_t> wf_off, wb_off;
     int64_t wbf_rep = 0;
+    std::vector<int64_t> tab_idx;
+    int64_t tab_ints = 0;
 };
 
 bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 
 int64_t up64(int64_t v) { return (v + 63) / 64 * 64; }
+
+// Measured on 32 replicas of the VGG-16 shape: forward and data gradient gain up to 8 x 8 images, the weight gradient up
+// to 4 x 4; beyond that the scattered rows of a position-major tile cost more than the skipped taps save.
+constexpr int kMaxTablePositions = 64, kMaxTablePositionsWgrad = 16;
 
 Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
 {
@@ -114,6 +126,15 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
         }
         L.wbf_rep = woff;
     }
+    // position tables: worth it for small images (many border pixels), and the weight gradient needs slabs of 32
+    // contraction indices to hold a single position
+    L.tab_idx.assign(plan.layers.size(), -1);
+    for (size_t i = 0; i < plan.layers.size(); ++i) {
+        if (!L.fast[i] || cfg.batch % 32 != 0) continue;
+        const TensorShape a = plan.tensors[plan.layers[i].in0];
+        if (a.h * a.w > kMaxTablePositions) continue;
+        L.tab_idx[i] = L.tab_ints; L.tab_ints += 2 * (int64_t)a.h * a.w;
+    }
     return L;
 }
 
@@ -123,7 +144,7 @@ int64_t train_work_floats(const hadfl_config& cfg, const NetPlan& plan)
 {
     if (cfg.net == HADFL_NET_NONE) return 0;
     const Layout L = make_layout(cfg, plan);
-    return L.rep_block * cfg.n_replicas + L.shared_floats + up64(L.wbf_rep * cfg.n_replicas / 2 + 64);
+    return L.rep_block * cfg.n_replicas + L.shared_floats + up64(L.wbf_rep * cfg.n_replicas / 2 + 64) + up64(L.tab_ints);
 }
 
 hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const TrainBuffers& buf,
@@ -146,6 +167,28 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
     e->fast = L.fast; e->wf_off = L.wf_off; e->wb_off = L.wb_off; e->wbf_rep = L.wbf_rep;
     e->wbf_off = e->shared_off + L.shared_floats;
     if (const char* h = std::getenv("HADFL_TILE_HINT")) e->tile_hint = std::atoi(h);
+    e->tab_off = e->wbf_off + up64(L.wbf_rep * cfg.n_replicas / 2 + 64);
+    e->tab_idx = L.tab_idx;
+    e->tables.assign((size_t)L.tab_ints, 0);
+    for (size_t i = 0; i < plan.layers.size(); ++i) {
+        if (L.tab_idx[i] < 0) continue;
+        const Layer& l = plan.layers[i];
+        const TensorShape a = plan.tensors[l.in0];
+        const int hw = a.h * a.w;
+        std::vector<uint32_t> mask(hw, 0);
+        for (int pos = 0; pos < hw; ++pos)
+            for (int t = 0; t < l.k * l.k; ++t) {
+                const int yy = pos / a.w + t / l.k - l.pad, xx = pos % a.w + t % l.k - l.pad;
+                if (yy >= 0 && yy < a.h && xx >= 0 && xx < a.w) mask[pos] |= 1u << t;
+            }
+        std::vector<int32_t> perm(hw);
+        for (int pos = 0; pos < hw; ++pos) perm[pos] = pos;
+        std::stable_sort(perm.begin(), perm.end(), [&](int x, int y) { return mask[x] < mask[y]; });
+        for (int ps = 0; ps < hw; ++ps) {
+            e->tables[L.tab_idx[i] + ps] = perm[ps];
+            e->tables[L.tab_idx[i] + hw + ps] = (int32_t)mask[perm[ps]];
+        }
+    }
     {
         const int nl = (int)plan.layers.size(), T = (int)plan.tensors.size();
         e->out_tensor.resize(nl); e->skip.assign(nl, 0); e->fused_relu.assign(nl, 0); e->masked.assign(T, 0);
@@ -183,6 +226,12 @@ struct Runner {
     float* grad(int t) const { return e.buf.work + e.grad_off[t]; }
     float* shared() const { return e.buf.work + e.shared_off; }
     __bf16* wbf() const { return reinterpret_cast<__bf16*>(e.buf.work + e.wbf_off); }
+    const int* perm(size_t i) const { return e.tab_idx[i] < 0 ? nullptr : reinterpret_cast<const int*>(e.buf.work + e.tab_off) + e.tab_idx[i]; }
+    const unsigned* posmask(size_t i) const
+    {
+        const TensorShape a = e.plan.tensors[e.plan.layers[i].in0];
+        return e.tab_idx[i] < 0 ? nullptr : reinterpret_cast<const unsigned*>(e.buf.work + e.tab_off) + e.tab_idx[i] + a.h * a.w;
+    }
 
     // bf16 configuration: refresh the bf16 weight matrices of the regular convolution layers from the fp32 master
     void prepare_weights()
@@ -282,6 +331,7 @@ struct Runner {
                 f.out = actw(ot); f.out_rep = e.rep_block;
                 f.bias = l.bias ? e.buf.replicas + l.b_off : nullptr; f.bias_rep = e.plan.row_stride;
                 f.relu = p.relu; f.order = e.buf.order; f.tile_hint = e.tile_hint;
+                f.perm = perm(i); f.posmask = posmask(i);
                 run("conv_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_conv_fast(f, 0, na, s); });
                 break;
             }
@@ -359,8 +409,9 @@ struct Runner {
             p.splits = e.splits[i];
             const int64_t mn = (int64_t)p.M * p.N;
             if (p.splits > 1) {
-                const int slabs = (p.K + 15) / 16;
-                p.kchunk = ((slabs + p.splits - 1) / p.splits) * 16;
+                const int unit = e.fast[i] ? 32 : 16;      // slab length of the kernel that will run
+                const int slabs = (p.K + unit - 1) / unit;
+                p.kchunk = ((slabs + p.splits - 1) / p.splits) * unit;
                 p.out_split = (mn + 63) / 64 * 64;
                 p.out = shared(); p.out_rep = p.out_split * p.splits;
             } else {
@@ -372,6 +423,7 @@ struct Runner {
                 f.M = p.M; f.K = p.K; f.kchunk = p.kchunk; f.splits = p.splits; f.w_shift = p.w_shift; f.has_bias = l.bias;
                 f.x = act(l.in0); f.x_rep = e.rep_block; f.dy = grad(ot); f.dy_rep = e.rep_block;
                 f.out = p.out; f.out_rep = p.out_rep; f.out_split = p.out_split; f.order = e.buf.order;
+                if (p.H * p.W <= kMaxTablePositionsWgrad) { f.perm = perm(i); f.posmask = posmask(i); }
                 run("conv_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return launch_wgrad_fast(f, na, s); });
             } else
             run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return gemm(p); });
@@ -394,6 +446,7 @@ struct Runner {
                     f.wmat = wbf() + e.wb_off[i]; f.wmat_rep = e.wbf_rep;
                     f.out = grad(l.in0); f.out_rep = e.rep_block;
                     f.mask = mask0; f.mask_rep = e.rep_block; f.accumulate = acc0; f.order = e.buf.order; f.tile_hint = e.tile_hint;
+                    f.perm = perm(i); f.posmask = posmask(i);
                     run("conv_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return launch_conv_fast(f, 1, na, s); });
                 } else
                 run(l.type == HADFL_OP_CONV ? "conv_dgrad" : "dense_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return gemm(d); });
@@ -443,6 +496,11 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
     Runner r{*e, s, (prof && prof->on) ? prof : nullptr};
     const int N = e->cfg.n_replicas;
     r.run("zero_versions", 0, 0, [&] { return launch_fill_u32((uint32_t*)e->buf.versions, 0u, N, s); });
+    if (!e->tables_uploaded && !e->tables.empty()) {
+        const hipError_t rc = hipMemcpyAsync(e->buf.work + e->tab_off, e->tables.data(), e->tables.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+        if (rc != hipSuccess) { err = std::string("copy position tables: ") + hipGetErrorString(rc); return HADFL_EDEVICE; }
+        e->tables_uploaded = true;
+    }
     const int T = (int)e->plan.tensors.size();
     for (int step = 0; step < e->e_max && r.rc == hipSuccess; ++step) {
         r.na = e->n_active[step];

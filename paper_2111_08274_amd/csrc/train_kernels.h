@@ -50,9 +50,12 @@ struct FastConvParams {      // out[m][n] = sum_k act[pixel(m) + tap(k)][c(k)] *
     int relu;
     const void* mask; long long mask_rep; int accumulate;   // data gradient
     const int* order;
-    int tile_hint;                             // 1: take the 256 x 256 tiles whenever the shape allows (N % 256 == 0, C % 64 == 0)
+    int tile_hint;                             // 1: take the 256 x 256 tiles whenever the shape allows (N % 256 == 0)
+    // optional position table (both null or both set): GEMM row ps * B + b is image b at pixel perm[ps]; posmask[ps] has
+    // bit r * S + s set when tap (r, s) of that pixel lies inside the image
+    const int* perm; const unsigned* posmask;
 };
-// epi 0: forward (+bias, ReLU); epi 1: data gradient (mask, accumulate).  Needs C % 32 == 0 and N % 64 == 0.
+// epi 0: forward (+bias, ReLU); epi 1: data gradient (mask, accumulate).  Needs C % 64 == 0 and N % 64 == 0.
 hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s);
 
 struct FastWgradParams {     // dW[(tap, ci) | bias row][co] over pixels; needs C % 8 == 0, N % 64 == 0, H, W powers of two
@@ -61,6 +64,7 @@ struct FastWgradParams {     // dW[(tap, ci) | bias row][co] over pixels; needs 
     const void* dy; long long dy_rep;
     float* out; long long out_rep, out_split;
     const int* order;
+    const int* perm; const unsigned* posmask;   // optional position table as in FastConvParams; needs B % 32 == 0, kchunk % 32 == 0
 };
 hipError_t launch_wgrad_fast(const FastWgradParams& p, int n_active, hipStream_t s);
 
