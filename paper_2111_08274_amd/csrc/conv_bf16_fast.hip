@@ -26,10 +26,8 @@ typedef float f16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 
-constexpr int BK = 32;
-constexpr int LDP = 40;      // LDS row pitch in bf16 elements (80 bytes: conflict-free 16-byte operand reads)
-constexpr int BM = 128;
 constexpr int kBigLds = 2 * (256 + 256) * 72 * 2;   // dynamic LDS of the 256 x 256 kernel: two buffers of both operands
+constexpr int kBigWgradLds = 2 * 64 * 2 * (256 + 32) * 2;   // 256 x 256 weight-gradient kernel: two buffers of 64 rows per operand
 
 __device__ __forceinline__ u4 ldg16(const char* base, unsigned off) { return *reinterpret_cast<const u4*>(base + off); }
 
@@ -257,28 +255,37 @@ __device__ __forceinline__ bf16x8 lds_read_tr8(const char* base, unsigned off, u
     return __builtin_bit_cast(bf16x8, v);
 }
 
-template <int BN>
-__global__ __launch_bounds__(256, 2) void wgrad_fast_kernel(FastWgradParams p)
+// Tile BMT x BN, WGM x WGN waves, slabs of BKT contraction indices, two LDS buffers.
+template <int BMT, int BN, int WGM, int WGN, int BKT>
+__global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN == 8 ? 1 : 2) void wgrad_kernel(FastWgradParams p)
 {
-    constexpr int TN = BN / 64;
-    constexpr int PA = (BM + 16) * 2, PB = (BN + 16) * 2;   // row pitches in bytes: 4 rows x 32 bytes land in distinct banks
-    constexpr int NQB = BN / 64;                            // B octet slots per thread: 32 k x BN/8 octets over 256 threads
-    __shared__ __attribute__((aligned(16))) char sA[2][BK * PA];
-    __shared__ __attribute__((aligned(16))) char sB[2][BK * PB];
+    constexpr int NT = WGM * WGN * 64;
+    constexpr int TM = BMT / WGM / 32, TN = BN / WGN / 32;
+    // row pitches in bytes, 64 modulo 256: the 4 rows x 64 bytes that 32 lanes of a transposing read touch land in
+    // distinct banks
+    constexpr int PA = (BMT + 32) * 2, PB = (BN + 32) * 2;
+    constexpr int AOCT = BMT / 8, BOCT = BN / 8;            // 16-byte octets per contraction row
+    constexpr int AROWS = NT / AOCT, BROWS = NT / BOCT;     // contraction rows the threads cover per pass
+    constexpr int NQA = BKT / AROWS, NQB = BKT / BROWS;     // passes (slots per thread)
+    static_assert(NT % AOCT == 0 && NT % BOCT == 0 && NQA >= 1 && NQB >= 1 && BKT % AROWS == 0 && BKT % BROWS == 0, "");
+    constexpr unsigned A_BUF = BKT * PA, B_BUF = BKT * PB;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* const sA = smem;                                  // [2][BKT][PA]
+    char* const sB = smem + 2 * A_BUF;                      // [2][BKT][PB]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const int g = blockIdx.z;
     const int rep = p.order[g];
     const int tiles_n = p.N / BN;
-    const int m0 = (blockIdx.x / tiles_n) * BM, n0 = (blockIdx.x % tiles_n) * BN;
+    const int m0 = (blockIdx.x / tiles_n) * BMT, n0 = (blockIdx.x % tiles_n) * BN;
     const int split = blockIdx.y;
     const int kbeg = split * p.kchunk, kend = min(p.K, kbeg + p.kchunk);
     const char* xbase = (const char*)p.x + (long long)rep * p.x_rep * 4;
     const char* dbase = (const char*)p.dy + (long long)rep * p.dy_rep * 4;
 
-    // A slots of this thread: octet of rows (tid % 16) at pixels k0 + tid/16 and k0 + tid/16 + 16
-    const int oct = tid & 15, krow = tid >> 4;
+    // A slots of this thread: octet of rows (tid % AOCT) at contraction rows tid / AOCT + AROWS * q
+    const int oct = tid % AOCT, krow = tid / AOCT;
     const int am = m0 + oct * 8;
     const int mw = p.R * p.S * p.C;
     const int atap = am / p.C, aci = am - atap * p.C;
@@ -287,42 +294,41 @@ __global__ __launch_bounds__(256, 2) void wgrad_fast_kernel(FastWgradParams p)
     const int a_kind = am < mw ? 0 : (am == mw && p.has_bias ? 1 : 2);      // 0 data, 1 bias row of ones, 2 nothing
     const int a_shift = ((ady * p.W + adx) * p.C + aci) * 2;
     const unsigned sa_st = (unsigned)(krow * PA + oct * 16);
-    // B slots: BN = 128: octet tid % 16, rows tid/16 and +16;  BN = 64: octet tid % 8, row tid/8
-    constexpr int BOCT = BN / 8;
+    // B slots: octet tid % BOCT at contraction rows tid / BOCT + BROWS * q
     const int boct = tid % BOCT, bkrow = tid / BOCT;
     const unsigned sb_st = (unsigned)(bkrow * PB + boct * 16);
     const unsigned bnoff = (unsigned)(n0 + boct * 8) * 2u;
     // operand read offsets (see lds_read_tr8): lane L of a 16-lane group points at row L/4, columns 4*(L%4)
     const unsigned rd_lane = (unsigned)(((lane >> 5) * 8 + ((lane & 15) >> 2)));
-    const unsigned a_rd = rd_lane * PA + (unsigned)(wm * 64 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2u;
-    const unsigned b_rd = rd_lane * PB + (unsigned)(wn * (BN / 2) + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2u;
+    const unsigned a_rd = rd_lane * PA + (unsigned)(wm * (BMT / WGM) + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2u;
+    const unsigned b_rd = rd_lane * PB + (unsigned)(wn * (BN / WGN) + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2u;
 
     // Contraction order.  With a position table, index k' = ps * B + b is image b at pixel perm[ps] (B a multiple of
-    // 32, so a slab of 32 holds one position); a slab whose position cannot reach any tap of this row tile contributes
-    // exact zeros and is left out.  Without a table k' is the pixel index and every slab is visited.
+    // the slab length, so a slab holds one position); a slab whose position cannot reach any tap of this row tile
+    // contributes exact zeros and is left out.  Without a table k' is the pixel index and every slab is visited.
     const int hw = p.H * p.W;
     unsigned tile_tapbits = 0xffffffffu;
-    if (p.perm && !(p.has_bias && m0 <= mw && mw < m0 + BM)) {
-        const int tlo = m0 / p.C, thi = min(m0 + BM - 1, mw - 1) / p.C;
+    if (p.perm && !(p.has_bias && m0 <= mw && mw < m0 + BMT)) {
+        const int tlo = m0 / p.C, thi = min(m0 + BMT - 1, mw - 1) / p.C;
         tile_tapbits = (thi >= 31 ? 0xffffffffu : ((2u << thi) - 1u)) & ~((1u << tlo) - 1u);
     }
     auto next_slab = [&](int k) {
         if (p.perm)
-            while (k < kend && !(p.posmask[k / p.B] & tile_tapbits)) k += BK;
+            while (k < kend && !(p.posmask[k / p.B] & tile_tapbits)) k += BKT;
         return k;
     };
-    u4 ra[2], rb[NQB];
+    u4 ra[NQA], rb[NQB];
     auto load_tiles = [&](int k0) {
-        int ps = 0, bbase = 0, pos = 0;
-        if (p.perm) { ps = k0 / p.B; bbase = k0 - ps * p.B; pos = p.perm[ps]; }
+        int bbase = 0, pos = 0;
+        if (p.perm) { const int ps = k0 / p.B; bbase = k0 - ps * p.B; pos = p.perm[ps]; }
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int kk = k0 + krow + 16 * h;
+        for (int q = 0; q < NQA; ++q) {
+            const int kr = krow + AROWS * q, kk = k0 + kr;
             u4 v = {0u, 0u, 0u, 0u};
             if (kk < kend) {
                 if (a_kind == 0) {
                     int pix = kk, ppos = kk;
-                    if (p.perm) { pix = (bbase + krow + 16 * h) * hw + pos; ppos = pos; }
+                    if (p.perm) { pix = (bbase + kr) * hw + pos; ppos = pos; }
                     const int yy = ((ppos >> p.w_shift) & (p.H - 1)) + ady, xx = (ppos & (p.W - 1)) + adx;
                     if (yy >= 0 && yy < p.H && xx >= 0 && xx < p.W)
                         v = ldg16(xbase, (unsigned)(pix * p.C * 2 + a_shift));
@@ -330,15 +336,15 @@ __global__ __launch_bounds__(256, 2) void wgrad_fast_kernel(FastWgradParams p)
                     v[0] = 0x3f80u;                 // bf16 1.0 in the first of the 8 rows
                 }
             }
-            ra[h] = v;
+            ra[q] = v;
         }
 #pragma unroll
         for (int q = 0; q < NQB; ++q) {
-            const int kk = k0 + bkrow + (BK / NQB) * q;
+            const int kr = bkrow + BROWS * q, kk = k0 + kr;
             u4 w = {0u, 0u, 0u, 0u};
             if (kk < kend) {
                 int pix = kk;
-                if (p.perm) pix = (bbase + bkrow + (BK / NQB) * q) * hw + pos;
+                if (p.perm) pix = (bbase + kr) * hw + pos;
                 w = ldg16(dbase, (unsigned)(pix * p.N) * 2u + bnoff);
             }
             rb[q] = w;
@@ -346,14 +352,14 @@ __global__ __launch_bounds__(256, 2) void wgrad_fast_kernel(FastWgradParams p)
     };
     auto store_tiles = [&](int buf) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) *reinterpret_cast<u4*>(&sA[buf][sa_st + 16 * h * PA]) = ra[h];
+        for (int q = 0; q < NQA; ++q) *reinterpret_cast<u4*>(sA + buf * A_BUF + sa_st + AROWS * q * PA) = ra[q];
 #pragma unroll
-        for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(&sB[buf][sb_st + (BK / NQB) * q * PB]) = rb[q];
+        for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sB + buf * B_BUF + sb_st + BROWS * q * PB) = rb[q];
     };
 
-    f16 acc[2][TN];
+    f16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -363,17 +369,17 @@ __global__ __launch_bounds__(256, 2) void wgrad_fast_kernel(FastWgradParams p)
     if (k0 < kend) { load_tiles(k0); store_tiles(0); }
     __syncthreads();
     while (k0 < kend) {
-        const int k1 = next_slab(k0 + BK);
+        const int k1 = next_slab(k0 + BKT);
         if (k1 < kend) load_tiles(k1);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            bf16x8 a[2], b[TN];
+        for (int ks = 0; ks < BKT / 16; ++ks) {
+            bf16x8 a[TM], b[TN];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) a[i] = lds_read_tr8(&sA[buf][0], a_rd + ks * 16 * PA + i * 64, PA);
+            for (int i = 0; i < TM; ++i) a[i] = lds_read_tr8(sA + buf * A_BUF, a_rd + ks * 16 * PA + i * 64, PA);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = lds_read_tr8(&sB[buf][0], b_rd + ks * 16 * PB + j * 64, PB);
+            for (int j = 0; j < TN; ++j) b[j] = lds_read_tr8(sB + buf * B_BUF, b_rd + ks * 16 * PB + j * 64, PB);
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
@@ -386,14 +392,14 @@ __global__ __launch_bounds__(256, 2) void wgrad_fast_kernel(FastWgradParams p)
     float* obase = (p.splits > 1) ? p.out + (long long)g * p.out_rep + (long long)split * p.out_split
                                   : p.out + (long long)rep * p.out_rep;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int mm = m0 + wm * 64 + i * 32 + (lane & 31);
+    for (int i = 0; i < TM; ++i) {
+        const int mm = m0 + wm * (BMT / WGM) + i * 32 + (lane & 31);
         if (mm >= p.M) continue;
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * (BN / 2) + j * 32 + 8 * q + 4 * (lane >> 5);
+                const int n = n0 + wn * (BN / WGN) + j * 32 + 8 * q + 4 * (lane >> 5);
                 const f4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
                 *reinterpret_cast<f4*>(obase + (long long)mm * p.N + n) = v;
             }
@@ -489,12 +495,41 @@ hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipS
 hipError_t launch_wgrad_fast(const FastWgradParams& p, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
-    // position-sorted contraction: a slab of 32 must hold a single position
-    if (p.perm && (p.B % BK != 0 || (p.splits > 1 && p.kchunk % BK != 0))) return hipErrorInvalidValue;
-    const int bn = (p.N % 128 == 0) ? 128 : 64;
-    const dim3 grid((unsigned)(((p.M + BM - 1) / BM) * (p.N / bn)), (unsigned)p.splits, (unsigned)n_active), block(256);
-    if (bn == 128) hipLaunchKernelGGL(wgrad_fast_kernel<128>, grid, block, 0, s, p);
-    else hipLaunchKernelGGL(wgrad_fast_kernel<64>, grid, block, 0, s, p);
+    if (p.C % 8 != 0 || p.N % 64 != 0) return hipErrorInvalidValue;
+    // 256-row tiles (and 256 columns where the layer has them) when the launch still fills the chip
+    static const BigTileInfo big = query_big_tile();
+    int bmt = 128;
+    if (p.N % 256 == 0) {
+        const long long blocks = (long long)((p.M + 255) / 256) * (p.N / 256) * p.splits * n_active;
+        const long long rounds = (blocks + big.n_cu - 1) / big.n_cu;
+        if (p.tile_hint == 1 || blocks * 5 >= rounds * big.n_cu * 4) bmt = 256;
+    } else if (p.N % 128 == 0) {
+        if (p.tile_hint == 1 || (long long)((p.M + 255) / 256) * (p.N / 128) * p.splits * n_active >= 2LL * big.n_cu) bmt = 256;
+    }
+    const int bkt = bmt == 256 && p.N % 256 == 0 ? 64 : 32;
+    // position-sorted contraction: a slab must hold a single position
+    if (p.perm && (p.B % bkt != 0 || (p.splits > 1 && p.kchunk % bkt != 0))) return hipErrorInvalidValue;
+    if (bmt == 256 && p.N % 256 == 0) {
+        static const bool lds_ok = hipFuncSetAttribute((const void*)wgrad_kernel<256, 256, 2, 4, 64>,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kBigWgradLds) == hipSuccess;
+        if (!lds_ok) return hipErrorInvalidValue;
+        const dim3 grid((unsigned)(((p.M + 255) / 256) * (p.N / 256)), (unsigned)p.splits, (unsigned)n_active);
+        hipLaunchKernelGGL((wgrad_kernel<256, 256, 2, 4, 64>), grid, dim3(512), kBigWgradLds, s, p);
+    } else if (bmt == 256 && p.N % 128 == 0) {
+        constexpr size_t lds = 2 * 32 * ((256 + 32) * 2 + (128 + 32) * 2);
+        const dim3 grid((unsigned)(((p.M + 255) / 256) * (p.N / 128)), (unsigned)p.splits, (unsigned)n_active);
+        hipLaunchKernelGGL((wgrad_kernel<256, 128, 2, 2, 32>), grid, dim3(256), lds, s, p);
+    } else if (bmt == 128 && p.N % 128 == 0) {
+        constexpr size_t lds = 2 * 32 * ((128 + 32) * 2 + (128 + 32) * 2);
+        const dim3 grid((unsigned)(((p.M + 127) / 128) * (p.N / 128)), (unsigned)p.splits, (unsigned)n_active);
+        hipLaunchKernelGGL((wgrad_kernel<128, 128, 2, 2, 32>), grid, dim3(256), lds, s, p);
+    } else if (bmt == 128) {
+        constexpr size_t lds = 2 * 32 * ((128 + 32) * 2 + (64 + 32) * 2);
+        const dim3 grid((unsigned)(((p.M + 127) / 128) * (p.N / 64)), (unsigned)p.splits, (unsigned)n_active);
+        hipLaunchKernelGGL((wgrad_kernel<128, 64, 2, 2, 32>), grid, dim3(256), lds, s, p);
+    } else {
+        return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -409,7 +409,7 @@ struct Runner {
             p.splits = e.splits[i];
             const int64_t mn = (int64_t)p.M * p.N;
             if (p.splits > 1) {
-                const int unit = e.fast[i] ? 32 : 16;      // slab length of the kernel that will run
+                const int unit = e.fast[i] ? 64 : 16;      // slab length of the kernel that will run
                 const int slabs = (p.K + unit - 1) / unit;
                 p.kchunk = ((slabs + p.splits - 1) / p.splits) * unit;
                 p.out_split = (mn + 63) / 64 * 64;
@@ -423,7 +423,8 @@ struct Runner {
                 f.M = p.M; f.K = p.K; f.kchunk = p.kchunk; f.splits = p.splits; f.w_shift = p.w_shift; f.has_bias = l.bias;
                 f.x = act(l.in0); f.x_rep = e.rep_block; f.dy = grad(ot); f.dy_rep = e.rep_block;
                 f.out = p.out; f.out_rep = p.out_rep; f.out_split = p.out_split; f.order = e.buf.order;
-                if (p.H * p.W <= kMaxTablePositionsWgrad) { f.perm = perm(i); f.posmask = posmask(i); }
+                if (p.H * p.W <= kMaxTablePositionsWgrad && p.B % 64 == 0) { f.perm = perm(i); f.posmask = posmask(i); }
+                f.tile_hint = e.tile_hint;
                 run("conv_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return launch_wgrad_fast(f, na, s); });
             } else
             run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return gemm(p); });

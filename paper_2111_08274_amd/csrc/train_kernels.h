@@ -64,7 +64,8 @@ struct FastWgradParams {     // dW[(tap, ci) | bias row][co] over pixels; needs 
     const void* dy; long long dy_rep;
     float* out; long long out_rep, out_split;
     const int* order;
-    const int* perm; const unsigned* posmask;   // optional position table as in FastConvParams; needs B % 32 == 0, kchunk % 32 == 0
+    const int* perm; const unsigned* posmask;   // optional position table as in FastConvParams; needs B % 64 == 0, kchunk % 64 == 0
+    int tile_hint;                              // 1: 256-row tiles whenever N % 128 == 0
 };
 hipError_t launch_wgrad_fast(const FastWgradParams& p, int n_active, hipStream_t s);
 

@@ -168,20 +168,20 @@ def test_regular_layer_bf16_256_tiles(monkeypatch):
 
 @pytest.mark.parametrize("hint", ["0", "1"])
 def test_regular_layers_bf16_position_sorted_rows(monkeypatch, hint):
-    """Batch 32 on 8x8 / 4x4 / 2x2 images: the lean kernels order GEMM rows (and the weight gradient's contraction) by
-    pixel position and leave out the taps no row of a tile can reach.  hint 1 also sends the 256-wide layers through
-    the 256 x 256 tiles."""
+    """Batch 64 on 8x8 / 4x4 / 2x2 images: the lean kernels order GEMM rows (and the weight gradient's contraction) by
+    pixel position and leave out the taps no row of a tile can reach.  hint 1 also sends the 128- and 256-wide layers
+    through the 256-row tiles."""
     monkeypatch.setenv("HADFL_TILE_HINT", hint)
     b = nets._Builder()
     t = b.relu(b.conv(0, 64))
     t = b.relu(b.bn(b.conv(t, 64)))
     t = b.maxpool(t)
-    t = b.relu(b.conv(t, 256))
+    t = b.relu(b.conv(t, 128))
     t = b.relu(b.bn(b.conv(t, 256)))
     t = b.maxpool(t)
     t = b.relu(b.conv(t, 256))
     b.dense(b.gap(t), 5)
-    ops, shape, batch = b.array(), (8, 8, 3), 32
+    ops, shape, batch = b.array(), (8, 8, 3), 64
     N = 3
     x, y = _data(N, 2 * batch, shape, 5, seed=79)
     p = Pair(ops, shape, N, 2, x, y, batch, 0.01, 0.9, [2, 1, 1], bf16=True)
