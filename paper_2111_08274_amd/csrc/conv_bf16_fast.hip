@@ -389,20 +389,50 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN == 8 ? 1 : 2) void wgrad_
         buf ^= 1; k0 = k1;
     }
 
+    // ---- epilogue ----
+    // A lane holds row (lane & 31) of a 32 x 32 block and 16 of its columns in groups of four; stored like that, one
+    // instruction would touch 32 rows with 32 bytes each.  Each wave passes its blocks through a private piece of LDS
+    // (free now: every wave is past the last barrier of the K loop) and takes them back with eight lanes per row, so
+    // that global accesses cover whole 128-byte lines.
     float* obase = (p.splits > 1) ? p.out + (long long)g * p.out_rep + (long long)split * p.out_split
                                   : p.out + (long long)rep * p.out_rep;
+    float* const sgd_w = (p.splits == 1 && p.sgd_w) ? p.sgd_w + (long long)rep * p.out_rep : nullptr;
+    float* const sgd_buf = (sgd_w && p.sgd_buf) ? p.sgd_buf + (long long)rep * p.out_rep : nullptr;
+    constexpr int SP = 36;                                   // floats per staged row (144 bytes: conflict-free 16-byte writes)
+    static_assert((size_t)NT / 64 * 32 * SP * 4 <= 2 * (size_t)(A_BUF + B_BUF), "staging area does not fit the LDS of the K loop");
+    float* const stage = reinterpret_cast<float*>(smem) + wave * (32 * SP);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int mm = m0 + wm * (BMT / WGM) + i * 32 + (lane & 31);
-        if (mm >= p.M) continue;
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < TN; ++j) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * (BN / WGN) + j * 32 + 8 * q + 4 * (lane >> 5);
                 const f4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                *reinterpret_cast<f4*>(obase + (long long)mm * p.N + n) = v;
+                *reinterpret_cast<f4*>(stage + (lane & 31) * SP + 8 * q + 4 * (lane >> 5)) = v;
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int rr = (lane >> 3) + 8 * t, cc = (lane & 7) * 4;
+                const f4 v = *reinterpret_cast<const f4*>(stage + rr * SP + cc);
+                const int mm = m0 + wm * (BMT / WGM) + i * 32 + rr;
+                const int n = n0 + wn * (BN / WGN) + j * 32 + cc;
+                if (mm >= p.M) continue;
+                const long long o = (long long)mm * p.N + n;
+                if (sgd_w) {                 // complete gradient in registers: apply the update here
+                    f4 d = v;
+                    if (sgd_buf) { d = *reinterpret_cast<const f4*>(sgd_buf + o) * p.momentum + d; *reinterpret_cast<f4*>(sgd_buf + o) = d; }
+                    *reinterpret_cast<f4*>(sgd_w + o) = *reinterpret_cast<const f4*>(sgd_w + o) - d * p.lr;
+                } else {
+                    *reinterpret_cast<f4*>(obase + o) = v;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
     }
 }
 

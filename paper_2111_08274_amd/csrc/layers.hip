@@ -538,16 +538,16 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void sgd_kernel(SgdParams p)
 {
     const int rep = p.order[blockIdx.y];
-    f4* w = reinterpret_cast<f4*>(p.w + rep * p.row_stride);
-    const f4* g = reinterpret_cast<const f4*>(p.g + rep * p.row_stride);
-    f4* buf = p.buf ? reinterpret_cast<f4*>(p.buf + rep * p.row_stride) : nullptr;
+    f4* w = reinterpret_cast<f4*>(p.w + rep * p.row_stride + p.first);
+    const f4* g = reinterpret_cast<const f4*>(p.g + rep * p.row_stride + p.first);
+    f4* buf = p.buf ? reinterpret_cast<f4*>(p.buf + rep * p.row_stride + p.first) : nullptr;
     const long long n4 = p.count / 4;
     for (long long i = gtid(); i < n4; i += gstride()) {
         f4 d = g[i];
         if (buf) { d = buf[i] * p.momentum + d; buf[i] = d; }
         w[i] = w[i] - d * p.lr;
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) { p.cursor[rep] += 1; p.versions[rep] += 1; }
+    if (p.bump && blockIdx.x == 0 && threadIdx.x == 0) { p.cursor[rep] += 1; p.versions[rep] += 1; }
 }
 
 // Narrow dense layer (the classifier: out <= 16): one workgroup per sample row; threads stride over the input
@@ -705,7 +705,8 @@ hipError_t launch_softmax_ce(const LossParams& p, int n_active, hipStream_t s)
 hipError_t launch_sgd(const SgdParams& p, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
-    hipLaunchKernelGGL(sgd_kernel, ew_grid(p.count / 4, n_active), dim3(256), 0, s, p);
+    if (p.count % 4 != 0 || p.first % 4 != 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(sgd_kernel, ew_grid(p.count / 4 > 0 ? p.count / 4 : 1, n_active), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

@@ -44,6 +44,10 @@ public:
     // Environment variable HADFL_TILE_HINT, read when the engine is created: 1 makes the lean kernels take their
     // 256 x 256 tiles wherever the layer shape allows, whatever the launch size (lets small problems exercise them).
     int tile_hint = 0;
+    // Layers whose weight-gradient kernel applies the update itself (lean kernel, no split): their slices of the
+    // parameter rows, ascending; the update kernel runs over the segments in between.
+    std::vector<char> fused_update;       // per layer
+    std::vector<std::pair<int64_t, int64_t>> update_segments;   // [first, first + count) floats
     // Position tables of the regular convolution layers (see FastConvParams::perm): per layer HW sorted positions
     // followed by HW tap masks, all layers back to back in `tables`; copied to `work` at tab_off by the first run.
     std::vector<int64_t> tab_idx;         // per layer: start inside `tables`, or -1
@@ -167,6 +171,20 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
     e->fast = L.fast; e->wf_off = L.wf_off; e->wb_off = L.wb_off; e->wbf_rep = L.wbf_rep;
     e->wbf_off = e->shared_off + L.shared_floats;
     if (const char* h = std::getenv("HADFL_TILE_HINT")) e->tile_hint = std::atoi(h);
+    {
+        e->fused_update.assign(plan.layers.size(), 0);
+        int64_t pos = 0;
+        for (size_t i = 0; i < plan.layers.size(); ++i) {
+            const Layer& l = plan.layers[i];
+            if (!e->fast[i] || e->splits[i] != 1) continue;
+            const int64_t cnt = l.w_count + (l.bias ? l.cout : 0);      // bias sits directly behind the weights
+            if (l.w_off % 4 != 0 || cnt % 4 != 0 || l.w_off < pos || (l.bias && l.b_off != l.w_off + l.w_count)) continue;
+            e->fused_update[i] = 1;
+            if (l.w_off > pos) e->update_segments.push_back({pos, l.w_off - pos});
+            pos = l.w_off + cnt;
+        }
+        if (plan.train_end > pos) e->update_segments.push_back({pos, plan.train_end - pos});
+    }
     e->tab_off = e->wbf_off + up64(L.wbf_rep * cfg.n_replicas / 2 + 64);
     e->tab_idx = L.tab_idx;
     e->tables.assign((size_t)L.tab_ints, 0);
@@ -425,6 +443,10 @@ struct Runner {
                 f.out = p.out; f.out_rep = p.out_rep; f.out_split = p.out_split; f.order = e.buf.order;
                 if (p.H * p.W <= kMaxTablePositionsWgrad && p.B % 64 == 0) { f.perm = perm(i); f.posmask = posmask(i); }
                 f.tile_hint = e.tile_hint;
+                if (e.fused_update[i]) {
+                    f.sgd_w = e.buf.replicas + l.w_off; f.sgd_buf = e.buf.mom ? e.buf.mom + l.w_off : nullptr;
+                    f.lr = e.cfg.lr; f.momentum = e.cfg.momentum;
+                }
                 run("conv_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return launch_wgrad_fast(f, na, s); });
             } else
             run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return gemm(p); });
@@ -518,9 +540,14 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
         for (size_t i = e->plan.layers.size(); i-- > 0;) r.backward_layer(i);
         SgdParams sp{};
         sp.w = e->buf.replicas; sp.g = e->buf.grad; sp.buf = e->buf.mom; sp.row_stride = e->plan.row_stride;
-        sp.count = e->plan.train_end; sp.lr = e->cfg.lr; sp.momentum = e->cfg.momentum;
+        sp.lr = e->cfg.lr; sp.momentum = e->cfg.momentum;
         sp.cursor = e->buf.cursor; sp.versions = e->buf.versions; sp.order = e->buf.order;
-        r.run("sgd", 0, (e->buf.mom ? 20.0 : 12.0) * e->plan.m_train, [&] { return launch_sgd(sp, r.na, s); });
+        r.cur_layer = 0;
+        for (size_t k = 0; k < e->update_segments.size(); ++k) {
+            sp.first = e->update_segments[k].first; sp.count = e->update_segments[k].second;
+            sp.bump = k + 1 == e->update_segments.size();
+            r.run("sgd", 0, (e->buf.mom ? 20.0 : 12.0) * sp.count, [&] { return launch_sgd(sp, r.na, s); });
+        }
     }
     if (r.rc != hipSuccess) {
         err = std::string("kernel launch failed in ") + (r.failed ? r.failed : "?") + ": " + hipGetErrorString(r.rc);

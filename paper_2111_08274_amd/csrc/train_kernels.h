@@ -66,6 +66,9 @@ struct FastWgradParams {     // dW[(tap, ci) | bias row][co] over pixels; needs 
     const int* order;
     const int* perm; const unsigned* posmask;   // optional position table as in FastConvParams; needs B % 64 == 0, kchunk % 64 == 0
     int tile_hint;                              // 1: 256-row tiles whenever N % 128 == 0
+    // splits == 1 only: when sgd_w is set the epilogue applies the update (buf = momentum*buf + g; w -= lr*buf) to the
+    // layer's slice of the parameter rows (same per-replica stride as `out`) instead of storing the gradient
+    float* sgd_w; float* sgd_buf; float lr, momentum;
 };
 hipError_t launch_wgrad_fast(const FastWgradParams& p, int n_active, hipStream_t s);
 
@@ -144,7 +147,8 @@ hipError_t launch_softmax_ce(const LossParams& p, int n_active, hipStream_t s);
 struct SgdParams {
     float* w; const float* g; float* buf; long long row_stride; long long count;   // count = trainable extent (multiple of 4)
     float lr, momentum;
-    long long* cursor; int* versions;      // bumped once per replica per step
+    long long* cursor; int* versions;      // bumped once per replica per step (when bump is set)
+    long long first; int bump;             // the launch covers floats [first, first + count) of each row
     const int* order;
 };
 hipError_t launch_sgd(const SgdParams& p, int n_active, hipStream_t s);
