@@ -234,6 +234,149 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
     }
 }
 
+// Wide images (16 or 32 pixels per row) with few channels move more bytes per multiply-add than the general kernel can
+// fetch: it reads every activation once per tap.  Here a workgroup owns 256 consecutive pixels of one image (whole
+// rows), loads them ONCE per 64-channel slice together with their one-pixel border (zeros outside the image) into
+// LDS, and serves all R*S taps from that patch by shifting the row it reads; only the weights still stream per tap.
+// IW = image width; 3x3-style filters with pad = (R-1)/2 <= 1.  Wave grid 2 x 2, wave tile 128 x BN/2.
+template <int IW, int BN, int EPI>
+__global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
+{
+    constexpr int BMT = 256, LDQ = 72, PW = IW + 2, TR = BMT / IW, PR = (TR + 2) * PW;   // patch: (TR + 2) x (IW + 2) pixels
+    constexpr int TM = 4, TN = BN / 64;
+    constexpr int NQB = BN * 8 / 256;
+    constexpr int NQP = (PR * 8 + 255) / 256;                 // patch slots per thread
+    constexpr unsigned P_BYTES = PR * LDQ * 2;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* const sP = smem;                                    // [PR][LDQ] activations with border
+    char* const sB = smem + P_BYTES;                          // [BN][LDQ] weights of one tap and channel slice
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int rep = p.order[blockIdx.z];
+    const int m0 = blockIdx.x * BMT, n0 = blockIdx.y * BN;
+    const int img = m0 / (p.H * IW), y0 = (m0 - img * p.H * IW) / IW;          // first image row of the tile
+    const char* abase = (const char*)p.a + (long long)rep * p.a_rep * 4;
+    const char* wbase = (const char*)(p.wmat + (long long)rep * p.wmat_rep);
+
+    // patch slots: slot i = (patch pixel i / 8, 16-byte channel group i % 8)
+    int poff[NQP];                                            // byte offset of the source pixel's slice start, or -1
+    unsigned pst[NQP];
+#pragma unroll
+    for (int q = 0; q < NQP; ++q) {
+        const int i = tid + q * 256, pr = i >> 3, kq = i & 7;
+        const int py = pr / PW, px = pr - py * PW;
+        const int yy = y0 - 1 + py, xx = px - 1;
+        const bool ok = pr < PR && yy >= 0 && yy < p.H && xx >= 0 && xx < IW;
+        poff[q] = ok ? (((img * p.H + yy) * IW + xx) * p.C + kq * 8) * 2 : -1;
+        pst[q] = (unsigned)(pr * LDQ + kq * 8) * 2u;
+    }
+    unsigned boff[NQB], sb_st[NQB];
+#pragma unroll
+    for (int q = 0; q < NQB; ++q) {
+        const int i = tid + q * 256;
+        boff[q] = (unsigned)((n0 + (i >> 3)) * p.K + (i & 7) * 8) * 2u;
+        sb_st[q] = (unsigned)((i >> 3) * LDQ + (i & 7) * 8) * 2u;
+    }
+    unsigned a_rd[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int pm = wm * 128 + i * 32 + (lane & 31);
+        a_rd[i] = (unsigned)(((pm / IW) * PW + (pm % IW)) * LDQ + (lane >> 5) * 8) * 2u;
+    }
+    const unsigned b_rd = (unsigned)((wn * (BN / 2) + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
+
+    f16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int taps = p.R * p.S;
+    const int off0 = 1 - p.pad;                               // patch border is one pixel: tap (r, s) reads patch pixel + (r + off0, s + off0)
+    u4 rb[NQB];
+    auto load_w = [&](int tap, int cs) {
+        const unsigned kb = (unsigned)(tap * p.C + cs) * 2u;
+#pragma unroll
+        for (int q = 0; q < NQB; ++q) rb[q] = ldg16(wbase, boff[q] + kb);
+    };
+    for (int cs = 0; cs < p.C; cs += 64) {
+        u4 rp[NQP];
+#pragma unroll
+        for (int q = 0; q < NQP; ++q) {
+            u4 v = {0u, 0u, 0u, 0u};
+            if (poff[q] >= 0) v = ldg16(abase, (unsigned)(poff[q] + cs * 2));
+            rp[q] = v;
+        }
+        load_w(0, cs);
+        __syncthreads();                                      // every wave is done with the previous slice
+#pragma unroll
+        for (int q = 0; q < NQP; ++q)
+            if (tid + q * 256 < PR * 8) *reinterpret_cast<u4*>(sP + pst[q]) = rp[q];
+        for (int tap = 0; tap < taps; ++tap) {
+            if (tap > 0) __syncthreads();                     // every wave is done reading the previous tap's weights
+#pragma unroll
+            for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sB + sb_st[q]) = rb[q];
+            __syncthreads();
+            if (tap + 1 < taps) load_w(tap + 1, cs);
+            const int r = tap / p.S, s2 = tap - r * p.S;
+            const unsigned toff = (unsigned)(((r + off0) * PW + (s2 + off0)) * LDQ) * 2u;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                bf16x8 a[TM], b[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sP + a_rd[i] + toff + ks * 32);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sB + b_rd + (j * 32 * LDQ + ks * 16) * 2);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- epilogue: lane holds output row (lane & 31) and channels 8*g + 4*(lane >> 5) + {0..3}, g = 0..3 ----
+    char* obase = (char*)p.out + (long long)rep * p.out_rep * 4;
+    const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
+    const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int mm = m0 + wm * 128 + i * 32 + (lane & 31);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + wn * (BN / 2) + j * 32 + 8 * g + 4 * (lane >> 5);
+                const unsigned o = (unsigned)(mm * p.N + n) * 2u;
+                f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                if (EPI == 0) {
+                    if (bias) v += *reinterpret_cast<const f4*>(bias + n);
+                    if (p.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
+                } else {
+                    if (mask) {
+                        const bf16x4 mk = *reinterpret_cast<const bf16x4*>(mask + o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) if (!((float)mk[e] > 0.f)) v[e] = 0.f;
+                    }
+                    if (p.accumulate) {
+                        const bf16x4 old = *reinterpret_cast<const bf16x4*>(obase + o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += (float)old[e];
+                    }
+                }
+                bf16x4 r;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) r[e] = (__bf16)v[e];
+                *reinterpret_cast<bf16x4*>(obase + o) = r;
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------------------------
 // Weight gradient: dW[m = (tap, ci) | bias row][n = co] = sum over pixels k of x[k + tap][ci] * dy[k][co]
 // ---------------------------------------------------------------------------------------------------------------
@@ -499,6 +642,25 @@ hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipS
 {
     if (n_active < 1) return hipSuccess;
     if (p.C % 64 != 0 || p.N % 64 != 0) return hipErrorInvalidValue;
+    // wide images with at most 128 channels in and out: the patch kernel (tiles are whole rows of one image)
+    if ((p.W == 16 || p.W == 32) && p.C <= 128 && p.N <= 128 && p.R == p.S && p.R <= 3 && 2 * p.pad == p.R - 1 &&
+        (p.H * p.W) % 256 == 0 && p.M % 256 == 0 && p.tile_hint != 2) {
+        const int bn = (p.N % 128 == 0) ? 128 : 64;
+        const dim3 grid((unsigned)(p.M / 256), (unsigned)(p.N / bn), (unsigned)n_active), block(256);
+#define HADFL_PATCH(IW_, BN_) do { \
+            constexpr size_t lds = (size_t)((256 / IW_ + 2) * (IW_ + 2) + BN_) * 72 * 2; \
+            static const bool ok = hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess && \
+                                   hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess; \
+            if (!ok) return hipErrorInvalidValue; \
+            if (epi == 0) hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, 0>), grid, block, lds, s, p); \
+            else hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, 1>), grid, block, lds, s, p); } while (0)
+        if (p.W == 32 && bn == 128) HADFL_PATCH(32, 128);
+        else if (p.W == 32) HADFL_PATCH(32, 64);
+        else if (bn == 128) HADFL_PATCH(16, 128);
+        else HADFL_PATCH(16, 64);
+#undef HADFL_PATCH
+        return hipGetLastError();
+    }
     if (p.N % 256 == 0) {
         // One 256 x 256 workgroup per compute unit at a time: worth it when the last round of workgroups is nearly full.
         static const BigTileInfo big = query_big_tile();     // once per process (one GPU per process)

@@ -190,3 +190,26 @@ def test_regular_layers_bf16_position_sorted_rows(monkeypatch, hint):
     print("position-sorted rows bf16 rel", d, "loss", p.gpu.losses(), p.cpu.loss, flush=True)
     assert d <= REL
     p.close()
+
+
+@pytest.mark.parametrize("side,batch", [(16, 6), (32, 3)])
+def test_wide_image_layers_bf16_patch_kernel(side, batch):
+    """16- and 32-pixel-wide images with 64 / 128 channels: forward and data gradient run in the kernel that keeps a
+    256-pixel tile with its border in LDS and serves all nine taps from it (one and two 64-channel slices, 64 and 128
+    output channels, tiles at the top, middle and bottom of an image)."""
+    b = nets._Builder()
+    t = b.relu(b.conv(0, 64))
+    t = b.relu(b.bn(b.conv(t, 64)))
+    t = b.relu(b.conv(t, 128))
+    t = b.relu(b.bn(b.conv(t, 128)))
+    t = b.relu(b.conv(t, 64))
+    b.dense(b.gap(t), 5)
+    ops, shape = b.array(), (side, side, 3)
+    N = 3
+    x, y = _data(N, 2 * batch, shape, 5, seed=80 + side)
+    p = Pair(ops, shape, N, 2, x, y, batch, 0.01, 0.9, [2, 1, 1], bf16=True)
+    p.local_steps()
+    d = p.max_rel_diff()
+    print("patch kernel bf16 rel", side, d, "loss", p.gpu.losses(), p.cpu.loss, flush=True)
+    assert d <= REL
+    p.close()
