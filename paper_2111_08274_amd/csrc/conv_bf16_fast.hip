@@ -29,6 +29,18 @@ typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 constexpr int kBigLds = 2 * (256 + 256) * 72 * 2;   // dynamic LDS of the 256 x 256 kernel: two buffers of both operands
 constexpr int kBigWgradLds = 2 * 64 * 2 * (256 + 32) * 2;   // 256 x 256 weight-gradient kernel: two buffers of 64 rows per operand
 
+// Workgroups are handed to the eight accelerator dies in turn (workgroup i runs on die i % 8), and each die has its own
+// L2.  The kernels below take a one-dimensional grid of 8 * chunk workgroups and give die d the logical work items
+// [d * chunk, (d + 1) * chunk): consecutive items -- the tiles of one replica, which share its weights and activations --
+// meet in one L2 instead of being fetched from memory by all eight.
+constexpr int kDies = 8;
+__device__ __forceinline__ unsigned logical_block()
+{
+    const unsigned chunk = gridDim.x / kDies;
+    return (blockIdx.x % kDies) * chunk + blockIdx.x / kDies;
+}
+inline unsigned die_grid(long long items) { return (unsigned)((items + kDies - 1) / kDies * kDies); }
+
 __device__ __forceinline__ u4 ldg16(const char* base, unsigned off) { return *reinterpret_cast<const u4*>(base + off); }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -87,8 +99,12 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    const int rep = p.order[blockIdx.z];
-    const int m0 = blockIdx.x * BMT, n0 = blockIdx.y * BN;
+    // logical item = (slot, column tile, row tile), row tiles fastest
+    const unsigned tiles_m = (unsigned)(p.M + BMT - 1) / BMT, tiles_n = (unsigned)p.N / BN;
+    const unsigned item = logical_block();
+    if (item >= tiles_m * tiles_n * (unsigned)p.n_active) return;
+    const int rep = p.order[item / (tiles_m * tiles_n)];
+    const int m0 = (int)(item % tiles_m) * BMT, n0 = (int)((item / tiles_m) % tiles_n) * BN;
     const char* abase = (const char*)p.a + (long long)rep * p.a_rep * 4;
     const char* wbase = (const char*)(p.wmat + (long long)rep * p.wmat_rep);
 
@@ -253,8 +269,11 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int rep = p.order[blockIdx.z];
-    const int m0 = blockIdx.x * BMT, n0 = blockIdx.y * BN;
+    const unsigned tiles_m = (unsigned)p.M / BMT, tiles_n = (unsigned)p.N / BN;
+    const unsigned item = logical_block();
+    if (item >= tiles_m * tiles_n * (unsigned)p.n_active) return;
+    const int rep = p.order[item / (tiles_m * tiles_n)];
+    const int m0 = (int)(item % tiles_m) * BMT, n0 = (int)((item / tiles_m) % tiles_n) * BN;
     const int img = m0 / (p.H * IW), y0 = (m0 - img * p.H * IW) / IW;          // first image row of the tile
     const char* abase = (const char*)p.a + (long long)rep * p.a_rep * 4;
     const char* wbase = (const char*)(p.wmat + (long long)rep * p.wmat_rep);
@@ -418,11 +437,15 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN == 8 ? 1 : 2) void wgrad_
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    const int g = blockIdx.z;
+    // logical item = (slot, split, tile): the tiles of one split of one replica read the same pixels
+    const unsigned tiles_n = (unsigned)p.N / BN, tiles = (unsigned)((p.M + BMT - 1) / BMT) * tiles_n;
+    const unsigned item = logical_block();
+    if (item >= tiles * (unsigned)p.splits * (unsigned)p.n_active) return;
+    const int g = (int)(item / (tiles * (unsigned)p.splits));
     const int rep = p.order[g];
-    const int tiles_n = p.N / BN;
-    const int m0 = (blockIdx.x / tiles_n) * BMT, n0 = (blockIdx.x % tiles_n) * BN;
-    const int split = blockIdx.y;
+    const unsigned tile = item % tiles;
+    const int m0 = (int)(tile / tiles_n) * BMT, n0 = (int)(tile % tiles_n) * BN;
+    const int split = (int)((item / tiles) % (unsigned)p.splits);
     const int kbeg = split * p.kchunk, kend = min(p.K, kbeg + p.kchunk);
     const char* xbase = (const char*)p.x + (long long)rep * p.x_rep * 4;
     const char* dbase = (const char*)p.dy + (long long)rep * p.dy_rep * 4;
@@ -614,7 +637,7 @@ template <int BMT, int BN, int WGM, int WGN, int NBUF>
 void launch_conv_t(const FastConvParams& p, int epi, int n_active, hipStream_t s)
 {
     constexpr size_t lds = (size_t)NBUF * (BMT + BN) * 72 * 2;
-    const dim3 grid((unsigned)((p.M + BMT - 1) / BMT), (unsigned)(p.N / BN), (unsigned)n_active), block(WGM * WGN * 64);
+    const dim3 grid(die_grid((long long)((p.M + BMT - 1) / BMT) * (p.N / BN) * n_active)), block(WGM * WGN * 64);
     if (epi == 0) hipLaunchKernelGGL((conv_kernel<BMT, BN, WGM, WGN, NBUF, 0>), grid, block, lds, s, p);
     else hipLaunchKernelGGL((conv_kernel<BMT, BN, WGM, WGN, NBUF, 1>), grid, block, lds, s, p);
 }
@@ -638,15 +661,17 @@ BigTileInfo query_big_tile()
 
 }  // namespace
 
-hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s)
+hipError_t launch_conv_fast(const FastConvParams& p0, int epi, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
+    FastConvParams p = p0;
+    p.n_active = n_active;
     if (p.C % 64 != 0 || p.N % 64 != 0) return hipErrorInvalidValue;
     // wide images with at most 128 channels in and out: the patch kernel (tiles are whole rows of one image)
     if ((p.W == 16 || p.W == 32) && p.C <= 128 && p.N <= 128 && p.R == p.S && p.R <= 3 && 2 * p.pad == p.R - 1 &&
         (p.H * p.W) % 256 == 0 && p.M % 256 == 0 && p.tile_hint != 2) {
         const int bn = (p.N % 128 == 0) ? 128 : 64;
-        const dim3 grid((unsigned)(p.M / 256), (unsigned)(p.N / bn), (unsigned)n_active), block(256);
+        const dim3 grid(die_grid((long long)(p.M / 256) * (p.N / bn) * n_active)), block(256);
 #define HADFL_PATCH(IW_, BN_) do { \
             constexpr size_t lds = (size_t)((256 / IW_ + 2) * (IW_ + 2) + BN_) * 72 * 2; \
             static const bool ok = hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess && \
@@ -684,9 +709,11 @@ hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipS
     return hipGetLastError();
 }
 
-hipError_t launch_wgrad_fast(const FastWgradParams& p, int n_active, hipStream_t s)
+hipError_t launch_wgrad_fast(const FastWgradParams& p0, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
+    FastWgradParams p = p0;
+    p.n_active = n_active;
     if (p.C % 8 != 0 || p.N % 64 != 0) return hipErrorInvalidValue;
     // 256-row tiles (and 256 columns where the layer has them) when the launch still fills the chip
     static const BigTileInfo big = query_big_tile();
@@ -705,19 +732,19 @@ hipError_t launch_wgrad_fast(const FastWgradParams& p, int n_active, hipStream_t
         static const bool lds_ok = hipFuncSetAttribute((const void*)wgrad_kernel<256, 256, 2, 4, 64>,
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kBigWgradLds) == hipSuccess;
         if (!lds_ok) return hipErrorInvalidValue;
-        const dim3 grid((unsigned)(((p.M + 255) / 256) * (p.N / 256)), (unsigned)p.splits, (unsigned)n_active);
+        const dim3 grid(die_grid((long long)((p.M + 255) / 256) * (p.N / 256) * p.splits * n_active));
         hipLaunchKernelGGL((wgrad_kernel<256, 256, 2, 4, 64>), grid, dim3(512), kBigWgradLds, s, p);
     } else if (bmt == 256 && p.N % 128 == 0) {
         constexpr size_t lds = 2 * 32 * ((256 + 32) * 2 + (128 + 32) * 2);
-        const dim3 grid((unsigned)(((p.M + 255) / 256) * (p.N / 128)), (unsigned)p.splits, (unsigned)n_active);
+        const dim3 grid(die_grid((long long)((p.M + 255) / 256) * (p.N / 128) * p.splits * n_active));
         hipLaunchKernelGGL((wgrad_kernel<256, 128, 2, 2, 32>), grid, dim3(256), lds, s, p);
     } else if (bmt == 128 && p.N % 128 == 0) {
         constexpr size_t lds = 2 * 32 * ((128 + 32) * 2 + (128 + 32) * 2);
-        const dim3 grid((unsigned)(((p.M + 127) / 128) * (p.N / 128)), (unsigned)p.splits, (unsigned)n_active);
+        const dim3 grid(die_grid((long long)((p.M + 127) / 128) * (p.N / 128) * p.splits * n_active));
         hipLaunchKernelGGL((wgrad_kernel<128, 128, 2, 2, 32>), grid, dim3(256), lds, s, p);
     } else if (bmt == 128) {
         constexpr size_t lds = 2 * 32 * ((128 + 32) * 2 + (64 + 32) * 2);
-        const dim3 grid((unsigned)(((p.M + 127) / 128) * (p.N / 64)), (unsigned)p.splits, (unsigned)n_active);
+        const dim3 grid(die_grid((long long)((p.M + 127) / 128) * (p.N / 64) * p.splits * n_active));
         hipLaunchKernelGGL((wgrad_kernel<128, 64, 2, 2, 32>), grid, dim3(256), lds, s, p);
     } else {
         return hipErrorInvalidValue;

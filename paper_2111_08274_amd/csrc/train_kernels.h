@@ -54,6 +54,7 @@ struct FastConvParams {      // out[m][n] = sum_k act[pixel(m) + tap(k)][c(k)] *
     // optional position table (both null or both set): GEMM row ps * B + b is image b at pixel perm[ps]; posmask[ps] has
     // bit r * S + s set when tap (r, s) of that pixel lies inside the image
     const int* perm; const unsigned* posmask;
+    int n_active;                              // set by the launcher
 };
 // epi 0: forward (+bias, ReLU); epi 1: data gradient (mask, accumulate).  Needs C % 64 == 0 and N % 64 == 0.
 hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s);
@@ -69,6 +70,7 @@ struct FastWgradParams {     // dW[(tap, ci) | bias row][co] over pixels; needs 
     // splits == 1 only: when sgd_w is set the epilogue applies the update (buf = momentum*buf + g; w -= lr*buf) to the
     // layer's slice of the parameter rows (same per-replica stride as `out`) instead of storing the gradient
     float* sgd_w; float* sgd_buf; float lr, momentum;
+    int n_active;                               // set by the launcher
 };
 hipError_t launch_wgrad_fast(const FastWgradParams& p, int n_active, hipStream_t s);
 
