@@ -417,6 +417,43 @@ __device__ __forceinline__ bf16x8 lds_read_tr8(const char* base, unsigned off, u
     return __builtin_bit_cast(bf16x8, v);
 }
 
+// Epilogue of the weight-gradient kernels.  A lane holds row (lane & 31) of a 32 x 32 block and 16 of its columns in
+// groups of four; stored like that, one instruction would touch 32 rows with 32 bytes each.  Each wave passes its blocks
+// through a private piece of LDS (free once every wave is past the last barrier of the K loop) and takes them back with
+// eight lanes per row, so that global accesses cover whole 128-byte lines.  Rows from m_end on are not stored.
+// With sgd_w set the block is a complete gradient and the update (buf = momentum*buf + g; w -= lr*buf) is applied instead.
+constexpr int kStagePitch = 36;                              // floats per staged row (144 bytes: conflict-free 16-byte writes)
+__device__ __forceinline__ void store_block32(const f16& acc, float* stage, int lane, int m_base, int m_end, int n_base,
+                                              const FastWgradParams& p, float* obase, float* sgd_w, float* sgd_buf)
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const f4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        *reinterpret_cast<f4*>(stage + (lane & 31) * kStagePitch + 8 * q + 4 * (lane >> 5)) = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int rr = (lane >> 3) + 8 * t, cc = (lane & 7) * 4;
+        const f4 v = *reinterpret_cast<const f4*>(stage + rr * kStagePitch + cc);
+        const int mm = m_base + rr;
+        if (mm >= m_end) continue;
+        const long long o = (long long)mm * p.N + n_base + cc;
+        if (sgd_w) {
+            f4 d = v;
+            if (sgd_buf) { d = *reinterpret_cast<const f4*>(sgd_buf + o) * p.momentum + d; *reinterpret_cast<f4*>(sgd_buf + o) = d; }
+            *reinterpret_cast<f4*>(sgd_w + o) = *reinterpret_cast<const f4*>(sgd_w + o) - d * p.lr;
+        } else {
+            *reinterpret_cast<f4*>(obase + o) = v;
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Tile BMT x BN, WGM x WGN waves, slabs of BKT contraction indices, two LDS buffers.
 template <int BMT, int BN, int WGM, int WGN, int BKT>
 __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN == 8 ? 1 : 2) void wgrad_kernel(FastWgradParams p)
@@ -555,51 +592,141 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN == 8 ? 1 : 2) void wgrad_
         buf ^= 1; k0 = k1;
     }
 
-    // ---- epilogue ----
-    // A lane holds row (lane & 31) of a 32 x 32 block and 16 of its columns in groups of four; stored like that, one
-    // instruction would touch 32 rows with 32 bytes each.  Each wave passes its blocks through a private piece of LDS
-    // (free now: every wave is past the last barrier of the K loop) and takes them back with eight lanes per row, so
-    // that global accesses cover whole 128-byte lines.
+    // ---- epilogue (see store_block32) ----
     float* obase = (p.splits > 1) ? p.out + (long long)g * p.out_rep + (long long)split * p.out_split
                                   : p.out + (long long)rep * p.out_rep;
     float* const sgd_w = (p.splits == 1 && p.sgd_w) ? p.sgd_w + (long long)rep * p.out_rep : nullptr;
     float* const sgd_buf = (sgd_w && p.sgd_buf) ? p.sgd_buf + (long long)rep * p.out_rep : nullptr;
-    constexpr int SP = 36;                                   // floats per staged row (144 bytes: conflict-free 16-byte writes)
-    static_assert((size_t)NT / 64 * 32 * SP * 4 <= 2 * (size_t)(A_BUF + B_BUF), "staging area does not fit the LDS of the K loop");
-    float* const stage = reinterpret_cast<float*>(smem) + wave * (32 * SP);
+    static_assert((size_t)NT / 64 * 32 * kStagePitch * 4 <= 2 * (size_t)(A_BUF + B_BUF), "staging area does not fit the LDS of the K loop");
+    float* const stage = reinterpret_cast<float*>(smem) + wave * (32 * kStagePitch);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
+        for (int j = 0; j < TN; ++j)
+            store_block32(acc[i][j], stage, lane, m0 + wm * (BMT / WGM) + i * 32, p.M, n0 + wn * (BN / WGN) + j * 32, p, obase, sgd_w, sgd_buf);
+}
+
+// Wide images (16 or 32 pixels per row) with few channels: the kernel above reads every activation once per tap and
+// is bound by that traffic.  Here a workgroup owns ALL taps of a 64-channel input slice against 64 output channels:
+// per slab of 32 pixels (whole image rows) it loads those rows with their one-pixel border ONCE into LDS and forms
+// the nine shifted operands from that patch by offsetting the row the transposing read points at.
+// Waves: (input-channel half, output-channel half); each keeps nine 32 x 32 blocks (one per tap), the waves of the
+// first half of slice 0 also the bias row.  IW = image width; 3 x 3 filter, pad 1.
+template <int IW>
+__global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(FastWgradParams p)
+{
+    constexpr int PW = IW + 2, SR = 32 / IW, PP = (SR + 2) * PW;      // patch: (SR + 2) x (IW + 2) pixels
+    constexpr int PT = 192;                                         // bytes per patch pixel / dY row: 64 channels + pad (64 mod 256)
+    constexpr int NQP = (PP * 8 + 255) / 256;
+    constexpr unsigned P_BUF = PP * PT, D_BUF = 32 * PT;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* const sP = smem;                                          // [2][PP][PT]
+    char* const sD = smem + 2 * P_BUF;                              // [2][32][PT]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ch = wave & 1, nh = wave >> 1;
+    // logical item = (slot, split, input slice, output tile)
+    const unsigned cslices = (unsigned)p.C / 64, ntiles = (unsigned)p.N / 64, tiles = cslices * ntiles;
+    const unsigned item = logical_block();
+    if (item >= tiles * (unsigned)p.splits * (unsigned)p.n_active) return;
+    const int g = (int)(item / (tiles * (unsigned)p.splits));
+    const int rep = p.order[g];
+    const int split = (int)((item / tiles) % (unsigned)p.splits);
+    const int ci0 = (int)((item % tiles) / ntiles) * 64, n0 = (int)(item % ntiles) * 64;
+    const int kbeg = split * p.kchunk, kend = min(p.K, kbeg + p.kchunk);
+    const char* xbase = (const char*)p.x + (long long)rep * p.x_rep * 4;
+    const char* dbase = (const char*)p.dy + (long long)rep * p.dy_rep * 4;
+    const int hw = p.H * IW;
+
+    // patch slots: slot i = (patch pixel i / 8, 16-byte channel group i % 8)
+    int prel[NQP], pyy[NQP];                                        // source offset relative to the slab, row offset (or a value that never fits)
+    unsigned pst[NQP];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                *reinterpret_cast<f4*>(stage + (lane & 31) * SP + 8 * q + 4 * (lane >> 5)) = v;
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int rr = (lane >> 3) + 8 * t, cc = (lane & 7) * 4;
-                const f4 v = *reinterpret_cast<const f4*>(stage + rr * SP + cc);
-                const int mm = m0 + wm * (BMT / WGM) + i * 32 + rr;
-                const int n = n0 + wn * (BN / WGN) + j * 32 + cc;
-                if (mm >= p.M) continue;
-                const long long o = (long long)mm * p.N + n;
-                if (sgd_w) {                 // complete gradient in registers: apply the update here
-                    f4 d = v;
-                    if (sgd_buf) { d = *reinterpret_cast<const f4*>(sgd_buf + o) * p.momentum + d; *reinterpret_cast<f4*>(sgd_buf + o) = d; }
-                    *reinterpret_cast<f4*>(sgd_w + o) = *reinterpret_cast<const f4*>(sgd_w + o) - d * p.lr;
-                } else {
-                    *reinterpret_cast<f4*>(obase + o) = v;
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        }
+    for (int q = 0; q < NQP; ++q) {
+        const int i = tid + q * 256, pp = i >> 3, kq = i & 7;
+        const int py = pp / PW, px = pp - py * PW;
+        const bool ok = pp < PP && px >= 1 && px <= IW;
+        prel[q] = (((py - 1) * IW + (px - 1)) * p.C + ci0 + kq * 8) * 2;
+        pyy[q] = ok ? py - 1 : -(1 << 20);
+        pst[q] = (unsigned)(pp * PT + kq * 16);
     }
+    const unsigned dst = (unsigned)((tid >> 3) * PT + (tid & 7) * 16);
+    const unsigned doff = (unsigned)(((tid >> 3) * p.N + n0 + (tid & 7) * 8) * 2);
+
+    u4 rp[NQP], rd;
+    auto load_slab = [&](int k0) {
+        const int b = k0 / hw, y0 = (k0 - b * hw) / IW;
+        const int base = (b * hw + y0 * IW) * p.C * 2;
+#pragma unroll
+        for (int q = 0; q < NQP; ++q) {
+            u4 v = {0u, 0u, 0u, 0u};
+            const int yy = y0 + pyy[q];
+            if (yy >= 0 && yy < p.H) v = ldg16(xbase, (unsigned)(base + prel[q]));
+            rp[q] = v;
+        }
+        rd = ldg16(dbase, (unsigned)(k0 * p.N * 2) + doff);
+    };
+    auto store_slab = [&](int buf) {
+#pragma unroll
+        for (int q = 0; q < NQP; ++q)
+            if (tid + q * 256 < PP * 8) *reinterpret_cast<u4*>(sP + buf * P_BUF + pst[q]) = rp[q];
+        *reinterpret_cast<u4*>(sD + buf * D_BUF + dst) = rd;
+    };
+
+    // operand reads (see lds_read_tr8): the lane's contraction index inside a 16-block and its 4-column group
+    const int kl = (lane >> 5) * 8 + ((lane & 15) >> 2);
+    const unsigned col = (unsigned)((((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2);
+    unsigned a_rd[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        const int k = ks * 16 + kl;
+        a_rd[ks] = (unsigned)(((k / IW) * PW + (k % IW)) * PT) + (unsigned)(ch * 64) + col;
+    }
+    const unsigned b_rd = (unsigned)(kl * PT) + (unsigned)(nh * 64) + col;
+    const bool with_bias = p.has_bias && ci0 == 0 && ch == 0;
+    bf16x8 ones;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones[e] = (__bf16)((lane & 31) == 0 ? 1.0f : 0.0f);
+
+    f16 acc[9], accb;
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) accb[v] = 0.f;
+
+    int buf = 0;
+    if (kbeg < kend) { load_slab(kbeg); store_slab(0); }
+    __syncthreads();
+    for (int k0 = kbeg; k0 < kend; k0 += 32) {
+        if (k0 + 32 < kend) load_slab(k0 + 32);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const bf16x8 b = lds_read_tr8(sD + buf * D_BUF, b_rd + ks * 16 * PT, PT);
+#pragma unroll
+            for (int t = 0; t < 9; ++t) {
+                const bf16x8 a = lds_read_tr8(sP + buf * P_BUF, a_rd[ks] + (unsigned)(((t / 3) * PW + (t % 3)) * PT), PT);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[t], 0, 0, 0);
+            }
+            if (with_bias) accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, ones, accb, 0, 0, 0);
+        }
+        if (k0 + 32 < kend) store_slab(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    float* obase = (p.splits > 1) ? p.out + (long long)g * p.out_rep + (long long)split * p.out_split
+                                  : p.out + (long long)rep * p.out_rep;
+    float* const sgd_w = (p.splits == 1 && p.sgd_w) ? p.sgd_w + (long long)rep * p.out_rep : nullptr;
+    float* const sgd_buf = (sgd_w && p.sgd_buf) ? p.sgd_buf + (long long)rep * p.out_rep : nullptr;
+    static_assert(4 * 32 * kStagePitch * 4 <= 2 * (P_BUF + D_BUF), "staging area does not fit the LDS of the K loop");
+    float* const stage = reinterpret_cast<float*>(smem) + wave * (32 * kStagePitch);
+    const int mw = 9 * p.C;
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+        store_block32(acc[t], stage, lane, t * p.C + ci0 + ch * 32, mw, n0 + nh * 32, p, obase, sgd_w, sgd_buf);
+    if (with_bias) store_block32(accb, stage, lane, mw, mw + 1, n0 + nh * 32, p, obase, sgd_w, sgd_buf);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -715,6 +842,20 @@ hipError_t launch_wgrad_fast(const FastWgradParams& p0, int n_active, hipStream_
     FastWgradParams p = p0;
     p.n_active = n_active;
     if (p.C % 8 != 0 || p.N % 64 != 0) return hipErrorInvalidValue;
+    // wide images with at most 128 channels in and out: all taps from one patch
+    if ((p.W == 16 || p.W == 32) && p.C <= 128 && p.N <= 128 && p.C % 64 == 0 && p.R == 3 && p.S == 3 && p.pad == 1 && !p.perm &&
+        (p.H * p.W) % 32 == 0 && p.K % 32 == 0 && (p.splits == 1 || p.kchunk % 32 == 0) && p.M == 9 * p.C + (p.has_bias ? 1 : 0) &&
+        p.tile_hint != 2) {
+        const dim3 grid(die_grid((long long)(p.C / 64) * (p.N / 64) * p.splits * n_active));
+        if (p.W == 32) {
+            constexpr size_t lds = 2 * ((size_t)3 * 34 + 32) * 192;
+            hipLaunchKernelGGL(wgrad_taps_kernel<32>, grid, dim3(256), lds, s, p);
+        } else {
+            constexpr size_t lds = 2 * ((size_t)4 * 18 + 32) * 192;
+            hipLaunchKernelGGL(wgrad_taps_kernel<16>, grid, dim3(256), lds, s, p);
+        }
+        return hipGetLastError();
+    }
     // 256-row tiles (and 256 columns where the layer has them) when the launch still fills the chip
     static const BigTileInfo big = query_big_tile();
     int bmt = 128;
