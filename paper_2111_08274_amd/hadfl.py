@@ -180,7 +180,12 @@ class Context:
             lib().hadfl_destroy(self.h)
             self.h = None
 
-    __del__ = close
+    def __del__(self):
+        # at interpreter shutdown module globals may already be gone; the process is ending anyway
+        try:
+            self.close()
+        except TypeError:
+            pass
 
     def local_steps(self):
         _check(lib().hadfl_local_steps(self.h), self.h)
