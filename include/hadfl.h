@@ -144,6 +144,32 @@ HADFL_API hadfl_status hadfl_local_steps(hadfl_ctx *ctx);
  * Errors: EINVAL if fewer than n_select replicas are available. */
 HADFL_API hadfl_status hadfl_select(hadfl_ctx *ctx, const int32_t *versions_dev, const uint8_t *avail_host, uint64_t cycle);
 
+/* Sec. 3.2, a device may complete fewer (or more) local steps in a round than the step-count rule planned: replace
+ * every replica's step count E_k for the following hadfl_local_steps calls.
+ *   steps_host    host, [n_replicas] int32, each in [0, 2^20]; 0 = the replica sits the round out (version 0)
+ * Synchronises the stream.  EINVAL on a value out of range. */
+HADFL_API hadfl_status hadfl_set_steps(hadfl_ctx *ctx, const int32_t *steps_host);
+
+/* Sec. 3.2, runtime version forecast by double exponential smoothing: feeds one observation per replica -- the
+ * versions recorded by the last hadfl_local_steps, or versions_dev -- into the per-replica states
+ *   s1 <- alpha*v + (1-alpha)*s1,  s2 <- alpha*s1 + (1-alpha)*s2   (both start at the first observation)
+ * and leaves the forecast `horizon` rounds ahead, (2*s1 - s2) + alpha/(1-alpha)*(s1 - s2)*horizon, on the device
+ * (fp64, every operation rounded on its own).
+ *   versions_dev  dev, [n_replicas] int32, or NULL
+ *   alpha         smoothing factor in (0, 1); horizon in [0, 2^20]
+ * Errors: EINVAL on alpha or horizon out of range. */
+HADFL_API hadfl_status hadfl_predict_versions(hadfl_ctx *ctx, const int32_t *versions_dev, double alpha, int32_t horizon);
+
+/* Sec. 3.1 step 2 with Sec. 3.3: the selection of the next round drawn from real-valued (forecast) versions; the
+ * same rule as hadfl_select with v_k real.
+ *   versions_dev  dev, [n_replicas] fp64, or NULL for the forecast left by hadfl_predict_versions
+ *   avail_host    as in hadfl_select
+ * Errors: ESTATE if versions_dev is NULL and no forecast exists; EINVAL as hadfl_select. */
+HADFL_API hadfl_status hadfl_select_real(hadfl_ctx *ctx, const double *versions_dev, const uint8_t *avail_host, uint64_t cycle);
+
+/* Read-back of the last forecast (synchronises the stream).  predicted: host, [n_replicas] fp64.  ESTATE if none. */
+HADFL_API hadfl_status hadfl_get_predicted(hadfl_ctx *ctx, double *predicted);
+
 /* Sec. 2.3, partial aggregation over the replicas flagged by the last hadfl_select:
  *   w_agg[j] = sum_k a_k * w_k[j], added in ascending k in fp32,
  * then, if resync != 0, Algorithm 1's global synchronisation: every replica's parameters become w_agg

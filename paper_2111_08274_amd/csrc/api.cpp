@@ -26,11 +26,12 @@ struct hadfl_ctx {
     int32_t *steps_d = nullptr, *selected = nullptr, *sel_sorted = nullptr;
     float *sel_weight = nullptr, *weights = nullptr;
     double* f = nullptr;
+    double* pred = nullptr;          // [3][N]: smoothing states s1, s2 and the forecast (Sec. 3.2)
     uint8_t *flag = nullptr, *avail_d = nullptr;
     // host state
     std::vector<int32_t> steps, order;
     uint8_t* avail_pinned = nullptr;
-    bool have_selection = false, have_agg = false;
+    bool have_selection = false, have_agg = false, have_forecast = false;
     TrainEngine* engine = nullptr;
     Profiler prof;
     std::string err;
@@ -52,7 +53,7 @@ struct Carver {
 
 struct Carved {
     size_t agg, mom, grad, work, order, versions, cursor, loss, steps, selected, sel_sorted, sel_weight, weights, f,
-        flag, avail, total;
+        pred, flag, avail, total;
 };
 
 hadfl_status validate(const hadfl_config* cfg, std::string& err)
@@ -95,6 +96,7 @@ Carved carve(const hadfl_config& cfg, const NetPlan& plan)
     o.sel_weight = c.take<float>((size_t)cfg.n_select);
     o.weights = c.take<float>(N);
     o.f = c.take<double>(N);
+    o.pred = c.take<double>(3 * N);
     o.flag = c.take<uint8_t>(N);
     o.avail = c.take<uint8_t>(N);
     o.total = (c.off + 255) / 256 * 256;
@@ -284,6 +286,7 @@ hadfl_status hadfl_init_replicas(const hadfl_config* cfg, const void* w0_dev, vo
     ctx->sel_weight = (float*)(b + c.sel_weight);
     ctx->weights = (float*)(b + c.weights);
     ctx->f = (double*)(b + c.f);
+    ctx->pred = (double*)(b + c.pred);
     ctx->flag = (uint8_t*)(b + c.flag);
     ctx->avail_d = (uint8_t*)(b + c.avail);
 
@@ -333,9 +336,9 @@ hadfl_status hadfl_local_steps(hadfl_ctx* ctx)
     return HADFL_OK;
 }
 
-hadfl_status hadfl_select(hadfl_ctx* ctx, const int32_t* versions_dev, const uint8_t* avail_host, uint64_t cycle)
+static hadfl_status select_common(hadfl_ctx* ctx, const int32_t* versions_i32, const double* versions_f64,
+                                  const uint8_t* avail_host, uint64_t cycle)
 {
-    if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
     const int N = ctx->cfg.n_replicas;
     const uint8_t* avail_d = nullptr;
     if (avail_host) {
@@ -349,7 +352,8 @@ hadfl_status hadfl_select(hadfl_ctx* ctx, const int32_t* versions_dev, const uin
         avail_d = ctx->avail_d;
     }
     SelectArgs a{};
-    a.versions = versions_dev ? versions_dev : ctx->tb.versions;
+    a.versions = versions_i32;
+    a.versions_f64 = versions_f64;
     a.avail = avail_d;
     a.n = N; a.n_select = ctx->cfg.n_select; a.weight_mode = ctx->cfg.weight_mode;
     a.seed = ctx->cfg.seed; a.cycle = cycle;
@@ -360,6 +364,62 @@ hadfl_status hadfl_select(hadfl_ctx* ctx, const int32_t* versions_dev, const uin
     ctx->prof.end(ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "select kernel");
     ctx->have_selection = true;
+    return HADFL_OK;
+}
+
+hadfl_status hadfl_select(hadfl_ctx* ctx, const int32_t* versions_dev, const uint8_t* avail_host, uint64_t cycle)
+{
+    if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
+    return select_common(ctx, versions_dev ? versions_dev : ctx->tb.versions, nullptr, avail_host, cycle);
+}
+
+hadfl_status hadfl_select_real(hadfl_ctx* ctx, const double* versions_dev, const uint8_t* avail_host, uint64_t cycle)
+{
+    if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
+    if (!versions_dev && !ctx->have_forecast)
+        return fail(ctx, HADFL_ESTATE, "hadfl_select_real without versions needs a preceding hadfl_predict_versions");
+    if (versions_dev && ((uintptr_t)versions_dev & 7)) return fail(ctx, HADFL_EINVAL, "versions_dev must be 8-byte aligned");
+    return select_common(ctx, nullptr, versions_dev ? versions_dev : ctx->pred + 2 * (size_t)ctx->cfg.n_replicas, avail_host, cycle);
+}
+
+hadfl_status hadfl_predict_versions(hadfl_ctx* ctx, const int32_t* versions_dev, double alpha, int32_t horizon)
+{
+    if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
+    if (!(alpha > 0.0) || !(alpha < 1.0)) return fail(ctx, HADFL_EINVAL, "alpha must be in (0, 1)");
+    if (horizon < 0 || horizon > (1 << 20)) return fail(ctx, HADFL_EINVAL, "horizon must be in [0, 2^20]");
+    const size_t N = (size_t)ctx->cfg.n_replicas;
+    const hipError_t e = launch_predict(versions_dev ? versions_dev : ctx->tb.versions, ctx->pred, ctx->pred + N, ctx->pred + 2 * N,
+                                        (int)N, alpha, horizon, ctx->have_forecast ? 0 : 1, ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "predict kernel");
+    ctx->have_forecast = true;
+    return HADFL_OK;
+}
+
+hadfl_status hadfl_get_predicted(hadfl_ctx* ctx, double* predicted)
+{
+    if (!ctx || !predicted) return fail(ctx, HADFL_EINVAL, "null argument");
+    if (!ctx->have_forecast) return fail(ctx, HADFL_ESTATE, "no forecast yet");
+    const size_t N = (size_t)ctx->cfg.n_replicas;
+    HIP_TRY(ctx, hipMemcpyAsync(predicted, ctx->pred + 2 * N, sizeof(double) * N, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HADFL_OK;
+}
+
+hadfl_status hadfl_set_steps(hadfl_ctx* ctx, const int32_t* steps_host)
+{
+    if (!ctx || !steps_host) return fail(ctx, HADFL_EINVAL, "null argument");
+    const int N = ctx->cfg.n_replicas;
+    for (int k = 0; k < N; ++k)
+        if (steps_host[k] < 0 || steps_host[k] > (1 << 20)) return fail(ctx, HADFL_EINVAL, "step counts must be in [0, 2^20]");
+    // the copies below read host vectors that are about to change: let earlier copies out of them finish
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->steps.assign(steps_host, steps_host + N);
+    std::iota(ctx->order.begin(), ctx->order.end(), 0);
+    std::stable_sort(ctx->order.begin(), ctx->order.end(), [&](int a, int b) { return ctx->steps[a] > ctx->steps[b]; });
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->steps_d, ctx->steps.data(), sizeof(int32_t) * N, hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(ctx->tb.order, ctx->order.data(), sizeof(int32_t) * N, hipMemcpyHostToDevice, ctx->stream));
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->engine) train_set_steps(ctx->engine, ctx->steps);
     return HADFL_OK;
 }
 

@@ -6,7 +6,8 @@ namespace hadfl {
 
 // ---- selection (Sec. 3.3) -------------------------------------------------
 struct SelectArgs {
-    const int32_t* versions;       // [n]
+    const int32_t* versions;       // [n] step counters, used when versions_f64 is null
+    const double* versions_f64;    // [n] real-valued (forecast) versions, or null
     const uint8_t* avail;          // [n] or null
     int n, n_select, weight_mode;
     uint64_t seed, cycle;
@@ -18,6 +19,9 @@ struct SelectArgs {
     double* f;                     // [n]
 };
 hipError_t launch_select(const SelectArgs& a, hipStream_t s);
+// Sec. 3.2: feed versions[n] into the smoothing states s1[n], s2[n] and write the forecast m cycles ahead to out[n]
+hipError_t launch_predict(const int32_t* versions, double* s1, double* s2, double* out, int n, double alpha, int m,
+                          int first, hipStream_t s);
 
 // ---- aggregation + global synchronisation (Sec. 2.3, Algorithm 1) ----------
 // agg[j] = sum_i sel_weight[i] * rows[sel_sorted[i]][j], i ascending; if n_bcast > 0 the result is also written

@@ -46,12 +46,20 @@ __device__ __forceinline__ double lane_value(double v, int k)
     return __hiloint2double(hi, lo);
 }
 
+__device__ __forceinline__ int lane_value(int v, int k) { return __builtin_amdgcn_readlane(v, k); }
+
+template <typename V> __device__ __forceinline__ const V* versions_of(const SelectArgs& a);
+template <> __device__ __forceinline__ const int* versions_of<int>(const SelectArgs& a) { return a.versions; }
+template <> __device__ __forceinline__ const double* versions_of<double>(const SelectArgs& a) { return a.versions_f64; }
+
+// V = int: versions are step counters; V = double: forecast (real-valued) versions (Sec. 3.2 feeding Sec. 3.3)
+template <typename V>
 __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
 {
     __shared__ double s_sorted[kMaxReplicas];
     __shared__ double s_f[kMaxReplicas];
     __shared__ unsigned char s_flag[kMaxReplicas];
-    __shared__ int s_v[kMaxReplicas];
+    __shared__ V s_v[kMaxReplicas];
     __shared__ unsigned char s_av[kMaxReplicas];
     const int lane = threadIdx.x, N = a.n;
 
@@ -60,7 +68,7 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
     // chunk by chunk with cross-lane reads, so no step waits on memory.
     const int chunks = (N + 63) / 64;
     for (int i = lane; i < N; i += 64) {
-        s_v[i] = a.versions[i];
+        s_v[i] = versions_of<V>(a)[i];
         s_av[i] = (!a.avail || a.avail[i]) ? 1 : 0;
         s_flag[i] = 0;
     }
@@ -68,17 +76,17 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
     int na = 0;
     for (int q = 0; q < chunks; ++q) {
         const int i = q * 64 + lane;
-        const int vi = i < N ? s_v[i] : 0;
+        const V vi = i < N ? s_v[i] : V(0);
         int rank = 0;
         na = 0;
         for (int c = 0; c < chunks; ++c) {
             const int idx = c * 64 + lane;
-            const int vjm = idx < N ? s_v[idx] : 0;
+            const V vjm = idx < N ? s_v[idx] : V(0);
             const unsigned long long mask = __ballot(idx < N && s_av[idx]);
             na += __popcll(mask);
 #pragma unroll
             for (int k = 0; k < 64; ++k) {
-                const int vj = __builtin_amdgcn_readlane(vjm, k);
+                const V vj = lane_value(vjm, k);
                 const int j = c * 64 + k;
                 const bool bj = (mask >> k) & 1ull;
                 rank += (bj && (vj < vi || (vj == vi && j < i))) ? 1 : 0;
@@ -168,11 +176,40 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
     }
 }
 
+// Version forecast (Sec. 3.2): double exponential smoothing of every replica's version series.
+//   s1 <- alpha*v + (1-alpha)*s1;  s2 <- alpha*s1 + (1-alpha)*s2   (both start at the first observation)
+//   forecast(m) = (2*s1 - s2) + alpha/(1-alpha)*(s1 - s2)*m
+__global__ __launch_bounds__(64) void predict_kernel(const int32_t* versions, double* s1, double* s2, double* out, int n,
+                                                     double alpha, int m, int first)
+{
+    for (int i = threadIdx.x; i < n; i += 64) {
+        const double v = (double)versions[i];
+        double a1, a2;
+        if (first) { a1 = v; a2 = v; }
+        else {
+            a1 = alpha * v + (1.0 - alpha) * s1[i];
+            a2 = alpha * a1 + (1.0 - alpha) * s2[i];
+        }
+        s1[i] = a1; s2[i] = a2;
+        const double level = 2.0 * a1 - a2;
+        const double trend = alpha / (1.0 - alpha) * (a1 - a2);
+        out[i] = level + trend * (double)m;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_predict(const int32_t* versions, double* s1, double* s2, double* out, int n, double alpha, int m,
+                          int first, hipStream_t s)
+{
+    hipLaunchKernelGGL(predict_kernel, dim3(1), dim3(64), 0, s, versions, s1, s2, out, n, alpha, m, first);
+    return hipGetLastError();
+}
 
 hipError_t launch_select(const SelectArgs& a, hipStream_t s)
 {
-    hipLaunchKernelGGL(select_kernel, dim3(1), dim3(64), 0, s, a);
+    if (a.versions_f64) hipLaunchKernelGGL(select_kernel<double>, dim3(1), dim3(64), 0, s, a);
+    else hipLaunchKernelGGL(select_kernel<int>, dim3(1), dim3(64), 0, s, a);
     return hipGetLastError();
 }
 

@@ -226,6 +226,15 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
     return HADFL_OK;
 }
 
+void train_set_steps(TrainEngine* e, const std::vector<int32_t>& steps)
+{
+    e->steps = steps;
+    e->e_max = steps.empty() ? 0 : *std::max_element(steps.begin(), steps.end());
+    e->n_active.assign(e->e_max, 0);
+    for (int s = 0; s < e->e_max; ++s)
+        for (int32_t v : steps) e->n_active[s] += v > s ? 1 : 0;
+}
+
 void train_destroy(TrainEngine* e) { delete e; }
 
 namespace {

@@ -41,7 +41,8 @@ class HadflKernelTime(ctypes.Structure):
 
 
 EXPORTS = ("hadfl_param_count", "hadfl_param_layout", "hadfl_workspace_bytes", "hadfl_init_replicas",
-           "hadfl_local_steps", "hadfl_select", "hadfl_aggregate", "hadfl_get_steps", "hadfl_get_versions",
+           "hadfl_local_steps", "hadfl_select", "hadfl_aggregate", "hadfl_set_steps", "hadfl_predict_versions",
+           "hadfl_select_real", "hadfl_get_predicted", "hadfl_get_steps", "hadfl_get_versions",
            "hadfl_get_selected", "hadfl_get_params", "hadfl_get_losses", "hadfl_profile_enable",
            "hadfl_profile_read", "hadfl_last_error", "hadfl_destroy")
 
@@ -73,6 +74,10 @@ def lib():
         L.hadfl_local_steps.argtypes = [vp]
         L.hadfl_select.argtypes = [vp, vp, vp, ctypes.c_uint64]
         L.hadfl_aggregate.argtypes = [vp, i32]
+        L.hadfl_set_steps.argtypes = [vp, vp]
+        L.hadfl_predict_versions.argtypes = [vp, vp, ctypes.c_double, i32]
+        L.hadfl_select_real.argtypes = [vp, vp, vp, ctypes.c_uint64]
+        L.hadfl_get_predicted.argtypes = [vp, vp]
         L.hadfl_get_steps.argtypes = [vp, vp]
         L.hadfl_get_versions.argtypes = [vp, vp, vp]
         L.hadfl_get_selected.argtypes = [vp, vp, vp, vp]
@@ -197,6 +202,31 @@ class Context:
             assert versions.dtype.__str__() == "torch.int32" and versions.is_cuda and versions.numel() == self.cfg.n_replicas
         _check(lib().hadfl_select(self.h, versions.data_ptr() if versions is not None else None,
                                   _np_ptr(av) if av is not None else None, int(cycle)), self.h)
+
+    def set_steps(self, steps):
+        st = np.ascontiguousarray(steps, dtype=np.int32)
+        assert st.size == self.cfg.n_replicas
+        _check(lib().hadfl_set_steps(self.h, _np_ptr(st)), self.h)
+
+    def predict_versions(self, alpha, horizon=1, versions=None):
+        """versions: torch int32 device tensor or None (the counters of the last local_steps)."""
+        if versions is not None:
+            assert versions.dtype.__str__() == "torch.int32" and versions.is_cuda and versions.numel() == self.cfg.n_replicas
+        _check(lib().hadfl_predict_versions(self.h, versions.data_ptr() if versions is not None else None,
+                                            float(alpha), int(horizon)), self.h)
+
+    def select_real(self, cycle, versions=None, avail=None):
+        """versions: torch float64 device tensor or None (the forecast of predict_versions)."""
+        av = None if avail is None else np.ascontiguousarray(avail, dtype=np.uint8)
+        if versions is not None:
+            assert versions.dtype.__str__() == "torch.float64" and versions.is_cuda and versions.numel() == self.cfg.n_replicas
+        _check(lib().hadfl_select_real(self.h, versions.data_ptr() if versions is not None else None,
+                                       _np_ptr(av) if av is not None else None, int(cycle)), self.h)
+
+    def predicted(self):
+        out = np.zeros(self.cfg.n_replicas, dtype=np.float64)
+        _check(lib().hadfl_get_predicted(self.h, _np_ptr(out)), self.h)
+        return out
 
     def aggregate(self, resync=True):
         _check(lib().hadfl_aggregate(self.h, int(bool(resync))), self.h)

@@ -158,3 +158,23 @@ def test_aggregation_weights_sum_to_one():
         a = oracle.aggregation_weights(flag, f, mode)
         assert abs(a.sum() - 1.0) < 1e-15 and np.all(a[flag == 0] == 0)
     assert np.all(oracle.aggregation_weights(flag, f, 0)[flag == 1] == 1 / 3)
+
+
+def test_real_valued_versions_same_rule():
+    # Sec. 3.2 forecasts are real numbers; Sec. 3.3's rule only uses v - Q3(v).  Integer versions given as floats select
+    # the same devices; adding one constant to every version changes nothing; and the probabilities are the unit-variance
+    # Gaussian about the interpolated quartile, written out by hand for one case.
+    v_int = np.array([4, 2, 2, 1, 3, 3, 1, 5])
+    for cycle in range(20):
+        a = oracle.select(v_int, 3, 7, cycle)
+        b = oracle.select(v_int.astype(np.float64), 3, 7, cycle)
+        c = oracle.select(v_int.astype(np.float64) + 0.5, 3, 7, cycle)       # exact shift: quartile moves with it
+        assert a[0].tolist() == b[0].tolist() == c[0].tolist()
+        assert np.array_equal(a[2], b[2]) and np.array_equal(a[2], c[2])
+    v = np.array([0.5, 1.25, 3.0, 2.5])
+    sel, flag, f, mu = oracle.select(v, 2, 7, 0)
+    # sorted 0.5 1.25 2.5 3.0; position 0.75 * 3 = 2.25 -> 2.5 + 0.25 * 0.5
+    assert mu == 2.625
+    want = np.exp(-0.5 * (v - 2.625) ** 2)
+    assert np.abs(f - want).max() < 1e-15
+    assert np.abs(oracle.probabilities(v) - want / want.sum()).max() < 1e-15
