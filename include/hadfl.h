@@ -144,6 +144,22 @@ HADFL_API hadfl_status hadfl_local_steps(hadfl_ctx *ctx);
  * Errors: EINVAL if fewer than n_select replicas are available. */
 HADFL_API hadfl_status hadfl_select(hadfl_ctx *ctx, const int32_t *versions_dev, const uint8_t *avail_host, uint64_t cycle);
 
+/* Sec. 3.2 (mutual-negotiation phase) with Sec. 3.3 (hyperperiod): step counts from measured calculation times.
+ * Device k reports the time times_host[k] it needed for e_warmup warm-up units.  Its time per unit,
+ * times_host[k] / e_warmup, is rounded to the nearest whole number q_k >= 1 of `quantum`; the hyperperiod is
+ * H = lcm(q_1..q_n) quanta, and in t_sync hyperperiods device k completes
+ *   steps_host[k] = t_sync * steps_per_unit * H / q_k
+ * units -- the same counts as hadfl_init_replicas derives from computing-power ratios r_k when times are
+ * proportional to 1/r_k.  Host arrays only; no context and no GPU work.
+ * Errors: EINVAL on a null pointer, n < 1, a non-positive time, quantum, e_warmup, t_sync or steps_per_unit, or when
+ * a step count would exceed 2^20 (quantum too fine for these times). */
+HADFL_API hadfl_status hadfl_steps_from_times(const double *times_host, int32_t n, int32_t e_warmup, double quantum,
+                                              int32_t t_sync, int32_t steps_per_unit, int32_t *steps_host);
+
+/* Learning rate of the following hadfl_local_steps calls (the warm-up of Sec. 3.2 uses a small one).  EINVAL unless
+ * lr > 0; ESTATE for a context without a trainable network. */
+HADFL_API hadfl_status hadfl_set_lr(hadfl_ctx *ctx, float lr);
+
 /* Sec. 3.2, a device may complete fewer (or more) local steps in a round than the step-count rule planned: replace
  * every replica's step count E_k for the following hadfl_local_steps calls.
  *   steps_host    host, [n_replicas] int32, each in [0, 2^20]; 0 = the replica sits the round out (version 0)

@@ -158,6 +158,20 @@ def step_counts(ratio, t_sync=1, steps_per_unit=1):
     return out
 
 
+def steps_from_times(times, e_warmup, quantum, t_sync=1, steps_per_unit=1):
+    t = np.ascontiguousarray(times, dtype=np.float64)
+    out = np.zeros(t.size, dtype=np.int32)
+    L = lib()
+    L.hadfl_oracle_steps_from_times.restype = ctypes.c_int
+    L.hadfl_oracle_steps_from_times.argtypes = [c_f64p, ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_int,
+                                                ctypes.c_int, c_i32p]
+    rc = L.hadfl_oracle_steps_from_times(_p(t, c_f64p), int(t.size), int(e_warmup), float(quantum), int(t_sync),
+                                         int(steps_per_unit), _p(out, c_i32p))
+    if rc != 0:
+        raise ValueError("times, quantum, e_warmup, t_sync and steps_per_unit must be positive and the counts at most 2^20")
+    return out
+
+
 def philox4x32_10(ctr, key):
     c = np.asarray(ctr, dtype=np.uint32)
     k = np.asarray(key, dtype=np.uint32)

@@ -500,6 +500,41 @@ int hadfl_oracle_step_counts(const int32_t *ratio, int n, int t_sync, int steps_
 }
 
 /* ------------------------------------------------------------------------- */
+/* Step counts from warm-up times (Sec. 3.2 mutual negotiation, Sec. 3.3       */
+/* hyperperiod).  Device k needed T[k] for e_warmup units, so one unit takes  */
+/* T[k]/e_warmup; measured times are not commensurable, so each is expressed  */
+/* as the nearest whole number (at least 1) of `quantum`.  The hyperperiod is */
+/* the least common multiple of those; within t_sync hyperperiods device k    */
+/* finishes t_sync * steps_per_unit * (hyperperiod / its unit time) units.    */
+/* Returns 0, or -1 on a non-positive input or a count beyond 2^20.           */
+/* ------------------------------------------------------------------------- */
+int hadfl_oracle_steps_from_times(const double *T, int n, int e_warmup, double quantum, int t_sync,
+                                  int steps_per_unit, int32_t *steps)
+{
+    if (n < 1 || e_warmup < 1 || t_sync < 1 || steps_per_unit < 1 || !(quantum > 0.0)) return -1;
+    int64_t unit[4096];
+    if (n > 4096) return -1;
+    int64_t hyper = 1;
+    for (int k = 0; k < n; ++k) {
+        if (!(T[k] > 0.0)) return -1;
+        double per_unit = T[k] / (double)e_warmup;
+        double whole = rint(per_unit / quantum);
+        if (whole >= 1048576.0) return -1;
+        unit[k] = whole < 1.0 ? 1 : (int64_t)whole;
+        int64_t a = hyper, b = unit[k];
+        while (b) { int64_t t = a % b; a = b; b = t; }          /* a = gcd(hyper, unit[k]) */
+        hyper = hyper / a * unit[k];
+        if (hyper > ((int64_t)1 << 40)) return -1;
+    }
+    for (int k = 0; k < n; ++k) {
+        int64_t e = (int64_t)t_sync * steps_per_unit * (hyper / unit[k]);
+        if (e > 1048576) return -1;
+        steps[k] = (int32_t)e;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Local training of every replica for its own number of steps (Algorithm 1,  */
 /* inner loop; local-update equation of Sec. 2.2).  Each step: next B rows of */
 /* the replica's shard (sequential walk with wrap-around), forward, backward, */

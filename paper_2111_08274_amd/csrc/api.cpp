@@ -2,6 +2,7 @@
 // sequence of one aggregation cycle.  Every step of the cycle itself runs in HIP kernels.
 #include <cstdio>
 #include <cstring>
+#include <cmath>
 #include <numeric>
 #include <algorithm>
 #include <new>
@@ -402,6 +403,43 @@ hadfl_status hadfl_get_predicted(hadfl_ctx* ctx, double* predicted)
     const size_t N = (size_t)ctx->cfg.n_replicas;
     HIP_TRY(ctx, hipMemcpyAsync(predicted, ctx->pred + 2 * N, sizeof(double) * N, hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HADFL_OK;
+}
+
+hadfl_status hadfl_steps_from_times(const double* times_host, int32_t n, int32_t e_warmup, double quantum, int32_t t_sync,
+                                    int32_t steps_per_unit, int32_t* steps_host)
+{
+    if (!times_host || !steps_host) return fail(nullptr, HADFL_EINVAL, "null argument");
+    if (n < 1 || e_warmup < 1 || t_sync < 1 || steps_per_unit < 1 || !(quantum > 0.0))
+        return fail(nullptr, HADFL_EINVAL, "n, e_warmup, quantum, t_sync and steps_per_unit must be positive");
+    const int64_t cap = 1 << 20;
+    std::vector<int64_t> q((size_t)n);
+    int64_t H = 1;
+    for (int32_t k = 0; k < n; ++k) {
+        if (!(times_host[k] > 0.0)) return fail(nullptr, HADFL_EINVAL, "calculation times must be positive");
+        const double units = std::nearbyint(times_host[k] / (double)e_warmup / quantum);
+        if (!(units < (double)cap)) return fail(nullptr, HADFL_EINVAL, "quantum too fine for these times");
+        q[k] = units < 1.0 ? 1 : (int64_t)units;
+        H = H / std::gcd<int64_t, int64_t>(H, q[k]) * q[k];
+        if (H > cap * cap) return fail(nullptr, HADFL_EINVAL, "quantum too fine for these times");
+    }
+    std::vector<int32_t> st((size_t)n);
+    for (int32_t k = 0; k < n; ++k) {
+        const int64_t e = (int64_t)t_sync * steps_per_unit * (H / q[k]);
+        if (e > cap) return fail(nullptr, HADFL_EINVAL, "step count above 2^20: quantum too fine for these times");
+        st[k] = (int32_t)e;
+    }
+    for (int32_t k = 0; k < n; ++k) steps_host[k] = st[k];
+    return HADFL_OK;
+}
+
+hadfl_status hadfl_set_lr(hadfl_ctx* ctx, float lr)
+{
+    if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
+    if (!ctx->engine) return fail(ctx, HADFL_ESTATE, "this context has no trainable network");
+    if (!(lr > 0.f)) return fail(ctx, HADFL_EINVAL, "lr must be positive");
+    ctx->cfg.lr = lr;
+    train_set_lr(ctx->engine, lr);
     return HADFL_OK;
 }
 

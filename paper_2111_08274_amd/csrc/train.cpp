@@ -235,6 +235,8 @@ void train_set_steps(TrainEngine* e, const std::vector<int32_t>& steps)
         for (int32_t v : steps) e->n_active[s] += v > s ? 1 : 0;
 }
 
+void train_set_lr(TrainEngine* e, float lr) { e->cfg.lr = lr; }
+
 void train_destroy(TrainEngine* e) { delete e; }
 
 namespace {

@@ -30,6 +30,7 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
 hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::string& err);
 // New per-replica step counts for the following runs (the caller has already re-sorted and uploaded `order`)
 void train_set_steps(TrainEngine* e, const std::vector<int32_t>& steps);
+void train_set_lr(TrainEngine* e, float lr);
 void train_destroy(TrainEngine* e);
 
 // Event-pair profiler used by hadfl_profile_*.

@@ -41,7 +41,7 @@ class HadflKernelTime(ctypes.Structure):
 
 
 EXPORTS = ("hadfl_param_count", "hadfl_param_layout", "hadfl_workspace_bytes", "hadfl_init_replicas",
-           "hadfl_local_steps", "hadfl_select", "hadfl_aggregate", "hadfl_set_steps", "hadfl_predict_versions",
+           "hadfl_local_steps", "hadfl_select", "hadfl_aggregate", "hadfl_steps_from_times", "hadfl_set_lr", "hadfl_set_steps", "hadfl_predict_versions",
            "hadfl_select_real", "hadfl_get_predicted", "hadfl_get_steps", "hadfl_get_versions",
            "hadfl_get_selected", "hadfl_get_params", "hadfl_get_losses", "hadfl_profile_enable",
            "hadfl_profile_read", "hadfl_last_error", "hadfl_destroy")
@@ -75,6 +75,8 @@ def lib():
         L.hadfl_select.argtypes = [vp, vp, vp, ctypes.c_uint64]
         L.hadfl_aggregate.argtypes = [vp, i32]
         L.hadfl_set_steps.argtypes = [vp, vp]
+        L.hadfl_steps_from_times.argtypes = [vp, i32, i32, ctypes.c_double, i32, i32, vp]
+        L.hadfl_set_lr.argtypes = [vp, ctypes.c_float]
         L.hadfl_predict_versions.argtypes = [vp, vp, ctypes.c_double, i32]
         L.hadfl_select_real.argtypes = [vp, vp, vp, ctypes.c_uint64]
         L.hadfl_get_predicted.argtypes = [vp, vp]
@@ -149,6 +151,15 @@ def _np_ptr(a):
     return a.ctypes.data_as(ctypes.c_void_p)
 
 
+def steps_from_times(times, e_warmup, quantum, t_sync=1, steps_per_unit=1):
+    """Step counts from measured warm-up times (host only) -> int32[n]."""
+    t = np.ascontiguousarray(times, dtype=np.float64)
+    out = np.zeros(t.size, dtype=np.int32)
+    _check(lib().hadfl_steps_from_times(_np_ptr(t), int(t.size), int(e_warmup), float(quantum), int(t_sync),
+                                        int(steps_per_unit), _np_ptr(out)))
+    return out
+
+
 class Context:
     """One set of replicas on the current torch device.  Holds the torch tensors the library works in."""
 
@@ -202,6 +213,9 @@ class Context:
             assert versions.dtype.__str__() == "torch.int32" and versions.is_cuda and versions.numel() == self.cfg.n_replicas
         _check(lib().hadfl_select(self.h, versions.data_ptr() if versions is not None else None,
                                   _np_ptr(av) if av is not None else None, int(cycle)), self.h)
+
+    def set_lr(self, lr):
+        _check(lib().hadfl_set_lr(self.h, float(lr)), self.h)
 
     def set_steps(self, steps):
         st = np.ascontiguousarray(steps, dtype=np.int32)

@@ -73,3 +73,27 @@ def test_init_rejects_null_and_misaligned_pointers_before_touching_the_device():
     assert out.value is None
     assert L.hadfl_local_steps(None) == hadfl.EINVAL and L.hadfl_aggregate(None, 1) == hadfl.EINVAL
     L.hadfl_destroy(None)
+
+
+def test_steps_from_warm_up_times_host_logic_against_the_oracle():
+    # host-only entry point (Sec. 3.2 warm-up times -> Sec. 3.3 step counts): same counts as the oracle on seeded
+    # inputs, and the documented errors
+    rng = np.random.default_rng(31)
+    for case in range(200):
+        n = int(rng.integers(1, 33))
+        e_warmup = int(rng.integers(1, 6))
+        quantum = float(rng.choice([0.25, 0.5, 1.0]))
+        base = rng.integers(1, 9, size=n).astype(np.float64)              # whole multiples of the quantum ...
+        times = base * quantum * e_warmup * (1.0 + rng.uniform(-0.02, 0.02, size=n))   # ... seen through a noisy clock
+        t_sync, spu = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        got = hadfl.steps_from_times(times, e_warmup, quantum, t_sync, spu)
+        want = oracle.steps_from_times(times, e_warmup, quantum, t_sync, spu)
+        assert got.tolist() == want.tolist(), (case, times)
+    einval = hadfl.STATUS_NAMES.index("HADFL_EINVAL")
+    for args in (([1.0, 0.0], 1, 1.0), ([1.0, 2.0], 0, 1.0), ([1.0, 2.0], 1, 0.0), ([1.0, 2.0], 1, -1.0),
+                 ([1.0, 1.0e6 + 0.37], 1, 1e-3)):
+        with pytest.raises(hadfl.HadflError) as e:
+            hadfl.steps_from_times(*args)
+        assert e.value.status == einval
+    with pytest.raises(hadfl.HadflError):
+        hadfl.steps_from_times([1.0, 2.0], 1, 1.0, t_sync=0)

@@ -90,3 +90,32 @@ def test_error_paths_of_the_forecast_calls():
     ctx.predict_versions(0.3, horizon=2, versions=torch.tensor([3, 1, 4, 1], dtype=torch.int32).cuda())
     assert ctx.predicted().tolist() == [3.0, 1.0, 4.0, 1.0]      # first observation: both states equal it, no trend
     ctx.close()
+
+
+def test_warm_up_round_then_step_counts_from_its_times():
+    """Mutual-negotiation phase of Sec. 3.2: every device trains the same few steps with a small learning rate and
+    reports its time; the step counts of the following rounds come from those times (Sec. 3.3)."""
+    cfg, x, y = synth.config_inputs(1, n_samples=128)
+    fn, shape = nets.NETS["mlp"]
+    N = cfg["n_replicas"]
+    power = np.array([4, 2, 2, 1])                         # Fig. 1's heterogeneity
+    p = Pair(fn(), shape, N, cfg["n_select"], x, y, cfg["batch"], cfg["lr"], 0.9, [1, 1, 1, 1], net_name="mlp")
+    e_warmup, low_lr = 2, cfg["lr"] / 10
+    p.gpu.set_lr(low_lr); p.cpu.lr = low_lr
+    warm = np.full(N, e_warmup, dtype=np.int32)
+    p.gpu.set_steps(warm)
+    p.gpu.local_steps(); p.cpu.local_steps(steps=warm)
+    assert p.max_param_diff() <= 1e-4
+    # simulated clocks: time = steps / power, read with 1 % noise
+    times = e_warmup / power * (1.0 + np.random.default_rng(3).uniform(-0.01, 0.01, size=N))
+    steps = hadfl.steps_from_times(times, e_warmup, 0.25)
+    assert steps.tolist() == oracle.steps_from_times(times, e_warmup, 0.25).tolist() == [4, 2, 2, 1]
+    p.gpu.set_lr(cfg["lr"]); p.cpu.lr = cfg["lr"]
+    p.gpu.set_steps(steps); p.cpu.steps = steps
+    for cycle in range(2):
+        p.local_steps()
+        p.select_aggregate(cycle)
+        assert p.max_param_diff() <= 1e-4
+    v, c = p.gpu.versions()
+    assert v.tolist() == [4, 2, 2, 1] and c.tolist() == [10, 6, 6, 4]       # 2 warm-up steps + 2 rounds
+    p.close()

@@ -104,3 +104,25 @@ def test_version_predictor_constant_and_linear_series():
     # one explicit hand-worked update, alpha = 0.5, series 4, 2: s1 = 3, s2 = 3.5, a = 2.5, b = -0.5
     r = oracle.Predictor(0.5); r.update(4.0)
     assert r.update(2.0, m=1) == 2.0 and r.update.__self__.s1.value == 3.0 and r.s2.value == 3.5
+
+
+def test_step_counts_from_warm_up_times_by_hand():
+    # Sec. 3.2 / Sec. 3.3: per-unit times 1, 2, 4 -> hyperperiod 4 -> 4, 2, 1 units per hyperperiod
+    assert oracle.steps_from_times([1.0, 2.0, 4.0], 1, 1.0).tolist() == [4, 2, 1]
+    # three warm-up units each, noisy clocks, quantum 0.5: 1.02, 1.967, 4.067 -> 2, 4, 8 quanta -> lcm 8
+    assert oracle.steps_from_times([3.06, 5.9, 12.2], 3, 0.5).tolist() == [4, 2, 1]
+    # times proportional to 1 / power reproduce the ratio rule: powers 1 : 2 : 3 : 4 -> times 12, 6, 4, 3
+    assert oracle.steps_from_times([12.0, 6.0, 4.0, 3.0], 1, 1.0).tolist() == oracle.step_counts([1, 2, 3, 4]).tolist() == [1, 2, 3, 4]
+    # Fig. 1's 4 : 2 : 1 powers with t_sync 2 and 5 steps per unit
+    assert oracle.steps_from_times([1.0, 2.0, 4.0], 1, 1.0, t_sync=2, steps_per_unit=5).tolist() == [40, 20, 10]
+    # equal devices: everybody takes t_sync units; a time below half a quantum still counts as one quantum
+    assert oracle.steps_from_times([7.0, 7.0, 7.0], 7, 0.25, t_sync=3).tolist() == [3, 3, 3]
+    assert oracle.steps_from_times([0.1, 2.0], 1, 1.0).tolist() == [2, 1]
+    import pytest
+    for bad in ([1.0, 0.0], [1.0, -2.0]):
+        with pytest.raises(ValueError):
+            oracle.steps_from_times(bad, 1, 1.0)
+    with pytest.raises(ValueError):
+        oracle.steps_from_times([1.0, 2.0], 1, 0.0)
+    with pytest.raises(ValueError):
+        oracle.steps_from_times([1.0, 1.0e6 + 0.37], 1, 1e-3)          # lcm of incommensurable fine counts explodes
