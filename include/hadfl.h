@@ -192,6 +192,18 @@ HADFL_API hadfl_status hadfl_get_predicted(hadfl_ctx *ctx, double *predicted);
  * (optimiser state and batch cursors are local and stay).  ESTATE without a preceding hadfl_select. */
 HADFL_API hadfl_status hadfl_aggregate(hadfl_ctx *ctx, int32_t resync);
 
+/* Sec. 3.3, last paragraph (many devices are divided into groups; intra-group rounds run separately, the
+ * inter-group round -- hadfl_select / hadfl_aggregate over everybody -- every integer multiple of them).
+ * hadfl_select_group: the rule of hadfl_select among the members of one group.
+ *   member_host   host, [n_replicas] bytes, nonzero = member of the group (and present this round)
+ *   n_select      devices to draw, in [1, cfg.n_select]; EINVAL if the group has fewer members; hadfl_get_selected
+ *                 then returns them in the first n_select entries
+ * hadfl_aggregate_group: the aggregate of the last selection, written to the rows of the given members only
+ * (pass the same mask to synchronise the group; synchronises the stream once to stage the row list). */
+HADFL_API hadfl_status hadfl_select_group(hadfl_ctx *ctx, const int32_t *versions_dev, const uint8_t *member_host,
+                                          int32_t n_select, uint64_t cycle);
+HADFL_API hadfl_status hadfl_aggregate_group(hadfl_ctx *ctx, const uint8_t *member_host);
+
 /* Read-back; each synchronises the stream.  All outputs are host arrays. */
 HADFL_API hadfl_status hadfl_get_steps(hadfl_ctx *ctx, int32_t *steps /* [n_replicas] E_k */);
 HADFL_API hadfl_status hadfl_get_versions(hadfl_ctx *ctx, int32_t *versions /* [n_replicas] */, int64_t *cursors /* [n_replicas] or NULL */);

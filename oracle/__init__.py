@@ -301,6 +301,21 @@ class Cycle:
             lib().hadfl_oracle_resync(_p(self.params, c_f64p), self.N, self.net.m_total, _p(self.agg, c_f64p))
         return self.agg
 
+    # Sec. 3.3, last paragraph: devices divided into groups; an intra-group round selects and aggregates among the
+    # members of one group and synchronises only them
+    def select_group(self, cycle, members, n_select, versions=None):
+        v = self.versions if versions is None else versions
+        self.selected, self.flag, self.f, self.mu = select(v, n_select, self.seed, cycle, np.asarray(members, dtype=np.uint8))
+        self.weights = aggregation_weights(self.flag, self.f, self.weight_mode)
+        return self.selected.copy()
+
+    def aggregate_group(self, members):
+        self.agg = aggregate(self.params, self.weights)
+        for k in range(self.N):
+            if members[k]:
+                self.params[k, :] = self.agg
+        return self.agg
+
     def run_cycle(self, cycle, resync=True):
         self.local_steps()
         self.select(cycle)

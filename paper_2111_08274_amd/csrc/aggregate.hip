@@ -14,7 +14,8 @@ constexpr int kAggUnroll = 2;      // float4 chunks per thread: 2*NP loads of 16
 template <int NP>
 __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(
     const float* rows, int64_t row_stride, int64_t n4, const int32_t* __restrict__ sel,
-    const float* __restrict__ wgt, int n_select, float* __restrict__ agg, int n_bcast, float* rows_out)
+    const float* __restrict__ wgt, int n_select, float* __restrict__ agg, int n_bcast, float* rows_out,
+    const int32_t* __restrict__ bcast_list)
 {
     const int np = NP > 0 ? NP : n_select;
     const int64_t base = ((int64_t)blockIdx.x * kAggUnroll) * kAggThreads + threadIdx.x;
@@ -44,7 +45,7 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(
                 for (int i = 1; i < NP; ++i) acc = acc + v[u][i] * a[i];
                 __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(agg) + j);
                 for (int r = 0; r < n_bcast; ++r)
-                    __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(rows_out + (int64_t)r * row_stride) + j);
+                    __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(rows_out + (int64_t)(bcast_list ? bcast_list[r] : r) * row_stride) + j);
             }
         }
     } else {
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(
                 acc = acc + __builtin_nontemporal_load(reinterpret_cast<const f4*>(rows + (int64_t)sel[i] * row_stride) + j) * wgt[i];
             __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(agg) + j);
             for (int r = 0; r < n_bcast; ++r)
-                __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(rows_out + (int64_t)r * row_stride) + j);
+                __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(rows_out + (int64_t)(bcast_list ? bcast_list[r] : r) * row_stride) + j);
         }
     }
 }
@@ -90,13 +91,13 @@ int grid_for(int64_t count, int per_block, int cap)
 
 hipError_t launch_aggregate(const float* rows, int64_t row_stride, int64_t len, const int32_t* sel_sorted,
                             const float* sel_weight, int n_select, float* agg, int n_bcast, float* rows_out,
-                            hipStream_t s)
+                            const int32_t* bcast_list, hipStream_t s)
 {
     const int64_t n4 = len / 4;
     const int64_t per_block = (int64_t)kAggThreads * kAggUnroll;
     const dim3 grid((unsigned)((n4 + per_block - 1) / per_block)), block(kAggThreads);
 #define HADFL_AGG(NP) hipLaunchKernelGGL(aggregate_kernel<NP>, grid, block, 0, s, rows, row_stride, n4, sel_sorted, \
-                                         sel_weight, n_select, agg, n_bcast, rows_out)
+                                         sel_weight, n_select, agg, n_bcast, rows_out, bcast_list)
     switch (n_select) {
     case 1: HADFL_AGG(1); break;
     case 2: HADFL_AGG(2); break;

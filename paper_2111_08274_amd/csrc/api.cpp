@@ -28,9 +28,11 @@ struct hadfl_ctx {
     float *sel_weight = nullptr, *weights = nullptr;
     double* f = nullptr;
     double* pred = nullptr;          // [3][N]: smoothing states s1, s2 and the forecast (Sec. 3.2)
+    int32_t* bcast_d = nullptr;      // [N]: rows that receive a group's aggregate
     uint8_t *flag = nullptr, *avail_d = nullptr;
     // host state
-    std::vector<int32_t> steps, order;
+    std::vector<int32_t> steps, order, bcast_h;
+    int last_n_select = 0;           // size of the last selection (cfg.n_select, or a group's)
     uint8_t* avail_pinned = nullptr;
     bool have_selection = false, have_agg = false, have_forecast = false;
     TrainEngine* engine = nullptr;
@@ -54,7 +56,7 @@ struct Carver {
 
 struct Carved {
     size_t agg, mom, grad, work, order, versions, cursor, loss, steps, selected, sel_sorted, sel_weight, weights, f,
-        pred, flag, avail, total;
+        pred, bcast, flag, avail, total;
 };
 
 hadfl_status validate(const hadfl_config* cfg, std::string& err)
@@ -98,6 +100,7 @@ Carved carve(const hadfl_config& cfg, const NetPlan& plan)
     o.weights = c.take<float>(N);
     o.f = c.take<double>(N);
     o.pred = c.take<double>(3 * N);
+    o.bcast = c.take<int32_t>(N);
     o.flag = c.take<uint8_t>(N);
     o.avail = c.take<uint8_t>(N);
     o.total = (c.off + 255) / 256 * 256;
@@ -288,6 +291,7 @@ hadfl_status hadfl_init_replicas(const hadfl_config* cfg, const void* w0_dev, vo
     ctx->weights = (float*)(b + c.weights);
     ctx->f = (double*)(b + c.f);
     ctx->pred = (double*)(b + c.pred);
+    ctx->bcast_d = (int32_t*)(b + c.bcast);
     ctx->flag = (uint8_t*)(b + c.flag);
     ctx->avail_d = (uint8_t*)(b + c.avail);
 
@@ -338,14 +342,14 @@ hadfl_status hadfl_local_steps(hadfl_ctx* ctx)
 }
 
 static hadfl_status select_common(hadfl_ctx* ctx, const int32_t* versions_i32, const double* versions_f64,
-                                  const uint8_t* avail_host, uint64_t cycle)
+                                  const uint8_t* avail_host, uint64_t cycle, int n_select)
 {
     const int N = ctx->cfg.n_replicas;
     const uint8_t* avail_d = nullptr;
     if (avail_host) {
         int na = 0;
         for (int k = 0; k < N; ++k) na += avail_host[k] ? 1 : 0;
-        if (na < ctx->cfg.n_select) return fail(ctx, HADFL_EINVAL, "fewer available replicas than n_select");
+        if (na < n_select) return fail(ctx, HADFL_EINVAL, "fewer available replicas than n_select");
         // the pinned staging buffer is reused: wait for the previous copy out of it
         HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
         for (int k = 0; k < N; ++k) ctx->avail_pinned[k] = avail_host[k] ? 1 : 0;
@@ -356,7 +360,7 @@ static hadfl_status select_common(hadfl_ctx* ctx, const int32_t* versions_i32, c
     a.versions = versions_i32;
     a.versions_f64 = versions_f64;
     a.avail = avail_d;
-    a.n = N; a.n_select = ctx->cfg.n_select; a.weight_mode = ctx->cfg.weight_mode;
+    a.n = N; a.n_select = n_select; a.weight_mode = ctx->cfg.weight_mode;
     a.seed = ctx->cfg.seed; a.cycle = cycle;
     a.selected = ctx->selected; a.sel_sorted = ctx->sel_sorted; a.sel_weight = ctx->sel_weight;
     a.flag = ctx->flag; a.weights = ctx->weights; a.f = ctx->f;
@@ -365,13 +369,14 @@ static hadfl_status select_common(hadfl_ctx* ctx, const int32_t* versions_i32, c
     ctx->prof.end(ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "select kernel");
     ctx->have_selection = true;
+    ctx->last_n_select = n_select;
     return HADFL_OK;
 }
 
 hadfl_status hadfl_select(hadfl_ctx* ctx, const int32_t* versions_dev, const uint8_t* avail_host, uint64_t cycle)
 {
     if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
-    return select_common(ctx, versions_dev ? versions_dev : ctx->tb.versions, nullptr, avail_host, cycle);
+    return select_common(ctx, versions_dev ? versions_dev : ctx->tb.versions, nullptr, avail_host, cycle, ctx->cfg.n_select);
 }
 
 hadfl_status hadfl_select_real(hadfl_ctx* ctx, const double* versions_dev, const uint8_t* avail_host, uint64_t cycle)
@@ -380,7 +385,8 @@ hadfl_status hadfl_select_real(hadfl_ctx* ctx, const double* versions_dev, const
     if (!versions_dev && !ctx->have_forecast)
         return fail(ctx, HADFL_ESTATE, "hadfl_select_real without versions needs a preceding hadfl_predict_versions");
     if (versions_dev && ((uintptr_t)versions_dev & 7)) return fail(ctx, HADFL_EINVAL, "versions_dev must be 8-byte aligned");
-    return select_common(ctx, nullptr, versions_dev ? versions_dev : ctx->pred + 2 * (size_t)ctx->cfg.n_replicas, avail_host, cycle);
+    return select_common(ctx, nullptr, versions_dev ? versions_dev : ctx->pred + 2 * (size_t)ctx->cfg.n_replicas, avail_host, cycle,
+                         ctx->cfg.n_select);
 }
 
 hadfl_status hadfl_predict_versions(hadfl_ctx* ctx, const int32_t* versions_dev, double alpha, int32_t horizon)
@@ -466,11 +472,41 @@ hadfl_status hadfl_aggregate(hadfl_ctx* ctx, int32_t resync)
     if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
     if (!ctx->have_selection) return fail(ctx, HADFL_ESTATE, "hadfl_aggregate needs a preceding hadfl_select");
     // algorithmic traffic: n_select rows read, the aggregate written (+ every replica row written when broadcasting)
-    const double agg_bytes = 4.0 * (double)ctx->plan.m_total * (ctx->cfg.n_select + 1 + (resync ? ctx->cfg.n_replicas : 0));
+    const double agg_bytes = 4.0 * (double)ctx->plan.m_total * (ctx->last_n_select + 1 + (resync ? ctx->cfg.n_replicas : 0));
     ctx->prof.begin(resync ? "aggregate_bcast" : "aggregate", ctx->stream, 0.0, agg_bytes);
     hipError_t e = launch_aggregate(ctx->replicas, ctx->plan.row_stride, ctx->plan.row_stride, ctx->sel_sorted,
-                                    ctx->sel_weight, ctx->cfg.n_select, ctx->agg, resync ? ctx->cfg.n_replicas : 0,
-                                    ctx->replicas, ctx->stream);
+                                    ctx->sel_weight, ctx->last_n_select, ctx->agg, resync ? ctx->cfg.n_replicas : 0,
+                                    ctx->replicas, nullptr, ctx->stream);
+    ctx->prof.end(ctx->stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "aggregate kernel");
+    ctx->have_agg = true;
+    return HADFL_OK;
+}
+
+hadfl_status hadfl_select_group(hadfl_ctx* ctx, const int32_t* versions_dev, const uint8_t* member_host, int32_t n_select,
+                                uint64_t cycle)
+{
+    if (!ctx || !member_host) return fail(ctx, HADFL_EINVAL, "null argument");
+    if (n_select < 1 || n_select > ctx->cfg.n_select) return fail(ctx, HADFL_EINVAL, "n_select must be in [1, cfg.n_select]");
+    return select_common(ctx, versions_dev ? versions_dev : ctx->tb.versions, nullptr, member_host, cycle, n_select);
+}
+
+hadfl_status hadfl_aggregate_group(hadfl_ctx* ctx, const uint8_t* member_host)
+{
+    if (!ctx || !member_host) return fail(ctx, HADFL_EINVAL, "null argument");
+    if (!ctx->have_selection) return fail(ctx, HADFL_ESTATE, "hadfl_aggregate_group needs a preceding selection");
+    const int N = ctx->cfg.n_replicas;
+    // the list below is copied from a host vector that is about to change: let an earlier copy out of it finish
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->bcast_h.clear();
+    for (int k = 0; k < N; ++k) if (member_host[k]) ctx->bcast_h.push_back(k);
+    const int nb = (int)ctx->bcast_h.size();
+    if (nb > 0)
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->bcast_d, ctx->bcast_h.data(), sizeof(int32_t) * nb, hipMemcpyHostToDevice, ctx->stream));
+    const double agg_bytes = 4.0 * (double)ctx->plan.m_total * (ctx->last_n_select + 1 + nb);
+    ctx->prof.begin("aggregate_group", ctx->stream, 0.0, agg_bytes);
+    hipError_t e = launch_aggregate(ctx->replicas, ctx->plan.row_stride, ctx->plan.row_stride, ctx->sel_sorted,
+                                    ctx->sel_weight, ctx->last_n_select, ctx->agg, nb, ctx->replicas, ctx->bcast_d, ctx->stream);
     ctx->prof.end(ctx->stream);
     if (e != hipSuccess) return hip_fail(ctx, e, "aggregate kernel");
     ctx->have_agg = true;

@@ -25,10 +25,11 @@ hipError_t launch_predict(const int32_t* versions, double* s1, double* s2, doubl
 
 // ---- aggregation + global synchronisation (Sec. 2.3, Algorithm 1) ----------
 // agg[j] = sum_i sel_weight[i] * rows[sel_sorted[i]][j], i ascending; if n_bcast > 0 the result is also written
-// to rows 0..n_bcast-1.  len is a multiple of 4 floats, all pointers 16-byte aligned.
+// to rows 0..n_bcast-1, or to rows bcast_list[0..n_bcast-1] when a list is given.  len is a multiple of 4 floats, all
+// pointers 16-byte aligned.
 hipError_t launch_aggregate(const float* rows, int64_t row_stride, int64_t len, const int32_t* sel_sorted,
                             const float* sel_weight, int n_select, float* agg, int n_bcast, float* rows_out,
-                            hipStream_t s);
+                            const int32_t* bcast_list, hipStream_t s);
 
 // ---- small utilities --------------------------------------------------------
 hipError_t launch_copy_f32(const float* src, float* dst, int64_t count, hipStream_t s);

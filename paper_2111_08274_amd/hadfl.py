@@ -41,7 +41,8 @@ class HadflKernelTime(ctypes.Structure):
 
 
 EXPORTS = ("hadfl_param_count", "hadfl_param_layout", "hadfl_workspace_bytes", "hadfl_init_replicas",
-           "hadfl_local_steps", "hadfl_select", "hadfl_aggregate", "hadfl_steps_from_times", "hadfl_set_lr", "hadfl_set_steps", "hadfl_predict_versions",
+           "hadfl_local_steps", "hadfl_select", "hadfl_aggregate", "hadfl_steps_from_times", "hadfl_set_lr", "hadfl_set_steps",
+           "hadfl_select_group", "hadfl_aggregate_group", "hadfl_predict_versions",
            "hadfl_select_real", "hadfl_get_predicted", "hadfl_get_steps", "hadfl_get_versions",
            "hadfl_get_selected", "hadfl_get_params", "hadfl_get_losses", "hadfl_profile_enable",
            "hadfl_profile_read", "hadfl_last_error", "hadfl_destroy")
@@ -77,6 +78,8 @@ def lib():
         L.hadfl_set_steps.argtypes = [vp, vp]
         L.hadfl_steps_from_times.argtypes = [vp, i32, i32, ctypes.c_double, i32, i32, vp]
         L.hadfl_set_lr.argtypes = [vp, ctypes.c_float]
+        L.hadfl_select_group.argtypes = [vp, vp, vp, i32, ctypes.c_uint64]
+        L.hadfl_aggregate_group.argtypes = [vp, vp]
         L.hadfl_predict_versions.argtypes = [vp, vp, ctypes.c_double, i32]
         L.hadfl_select_real.argtypes = [vp, vp, vp, ctypes.c_uint64]
         L.hadfl_get_predicted.argtypes = [vp, vp]
@@ -213,6 +216,7 @@ class Context:
             assert versions.dtype.__str__() == "torch.int32" and versions.is_cuda and versions.numel() == self.cfg.n_replicas
         _check(lib().hadfl_select(self.h, versions.data_ptr() if versions is not None else None,
                                   _np_ptr(av) if av is not None else None, int(cycle)), self.h)
+        self._n_last = self.cfg.n_select
 
     def set_lr(self, lr):
         _check(lib().hadfl_set_lr(self.h, float(lr)), self.h)
@@ -236,11 +240,26 @@ class Context:
             assert versions.dtype.__str__() == "torch.float64" and versions.is_cuda and versions.numel() == self.cfg.n_replicas
         _check(lib().hadfl_select_real(self.h, versions.data_ptr() if versions is not None else None,
                                        _np_ptr(av) if av is not None else None, int(cycle)), self.h)
+        self._n_last = self.cfg.n_select
 
     def predicted(self):
         out = np.zeros(self.cfg.n_replicas, dtype=np.float64)
         _check(lib().hadfl_get_predicted(self.h, _np_ptr(out)), self.h)
         return out
+
+    def select_group(self, cycle, members, n_select, versions=None):
+        mb = np.ascontiguousarray(members, dtype=np.uint8)
+        assert mb.size == self.cfg.n_replicas
+        if versions is not None:
+            assert versions.dtype.__str__() == "torch.int32" and versions.is_cuda and versions.numel() == self.cfg.n_replicas
+        _check(lib().hadfl_select_group(self.h, versions.data_ptr() if versions is not None else None, _np_ptr(mb),
+                                        int(n_select), int(cycle)), self.h)
+        self._n_last = int(n_select)
+
+    def aggregate_group(self, members):
+        mb = np.ascontiguousarray(members, dtype=np.uint8)
+        assert mb.size == self.cfg.n_replicas
+        _check(lib().hadfl_aggregate_group(self.h, _np_ptr(mb)), self.h)
 
     def aggregate(self, resync=True):
         _check(lib().hadfl_aggregate(self.h, int(bool(resync))), self.h)
@@ -261,7 +280,7 @@ class Context:
         flag = np.zeros(self.cfg.n_replicas, dtype=np.uint8)
         w = np.zeros(self.cfg.n_replicas, dtype=np.float32)
         _check(lib().hadfl_get_selected(self.h, _np_ptr(sel), _np_ptr(flag), _np_ptr(w)), self.h)
-        return sel, flag, w
+        return sel[:getattr(self, "_n_last", self.cfg.n_select)], flag, w
 
     def params(self, replica, n=None):
         n = self.m_total if n is None else n

@@ -1,0 +1,45 @@
+"""Device groups (paper Sec. 3.3, last paragraph): intra-group rounds select and synchronise inside a group, the
+inter-group round runs every second one over everybody.  HIP path against the oracle."""
+import numpy as np
+import pytest
+
+from oracle import nets
+from paper_2111_08274_amd import hadfl, synth
+from tests.pair import Pair
+
+pytestmark = pytest.mark.gpu
+
+
+def test_grouped_synchronisation_parity():
+    cfg, x, y = synth.config_inputs(2, n_samples=128)
+    fn, shape = nets.NETS["cnn2"]
+    N = cfg["n_replicas"]                                    # 8 devices, powers 1 1 2 2 3 3 4 4
+    p = Pair(fn(), shape, N, 4, x, y, cfg["batch"], cfg["lr"], 0.9, cfg["ratio"], net_name="cnn2")
+    groups = [np.array([1, 0, 1, 0, 1, 0, 1, 0], dtype=np.uint8), np.array([0, 1, 0, 1, 0, 1, 0, 1], dtype=np.uint8)]
+    for rnd in range(4):
+        p.local_steps()
+        for g, members in enumerate(groups):
+            p.gpu.select_group(2 * rnd + g, members, 2)
+            p.cpu.select_group(2 * rnd + g, members, 2)
+            sel, flag, w = p.gpu.selected()
+            assert sel.tolist() == p.cpu.selected.tolist() and flag.tolist() == p.cpu.flag.tolist()
+            assert all(members[k] for k in sel)
+            p.gpu.aggregate_group(members)
+            p.cpu.aggregate_group(members)
+        d = p.max_param_diff()
+        if rnd % 2 == 1:                                      # inter-group round: the ordinary calls over everybody
+            d_agg = p.select_aggregate(100 + rnd)
+            d = max(d, d_agg, p.max_param_diff())
+        print("round", rnd, "max |w_gpu - w_oracle|", d, flush=True)
+        assert d <= 1e-4
+    # after an inter-group round every device holds the same model
+    ref = p.gpu.params(0)
+    assert all(np.array_equal(p.gpu.params(k), ref) for k in range(N))
+    # errors: more devices asked for than the group has, or than cfg.n_select
+    einval = hadfl.STATUS_NAMES.index("HADFL_EINVAL")
+    few = np.array([1, 0, 0, 0, 0, 0, 0, 0], dtype=np.uint8)
+    for members, n in ((few, 2), (groups[0], 5), (groups[0], 0)):
+        with pytest.raises(hadfl.HadflError) as e:
+            p.gpu.select_group(0, members, n)
+        assert e.value.status == einval
+    p.close()

@@ -78,3 +78,25 @@ def test_cycle_bookkeeping_and_momentum_survive_synchronisation():
     assert np.array_equal(cyc.buf, buf_before)
     cyc.run_cycle(2)
     assert cyc.versions.tolist() == [1, 2, 3, 4] and cyc.cursor.tolist() == [2, 4, 6, 8]
+
+
+def test_grouped_rounds_mean_of_group_means_is_the_global_mean():
+    # Sec. 3.3, last paragraph: two equal groups, everybody selected inside each group, then an inter-group round over
+    # everybody: group members hold their group's mean after the intra-group rounds, so the inter-group mean is the mean
+    # of the group means -- for equal groups, the plain mean of all devices (FedAvg's aggregation equation).
+    net, w0, x, y, cyc = _toy(4, [1, 2, 3, 4], 2)
+    cyc.local_steps()
+    before = cyc.params.copy()
+    groups = [np.array([1, 1, 0, 0], dtype=np.uint8), np.array([0, 0, 1, 1], dtype=np.uint8)]
+    for g, members in enumerate(groups):
+        sel = cyc.select_group(g, members, 2)
+        assert sorted(sel.tolist()) == np.flatnonzero(members).tolist()          # nobody outside the group is drawn
+        agg = cyc.aggregate_group(members)
+        assert np.abs(agg - before[members.astype(bool)].mean(axis=0)).max() < 1e-15
+        other = groups[1 - g].astype(bool)
+        if g == 0:
+            assert np.array_equal(cyc.params[other], before[other])               # the other group is untouched
+    assert np.array_equal(cyc.params[0], cyc.params[1]) and np.array_equal(cyc.params[2], cyc.params[3])
+    cyc.n_select = 4
+    cyc.select(9); cyc.aggregate(resync=True)
+    assert np.abs(cyc.agg - before.mean(axis=0)).max() < 1e-15
