@@ -351,6 +351,14 @@ struct Runner {
             p.a_f32 = l.in0 == 0;
             p.out = actw(ot); p.out_rep = e.rep_block;
             p.relu = e.fused_relu[i];
+            {
+                FirstConvParams fc;
+                if (first_conv(i, fc)) {
+                    fc.out = actw(ot); fc.out_rep = e.rep_block; fc.relu = p.relu;
+                    run("conv_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_conv_first_fwd(fc, na, s); });
+                    break;
+                }
+            }
             if (e.fast[i]) {
                 FastConvParams f{};
                 f.B = p.B; f.H = p.H; f.W = p.W; f.C = p.Cin; f.N = p.Cout; f.R = p.R; f.S = p.S; f.pad = p.pad;
@@ -387,6 +395,24 @@ struct Runner {
             run("bn_fwd", 0, asz() * (8.0 * B * a.numel()), [&] { return launch_bn_fwd(b, na, s); });
             break; }
         }
+    }
+
+    // bf16 configuration: the first convolution (data set in) has its own kernels when its footprint fits one MFMA
+    bool first_conv(size_t i, FirstConvParams& f) const
+    {
+        const Layer& l = e.plan.layers[i];
+        if (!e.cfg.bf16 || l.type != HADFL_OP_CONV || l.in0 != 0 || l.stride != 1) return false;
+        if (l.bias && l.b_off != l.w_off + l.w_count) return false;
+        const TensorShape a = e.plan.tensors[0], r = e.plan.tensors[l.out];
+        if (r.h != a.h || r.w != a.w) return false;
+        f = FirstConvParams{};
+        f.x = e.buf.x; f.cursor = e.buf.cursor; f.n_samples = e.cfg.n_samples;
+        f.B = e.cfg.batch; f.H = a.h; f.W = a.w; f.C = a.c; f.N = l.cout; f.R = f.S = l.k; f.pad = l.pad;
+        f.K = l.k * l.k * a.c; f.M = e.cfg.batch * a.h * a.w;
+        f.w = e.buf.replicas + l.w_off; f.w_rep = e.plan.row_stride;
+        f.bias = l.bias ? e.buf.replicas + l.b_off : nullptr;
+        f.order = e.buf.order;
+        return conv_first_supported(f);
     }
 
     BnParams bn_params(size_t i) const
@@ -446,6 +472,12 @@ struct Runner {
             } else {
                 p.out = e.buf.grad + l.w_off; p.out_rep = e.plan.row_stride;
             }
+            FirstConvParams fc;
+            if (first_conv(i, fc)) {
+                fc.dy = grad(ot); fc.dy_rep = e.rep_block;
+                fc.gout = p.out; fc.gout_rep = p.out_rep; fc.gout_split = p.out_split; fc.splits = p.splits; fc.kchunk = p.kchunk;
+                run("conv_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return launch_conv_first_wgrad(fc, na, s); });
+            } else
             if (e.fast[i]) {
                 FastWgradParams f{};
                 f.B = p.B; f.H = p.H; f.W = p.W; f.C = p.Cin; f.N = p.Cout; f.R = p.R; f.S = p.S; f.pad = p.pad;

@@ -74,6 +74,21 @@ struct FastWgradParams {     // dW[(tap, ci) | bias row][co] over pixels; needs 
 };
 hipError_t launch_wgrad_fast(const FastWgradParams& p, int n_active, hipStream_t s);
 
+// ---- bf16 configuration, first convolution (fp32 data set in, few channels): conv_first_bf16.hip ----
+struct FirstConvParams {     // K = R*S*C footprint values per pixel (K + bias row <= 32), N = 32 or 64 output channels, stride 1
+    const float* x; const long long* cursor; int n_samples;     // data set [replica][n_samples][H][W][C] and batch cursors
+    int B, H, W, C, N, R, S, pad, K, M;                          // M = B*H*W pixels of a batch
+    const float* w; long long w_rep;                             // fp32 weights [K][N] inside the replica rows (stride w_rep)
+    const float* bias;                                           // inside the same rows, or null
+    void* out; long long out_rep; int relu;                      // forward: bf16 [M][N]
+    const void* dy; long long dy_rep;                            // weight gradient: bf16 [M][N]
+    float* gout; long long gout_rep, gout_split; int splits, kchunk;   // rows 0..K-1 weights, row K bias; split over pixels
+    const int* order;
+};
+bool conv_first_supported(const FirstConvParams& p);
+hipError_t launch_conv_first_fwd(const FirstConvParams& p, int n_active, hipStream_t s);
+hipError_t launch_conv_first_wgrad(const FirstConvParams& p, int n_active, hipStream_t s);
+
 struct WeightPrepParams {    // fp32 W[tap][C][N] -> bf16 Wf[N][tap*C + ci] and Wb[C][(taps-1-tap)*N + co]
     const float* w; long long w_rep;
     __bf16* wf; __bf16* wb; long long wbf_rep;
