@@ -254,12 +254,14 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
 // fetch: it reads every activation once per tap.  Here a workgroup owns 256 consecutive pixels of one image (whole
 // rows), loads them ONCE per 64-channel slice together with their one-pixel border (zeros outside the image) into
 // LDS, and serves all R*S taps from that patch by shifting the row it reads; only the weights still stream per tap.
-// IW = image width; 3x3-style filters with pad = (R-1)/2 <= 1.  Wave grid 2 x 2, wave tile 128 x BN/2.
-template <int IW, int BN, int EPI>
+// IW = image width; 3x3-style filters with pad = (R-1)/2 <= 1.
+template <int IW, int BN, int WGM, int EPI>
 __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
 {
     constexpr int BMT = 256, LDQ = 72, PW = IW + 2, TR = BMT / IW, PR = (TR + 2) * PW;   // patch: (TR + 2) x (IW + 2) pixels
-    constexpr int TM = 4, TN = BN / 64;
+    constexpr int WGN = 4 / WGM;                              // wave grid WGM x WGN, wave tile (256 / WGM) x (BN / WGN)
+    constexpr int TM = 256 / WGM / 32, TN = BN / WGN / 32;
+    static_assert(TM >= 1 && TN >= 1, "");
     constexpr int NQB = BN * 8 / 256;
     constexpr int NQP = (PR * 8 + 255) / 256;                 // patch slots per thread
     constexpr unsigned P_BYTES = PR * LDQ * 2;
@@ -268,7 +270,7 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
     char* const sB = smem + P_BYTES;                          // [BN][LDQ] weights of one tap and channel slice
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     const unsigned tiles_m = (unsigned)p.M / BMT, tiles_n = (unsigned)p.N / BN;
     const unsigned item = logical_block();
     if (item >= tiles_m * tiles_n * (unsigned)p.n_active) return;
@@ -300,10 +302,10 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
     unsigned a_rd[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int pm = wm * 128 + i * 32 + (lane & 31);
+        const int pm = wm * (256 / WGM) + i * 32 + (lane & 31);
         a_rd[i] = (unsigned)(((pm / IW) * PW + (pm % IW)) * LDQ + (lane >> 5) * 8) * 2u;
     }
-    const unsigned b_rd = (unsigned)((wn * (BN / 2) + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
+    const unsigned b_rd = (unsigned)((wn * (BN / WGN) + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
 
     f16 acc[TM][TN];
 #pragma unroll
@@ -364,12 +366,12 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
     const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int mm = m0 + wm * 128 + i * 32 + (lane & 31);
+        const int mm = m0 + wm * (256 / WGM) + i * 32 + (lane & 31);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * (BN / 2) + j * 32 + 8 * g + 4 * (lane >> 5);
+                const int n = n0 + wn * (BN / WGN) + j * 32 + 8 * g + 4 * (lane >> 5);
                 const unsigned o = (unsigned)(mm * p.N + n) * 2u;
                 f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
                 if (EPI == 0) {
@@ -799,17 +801,18 @@ hipError_t launch_conv_fast(const FastConvParams& p0, int epi, int n_active, hip
         (p.H * p.W) % 256 == 0 && p.M % 256 == 0 && p.tile_hint != 2) {
         const int bn = (p.N % 128 == 0) ? 128 : 64;
         const dim3 grid(die_grid((long long)(p.M / 256) * (p.N / bn) * n_active)), block(256);
-#define HADFL_PATCH(IW_, BN_) do { \
+#define HADFL_PATCH(IW_, BN_, WGM_) do { \
             constexpr size_t lds = (size_t)((256 / IW_ + 2) * (IW_ + 2) + BN_) * 72 * 2; \
-            static const bool ok = hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess && \
-                                   hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess; \
+            static const bool ok = hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, WGM_, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess && \
+                                   hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, WGM_, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess; \
             if (!ok) return hipErrorInvalidValue; \
-            if (epi == 0) hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, 0>), grid, block, lds, s, p); \
-            else hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, 1>), grid, block, lds, s, p); } while (0)
-        if (p.W == 32 && bn == 128) HADFL_PATCH(32, 128);
-        else if (p.W == 32) HADFL_PATCH(32, 64);
-        else if (bn == 128) HADFL_PATCH(16, 128);
-        else HADFL_PATCH(16, 64);
+            if (epi == 0) hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, WGM_, 0>), grid, block, lds, s, p); \
+            else hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, WGM_, 1>), grid, block, lds, s, p); } while (0)
+        // 128 output channels: waves 2 x 2 (128 x 64 each); 64: waves 4 x 1 (64 x 64 each)
+        if (p.W == 32 && bn == 128) HADFL_PATCH(32, 128, 2);
+        else if (p.W == 32) HADFL_PATCH(32, 64, 4);
+        else if (bn == 128) HADFL_PATCH(16, 128, 2);
+        else HADFL_PATCH(16, 64, 4);
 #undef HADFL_PATCH
         return hipGetLastError();
     }
