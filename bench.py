@@ -22,11 +22,17 @@ MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 PAPER_CONTEXT = {"speedup_vs_decentralized_fedavg": 3.15, "speedup_vs_pytorch_distributed": 4.68,
                  "hardware": "4x V100, PCIe 3.0 x8, CIFAR-10, time-to-max-accuracy (Table 1, Sec. 4.2)"}
 # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE (scaled by a plain copy of known size; see profiles/),
-# valid only while the kernel's source file is unchanged: (source file, sha256 at measurement, workload, bytes)
+# valid only while the kernel's source files are unchanged: (kernel, workload) -> (source files, sha256 of their
+# concatenation at measurement, bytes)
 TRAFFIC = {
     ("aggregate", "agg-stress-n64"): (("paper_2111_08274_amd/csrc/aggregate.hip",),
-                                      "82d23ef5563a057ede8300c4f42727e1f09a1ffe25e76238a46006f416269703",
-                                      (174613.6 * 2.0 + 43648.5 * 1.0) * 1024.0),
+                                      "ee3f9871add01e241b80b96d0fcdd3250747a0ef8da76f148d5575daca1ed43f",
+                                      402288103.0),
+    # all weight-gradient launches of a cycle, averaged (the figure includes the fused update's parameter traffic)
+    ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
+                                        "paper_2111_08274_amd/csrc/conv_first_bf16.hip"),
+                                       "92ba173ae1cdb7754c5b944da525844b75ab535011ed187331c4bede1bf85d11",
+                                       545061336.0),
 }
 
 
