@@ -463,6 +463,16 @@ struct Runner {
             p.dy = grad(ot); p.dy_rep = e.rep_block;
             p.splits = e.splits[i];
             const int64_t mn = (int64_t)p.M * p.N;
+            if (p.splits > 1 && e.fast[i] && (p.W == 16 || p.W == 32) && p.Cin <= 128 && p.N <= 128) {
+                // Wide-image layers run the all-taps kernel: few tiles (one per 64 x 64 channel pair) and a small result,
+                // so a sub-step with few active replicas can split K further at little cost; the partial-sum buffer
+                // (sized for all replicas at the planned split count) bounds how far.
+                const int64_t tiles = (int64_t)(p.Cin / 64) * (p.N / 64);
+                const int64_t want = (1024 + tiles * na - 1) / (tiles * na);
+                const int64_t by_buffer = e.shared_floats / ((int64_t)na * ((mn + 63) / 64 * 64));
+                const int64_t by_k = std::max<int64_t>(1, p.K / 512);
+                p.splits = (int)std::max<int64_t>(p.splits, std::min<int64_t>(std::min<int64_t>(want, by_buffer), std::min<int64_t>(by_k, 256)));
+            }
             if (p.splits > 1) {
                 const int unit = e.fast[i] ? 64 : 16;      // slab length of the kernel that will run
                 const int slabs = (p.K + unit - 1) / unit;
