@@ -351,6 +351,7 @@ __global__ __launch_bounds__(256) void bn_sums_vec_kernel(BnParams p)
             for (int e = 0; e < VEC; ++e) { a[e] = sv[g.c + e]; b[e] = sv[p.C + g.c + e]; }
         }
         const int r0 = g.chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
+#pragma unroll 4
         for (int r = r0 + g.rl; r < r1; r += g.rl_count) {
             float v[VEC];
             ldv(x, (long long)r * p.C + g.c, v);
@@ -445,6 +446,7 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_vec_kernel(BnParams p)
         sc[e] = gamma * istd; sh[e] = beta - mean * gamma * istd;
     }
     const int r0 = g.chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
+#pragma unroll 4
     for (int r = r0 + g.rl; r < r1; r += g.rl_count) {
         float v[VEC];
         const long long i = (long long)r * p.C + g.c;
@@ -479,6 +481,7 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_vec_kernel(BnParams p)
         kb[e] = db * inv_n; kg[e] = dg * inv_n;
     }
     const int r0 = g.chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
+#pragma unroll 4
     for (int r = r0 + g.rl; r < r1; r += g.rl_count) {
         const long long i = (long long)r * p.C + g.c;
         float v[VEC], d[VEC], o[VEC];
