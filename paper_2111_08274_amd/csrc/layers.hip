@@ -314,6 +314,79 @@ __device__ __forceinline__ void stv(__bf16* p, long long i, const float (&o)[8])
     *reinterpret_cast<bf8v*>(p + i) = v;
 }
 
+// 2 x 2 max pooling, one thread per pooled pixel and group of VEC channels (16-byte accesses); count = pooled elements.
+// Same results as the scalar kernels above, which stay for channel counts that are not a multiple of VEC.
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_fwd_vec_kernel(EwParams p)
+{
+    constexpr int VEC = VecOf<T>::n;
+    const int rep = p.order[blockIdx.y];
+    const T* in = tptr<T>(p.in, rep, p.in_rep);
+    T* out = tptr<T>(p.out, rep, p.out_rep);
+    const int Ho = p.H / 2, Wo = p.W / 2, CV = p.C / VEC;
+    const long long nvec = p.count / VEC;
+    const long long rowp = (long long)p.W * p.C;
+    for (long long i = gtid(); i < nvec; i += gstride()) {
+        const int cv = (int)(i % CV);
+        long long t = i / CV;
+        const int xo = (int)(t % Wo); t /= Wo;
+        const int yo = (int)(t % Ho);
+        const int b = (int)(t / Ho);
+        const long long q = (((long long)b * p.H + 2 * yo) * p.W + 2 * xo) * p.C + cv * VEC;
+        float a0[VEC], a1[VEC], a2[VEC], a3[VEC];
+        ldv(in, q, a0); ldv(in, q + p.C, a1); ldv(in, q + rowp, a2); ldv(in, q + rowp + p.C, a3);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) a0[e] = fmaxf(fmaxf(a0[e], a1[e]), fmaxf(a2[e], a3[e]));
+        stv(out, i * VEC, a0);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_bwd_vec_kernel(EwParams p)
+{
+    constexpr int VEC = VecOf<T>::n;
+    const int rep = p.order[blockIdx.y];
+    const T* x = tptr<T>(p.in, rep, p.in_rep);
+    const T* dout = tptr<T>(p.in2, rep, p.in2_rep);
+    T* din = tptr<T>(p.out, rep, p.out_rep);
+    const int Ho = p.H / 2, Wo = p.W / 2, CV = p.C / VEC;
+    const long long nvec = p.count / VEC;
+    const long long rowp = (long long)p.W * p.C;
+    for (long long i = gtid(); i < nvec; i += gstride()) {
+        const int cv = (int)(i % CV);
+        long long t = i / CV;
+        const int xo = (int)(t % Wo); t /= Wo;
+        const int yo = (int)(t % Ho);
+        const int b = (int)(t / Ho);
+        const long long base = (((long long)b * p.H + 2 * yo) * p.W + 2 * xo) * p.C + cv * VEC;
+        const long long off[4] = {0, p.C, rowp, rowp + p.C};
+        float v[4][VEC], g[VEC];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ldv(x, base + off[j], v[j]);
+        ldv(dout, i * VEC, g);
+        int arg[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            float m = v[0][e]; arg[e] = 0;
+#pragma unroll
+            for (int j = 1; j < 4; ++j) if (v[j][e] > m) { m = v[j][e]; arg[e] = j; }     // first maximum in scan order
+            // with p.mask set, x is a fused ReLU output: the gradient passes only where it is positive
+            if (p.mask && !(m > 0.f)) arg[e] = -1;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float o[VEC];
+            if (p.accumulate) ldv(din, base + off[j], o);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const float w = (arg[e] == j) ? g[e] : 0.f;
+                o[e] = p.accumulate ? o[e] + w : w;
+            }
+            stv(din, base + off[j], o);
+        }
+    }
+}
+
 struct BnGeo { int cvb, rl_count, cgroups, chunk, cv, rl, c; bool live; };
 __device__ __forceinline__ BnGeo bn_geo(const BnParams& p, int vec)
 {
@@ -608,13 +681,39 @@ dim3 ew_grid(long long count, int n_active)
         return hipGetLastError(); }
 HADFL_EW_LAUNCH(launch_relu_fwd, relu_fwd_kernel)
 HADFL_EW_LAUNCH(launch_relu_bwd, relu_bwd_kernel)
-HADFL_EW_LAUNCH(launch_maxpool_fwd, maxpool_fwd_kernel)
-HADFL_EW_LAUNCH(launch_maxpool_bwd, maxpool_bwd_kernel)
 HADFL_EW_LAUNCH(launch_add_fwd, add_fwd_kernel)
 HADFL_EW_LAUNCH(launch_pass_grad, pass_grad_kernel)
 HADFL_EW_LAUNCH(launch_gap_fwd, gap_fwd_kernel)
 HADFL_EW_LAUNCH(launch_gap_bwd, gap_bwd_kernel)
 #undef HADFL_EW_LAUNCH
+
+hipError_t launch_maxpool_fwd(const EwParams& p, int n_active, hipStream_t s)
+{
+    if (n_active < 1 || p.count < 1) return hipSuccess;
+    const int vec = p.bf16 ? 8 : 4;
+    if (p.C % vec == 0) {
+        if (p.bf16) hipLaunchKernelGGL(maxpool_fwd_vec_kernel<__bf16>, ew_grid(p.count / vec, n_active), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL(maxpool_fwd_vec_kernel<float>, ew_grid(p.count / vec, n_active), dim3(256), 0, s, p);
+    } else {
+        if (p.bf16) hipLaunchKernelGGL(maxpool_fwd_kernel<__bf16>, ew_grid(p.count, n_active), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL(maxpool_fwd_kernel<float>, ew_grid(p.count, n_active), dim3(256), 0, s, p);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool_bwd(const EwParams& p, int n_active, hipStream_t s)
+{
+    if (n_active < 1 || p.count < 1) return hipSuccess;
+    const int vec = p.bf16 ? 8 : 4;
+    if (p.C % vec == 0) {
+        if (p.bf16) hipLaunchKernelGGL(maxpool_bwd_vec_kernel<__bf16>, ew_grid(p.count / vec, n_active), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL(maxpool_bwd_vec_kernel<float>, ew_grid(p.count / vec, n_active), dim3(256), 0, s, p);
+    } else {
+        if (p.bf16) hipLaunchKernelGGL(maxpool_bwd_kernel<__bf16>, ew_grid(p.count, n_active), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL(maxpool_bwd_kernel<float>, ew_grid(p.count, n_active), dim3(256), 0, s, p);
+    }
+    return hipGetLastError();
+}
 
 hipError_t launch_dense_small_fwd(const DenseSmallParams& p, int n_active, hipStream_t s)
 {
