@@ -733,32 +733,32 @@ __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(FastWgradParams p)
 
 // ---------------------------------------------------------------------------------------------------------------
 // Weight preparation: fp32 master W[tap][ci][co] -> Wf[co][tap*C + ci] and Wb[ci][(T-1-tap)*N + co], both bf16.
-// Block (32, 8) handles one tap and a 32 x 32 (ci, co) tile.
+// A workgroup handles one tap and a 64 x 64 (ci, co) tile: 256-byte reads, whole 128-byte lines written to both copies.
 // ---------------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void weight_prep_kernel(WeightPrepParams p)
 {
-    __shared__ float tile[32][33];
+    __shared__ float tile[64][65];
     const int rep = p.order[blockIdx.z];
     const int taps = p.taps;
     const int tap = blockIdx.y % taps, cot = blockIdx.y / taps;
-    const int ci0 = blockIdx.x * 32, co0 = cot * 32;
+    const int ci0 = blockIdx.x * 64, co0 = cot * 64;
     const float* w = p.w + (long long)rep * p.w_rep + ((long long)tap * p.C) * p.N;
     __bf16* wf = p.wf + (long long)rep * p.wbf_rep;
     __bf16* wb = p.wb + (long long)rep * p.wbf_rep;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     const int K = taps * p.C, Kb = taps * p.N;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int ci = ci0 + ty + 8 * r;
+    for (int r = 0; r < 16; ++r) {
+        const int ci = ci0 + ty + 4 * r;
         const float v = w[(long long)ci * p.N + co0 + tx];
-        tile[ty + 8 * r][tx] = v;
+        tile[ty + 4 * r][tx] = v;
         wb[(long long)ci * Kb + (taps - 1 - tap) * p.N + co0 + tx] = (__bf16)v;
     }
     __syncthreads();
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int co = co0 + ty + 8 * r;
-        wf[(long long)co * K + tap * p.C + ci0 + tx] = (__bf16)tile[tx][ty + 8 * r];
+    for (int r = 0; r < 16; ++r) {
+        const int co = co0 + ty + 4 * r;
+        wf[(long long)co * K + tap * p.C + ci0 + tx] = (__bf16)tile[tx][ty + 4 * r];
     }
 }
 
@@ -899,7 +899,8 @@ hipError_t launch_wgrad_fast(const FastWgradParams& p0, int n_active, hipStream_
 hipError_t launch_weight_prep(const WeightPrepParams& p, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
-    const dim3 grid((unsigned)(p.C / 32), (unsigned)(p.taps * (p.N / 32)), (unsigned)n_active), block(256);
+    if (p.C % 64 != 0 || p.N % 64 != 0) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(p.C / 64), (unsigned)(p.taps * (p.N / 64)), (unsigned)n_active), block(256);
     hipLaunchKernelGGL(weight_prep_kernel, grid, block, 0, s, p);
     return hipGetLastError();
 }
