@@ -5,6 +5,7 @@
 // LDS (double buffered, one barrier per slab) as A[k][m] and B[k][n], so that the MFMA operand reads
 // (lane -> m or n, lane/32 -> k) are unit-stride.  Operands whose memory order runs along K are transposed on
 // the way into LDS.  The im2col matrices are never materialised: loaders compute addresses from the geometry.
+#include <cstdint>
 #include "train_kernels.h"
 
 namespace hadfl {
@@ -383,6 +384,25 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     }
 }
 
+// The same sum for counts that are a multiple of 4: one thread per 4 consecutive outputs, splits added one after another
+// in ascending order with 16-byte accesses.
+__global__ __launch_bounds__(256) void splitk_reduce_vec_kernel(const float* __restrict__ partial, long long split_stride,
+                                                                int splits, float* __restrict__ out, long long out_rep,
+                                                                long long count4, const int* __restrict__ order)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const int g = blockIdx.y, rep = order[g];
+    const f4* src = reinterpret_cast<const f4*>(partial + (long long)g * split_stride * splits);
+    f4* dst = reinterpret_cast<f4*>(out + (long long)rep * out_rep);
+    const long long stride4 = split_stride / 4;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < count4; i += (long long)gridDim.x * 256) {
+        f4 acc = src[i];
+#pragma unroll 4
+        for (int k = 1; k < splits; ++k) acc = acc + src[(long long)k * stride4 + i];
+        dst[i] = acc;
+    }
+}
+
 template <int BM, int BN, int WM, int WN>
 hipError_t launch_tile(const GemmParams& p0, int n_active, hipStream_t s)
 {
@@ -422,6 +442,13 @@ hipError_t launch_splitk_reduce(const float* partial, long long split_stride, in
                                 long long count, const int* order, int n_active, hipStream_t s)
 {
     if (n_active < 1 || count < 1) return hipSuccess;
+    if (count % 4 == 0 && split_stride % 4 == 0 && out_rep % 4 == 0 && (((uintptr_t)partial | (uintptr_t)out) & 15) == 0) {
+        long long bx = (count / 4 + 255) / 256;
+        if (bx > 2048) bx = 2048;
+        hipLaunchKernelGGL(splitk_reduce_vec_kernel, dim3((unsigned)bx, (unsigned)n_active), dim3(256), 0, s, partial,
+                           split_stride, splits, out, out_rep, count / 4, order);
+        return hipGetLastError();
+    }
     long long bx = (count + 31) / 32;
     if (bx > 4096) bx = 4096;
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)bx, (unsigned)n_active), dim3(256), 0, s, partial,
