@@ -463,11 +463,12 @@ struct Runner {
             p.dy = grad(ot); p.dy_rep = e.rep_block;
             p.splits = e.splits[i];
             const int64_t mn = (int64_t)p.M * p.N;
-            if (p.splits > 1 && e.fast[i] && (p.W == 16 || p.W == 32) && p.Cin <= 128 && p.N <= 128) {
-                // Wide-image layers run the all-taps kernel: few tiles (one per 64 x 64 channel pair) and a small result,
-                // so a sub-step with few active replicas can split K further at little cost; the partial-sum buffer
-                // (sized for all replicas at the planned split count) bounds how far.
-                const int64_t tiles = (int64_t)(p.Cin / 64) * (p.N / 64);
+            if (p.splits > 1 && e.fast[i]) {
+                // The planned split count fills the chip when every replica is active.  A sub-step with fewer active
+                // replicas splits K further; the partial-sum buffer (sized for all replicas at the planned count) and
+                // K bound how far.  Wide-image layers run the all-taps kernel with one tile per 64 x 64 channel pair.
+                const bool wide = (p.W == 16 || p.W == 32) && p.Cin <= 128 && p.N <= 128;
+                const int64_t tiles = wide ? (int64_t)(p.Cin / 64) * (p.N / 64) : ((p.M + 127) / 128) * ((p.N + 127) / 128);
                 const int64_t want = (1024 + tiles * na - 1) / (tiles * na);
                 const int64_t by_buffer = e.shared_floats / ((int64_t)na * ((mn + 63) / 64 * 64));
                 const int64_t by_k = std::max<int64_t>(1, p.K / 512);
