@@ -56,7 +56,7 @@ typedef enum {
     HADFL_ENOMEM = 2,        /* host allocation failed */
     HADFL_EDEVICE = 3,       /* a HIP call failed; text in hadfl_last_error */
     HADFL_ESTATE = 4,        /* call out of order (e.g. aggregate before select) */
-    HADFL_EUNSUPPORTED = 5   /* valid request this build has no kernel for */
+    HADFL_EUNSUPPORTED = 5   /* valid request the library has no kernel for */
 } hadfl_status;
 
 typedef enum {

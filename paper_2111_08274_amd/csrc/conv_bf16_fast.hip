@@ -1,5 +1,6 @@
-// Lean bf16 kernels for the regular convolution layers of the bf16 configuration (3x3-style "same" convolutions,
-// stride 1, channel counts that are multiples of 32/64): the bulk of the network's multiply-adds.
+// bf16 kernels for the regular convolution layers of the bf16 configuration (3x3-style "same" convolutions, stride 1,
+// channel counts that are multiples of 64): the bulk of the network's multiply-adds (paper Sec. 2.1: the forward and
+// backward passes of every local step).
 //
 // The generic kernel spends ~20 vector-ALU instructions per MFMA on address arithmetic, conversions and a scalar
 // epilogue, which caps the matrix cores near 10 %.  Here everything that does not change along K is computed once:
@@ -11,8 +12,10 @@
 //     added; all offsets are 32-bit;
 //   * the MFMA operands are swapped (C^T = B^T A^T), which leaves 4 consecutive output channels in each lane, so
 //     the epilogue stores 8 bytes (bf16) or 16 bytes (fp32) per lane instead of single elements.
-// The weight gradient transposes both operands (pixels are the contraction index) while staging them: a thread
-// takes two consecutive pixels of 8 channels and writes eight 32-bit (k, k+1) pairs.
+// Kernels: conv_kernel (forward / data gradient, any image size), conv_patch_kernel (the same on 16- and 32-pixel-wide
+// images with at most 128 channels: tile and border resident in LDS), wgrad_kernel (weight gradient: operands stored
+// as they arrive and transposed by the LDS read), wgrad_taps_kernel (weight gradient on wide images: all taps from one
+// patch), weight_prep_kernel.  Each has its own comment.
 #include "train_kernels.h"
 
 namespace hadfl {
@@ -20,11 +23,9 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u2 __attribute__((ext_vector_type(2)));
 
 constexpr int kBigLds = 2 * (256 + 256) * 72 * 2;   // dynamic LDS of the 256 x 256 kernel: two buffers of both operands
 constexpr int kBigWgradLds = 2 * 64 * 2 * (256 + 32) * 2;   // 256 x 256 weight-gradient kernel: two buffers of 64 rows per operand
