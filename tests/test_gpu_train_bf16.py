@@ -213,3 +213,57 @@ def test_wide_image_layers_bf16_patch_kernel(side, batch):
     print("patch kernel bf16 rel", side, d, "loss", p.gpu.losses(), p.cpu.loss, flush=True)
     assert d <= REL
     p.close()
+
+
+@pytest.mark.timeout(400)
+def test_vgg16_workload_launch_shape_properties_and_sampled_replica():
+    """Workload 5 at full size (32 replicas, batch 128, bf16, ratios U{1..8}) in the launch configuration the benchmark
+    times.  The oracle needs about a minute per replica-step here, so one replica is compared with it -- a replica that
+    takes a single step this cycle, all of its parameters -- and the rest is checked through what holds at any size:
+    integer bookkeeping exact, selection identical to the oracle's, the aggregate equal to the fp64 mean of the
+    selected rows, every replica equal to the aggregate after the global synchronisation, the cycle bit-reproducible."""
+    import torch
+    cfg, x, y = synth.config_inputs(5, n_samples=256)
+    N = cfg["n_replicas"]
+    hc = hadfl.make_config(N, cfg["n_select"], net="vgg16", batch=cfg["batch"], n_samples=256, in_shape=cfg["in_shape"],
+                           lr=cfg["lr"], momentum=cfg["momentum"], seed=synth.SELECT_SEED, bf16=1)
+    w0 = synth.he_normal_init(hadfl.param_layout(hc))
+    steps = oracle.step_counts(cfg["ratio"])
+    k1 = int(np.flatnonzero(steps == steps.min())[0])
+    assert steps[k1] == 1
+    outs = []
+    for run in range(2):
+        ctx = hadfl.Context(hc, cfg["ratio"], w0=w0, x=x, y=y)
+        ctx.local_steps()
+        v, c = ctx.versions()
+        assert v.tolist() == steps.tolist() == c.tolist()
+        losses = ctx.losses()
+        assert np.all(np.isfinite(losses)) and losses.max() < 20
+        if run == 0:
+            fn, shape = nets.NETS["vgg16"]
+            net = oracle.Net(fn(), shape, bf16=True)
+            one = oracle.Cycle(net, 1, 1, w0, x[k1:k1 + 1].reshape(1, 256, -1), y[k1:k1 + 1], cfg["batch"], cfg["lr"],
+                               cfg["momentum"], [1], seed=synth.SELECT_SEED)
+            one.local_steps()
+            ref = one.params[0][:net.m_train]
+            got = ctx.params(k1)[:net.m_train].astype(np.float64)
+            rel = float(np.abs(got - ref).max() / np.abs(ref).max())
+            print("replica", k1, "one full-size step: rel", rel, "loss gpu", losses[k1], "oracle", one.loss[0], flush=True)
+            assert rel <= REL
+            assert abs(float(losses[k1]) - float(one.loss[0])) <= 2e-2 * max(1.0, abs(float(one.loss[0])))
+        ctx.select(0)
+        sel, flag, w = ctx.selected()
+        osel, oflag, _, _ = oracle.select(v, cfg["n_select"], synth.SELECT_SEED, 0)
+        assert sel.tolist() == osel.tolist() and flag.tolist() == oflag.tolist()
+        before = [ctx.params(int(k)) for k in sel]
+        ctx.aggregate(True)
+        agg = ctx.params(-1)
+        exact = np.mean(np.stack(before).astype(np.float64), axis=0)
+        assert np.abs(agg - exact).max() <= 9 * np.finfo(np.float32).eps * np.abs(exact).max()
+        for k in (0, 13, 31):
+            assert np.array_equal(ctx.params(k), agg)
+        outs.append(agg)
+        ctx.close()
+        del ctx
+        torch.cuda.empty_cache()
+    assert np.array_equal(outs[0], outs[1])
