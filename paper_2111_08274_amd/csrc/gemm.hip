@@ -34,10 +34,20 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int rep = p.order[blockIdx.z];
-    const int tile_m = blockIdx.x / p.tiles_n, tile_n = blockIdx.x % p.tiles_n;
+    // One-dimensional grid of 8 * chunk workgroups.  Workgroups are handed to the eight dies in turn (workgroup i runs
+    // on die i % 8, each die with its own L2); die d takes the consecutive logical items [d * chunk, (d + 1) * chunk),
+    // item = (slot, split or class, tile), so the tiles of one replica meet in one L2.
+    const unsigned chunk = gridDim.x / 8u;
+    const unsigned item = (blockIdx.x % 8u) * chunk + blockIdx.x / 8u;
+    const unsigned tiles = (unsigned)(p.tiles_m * p.tiles_n);
+    if (item >= tiles * (unsigned)p.grid_y * (unsigned)p.n_active) return;
+    const int slot = (int)(item / (tiles * (unsigned)p.grid_y));
+    const int by = (int)((item / tiles) % (unsigned)p.grid_y);
+    const int bx = (int)(item % tiles);
+    const int rep = p.order[slot];
+    const int tile_m = bx / p.tiles_n, tile_n = bx % p.tiles_n;
     const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int split = blockIdx.y;
+    const int split = by;
     const int kbeg = (MODE == kDgrad) ? 0 : split * p.kchunk;
 
     // activation-side base for this replica (the data set is indexed through the batch cursor)
@@ -52,11 +62,11 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
 
     // kDgrad: an input pixel (y, x) only receives taps with r = (y + pad) mod stride (likewise s), so the pixels are
     // split into stride*stride classes by (y mod stride, x mod stride); a class is a dense GEMM over its own tap list
-    // and no multiply-add is spent on taps that never contribute.  blockIdx.y is the class (1 class for stride 1).
+    // and no multiply-add is spent on taps that never contribute.  `by` is the class (1 class for stride 1).
     int d_ph = 0, d_pw = 0, d_r0 = 0, d_s0 = 0, d_ns = p.S, d_hc = p.H, d_wc = p.W, d_m = p.M;
     int kend = min(p.K, kbeg + p.kchunk);
     if (MODE == kDgrad) {
-        d_ph = blockIdx.y / p.stride; d_pw = blockIdx.y % p.stride;
+        d_ph = by / p.stride; d_pw = by % p.stride;
         d_hc = (p.H - d_ph + p.stride - 1) / p.stride; d_wc = (p.W - d_pw + p.stride - 1) / p.stride;
         d_r0 = (d_ph + p.pad) % p.stride; d_s0 = (d_pw + p.pad) % p.stride;
         const int nr = d_r0 < p.R ? (p.R - d_r0 + p.stride - 1) / p.stride : 0;
@@ -323,7 +333,7 @@ __global__ __launch_bounds__(64 * WM * WN) void igemm_kernel(GemmParams p)
     // ---------------- epilogue: lane holds column (lane & 31), rows 8*(v/4) + 4*(lane>>5) + v%4 ----------------
     float* obase;
     if (MODE == kWgrad && p.splits > 1)
-        obase = p.out + (long long)blockIdx.z * p.out_rep + (long long)split * p.out_split;
+        obase = p.out + (long long)slot * p.out_rep + (long long)split * p.out_split;
     else
         obase = p.out + (long long)rep * p.out_rep;
     const float* bias = (MODE == kFwd && p.has_bias) ? (wbase + (long long)p.K * p.N) : nullptr;
@@ -415,7 +425,9 @@ hipError_t launch_tile(const GemmParams& p0, int n_active, hipStream_t s)
         const int rows0 = p.B * ((p.H + p.stride - 1) / p.stride) * ((p.W + p.stride - 1) / p.stride);   // largest class
         p.tiles_m = (rows0 + BM - 1) / BM;
     }
-    const dim3 grid((unsigned)(p.tiles_m * p.tiles_n), gy, (unsigned)n_active), block(64 * WM * WN);
+    p.grid_y = (int)gy; p.n_active = n_active;
+    const long long items = (long long)p.tiles_m * p.tiles_n * gy * n_active;
+    const dim3 grid((unsigned)((items + 7) / 8 * 8)), block(64 * WM * WN);
     switch (p.mode) {
     case kFwd: hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, kFwd>), grid, block, 0, s, p); break;
     case kDgrad: hipLaunchKernelGGL((igemm_kernel<BM, BN, WM, WN, kDgrad>), grid, block, 0, s, p); break;

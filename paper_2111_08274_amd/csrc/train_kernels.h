@@ -17,6 +17,7 @@ struct GemmParams {
     int B, H, W, Cin, Ho, Wo, Cout, R, S, stride, pad;
     int M, N, K;
     int tiles_m, tiles_n;
+    int grid_y, n_active;         // set by the fp32 launcher: splits (or dgrad pixel classes) and active replicas
     int kchunk, splits;
     int hw_shift, w_shift;        // log2 of Ho*Wo and Wo (kWgrad) when powers of two, else -1
     // activation-side source: X (fwd, wgrad) or dY (dgrad)
