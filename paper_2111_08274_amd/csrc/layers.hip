@@ -314,6 +314,53 @@ __device__ __forceinline__ void stv(__bf16* p, long long i, const float (&o)[8])
     *reinterpret_cast<bf8v*>(p + i) = v;
 }
 
+// Element-wise kernels with 16-byte accesses for counts that are a multiple of VEC (same results as the scalar ones).
+template <typename T>
+__global__ __launch_bounds__(256) void add_fwd_vec_kernel(EwParams p)
+{
+    constexpr int VEC = VecOf<T>::n;
+    const int rep = p.order[blockIdx.y];
+    const T* a = tptr<T>(p.in, rep, p.in_rep);
+    const T* b = tptr<T>(p.in2, rep, p.in2_rep);
+    T* out = tptr<T>(p.out, rep, p.out_rep);
+    const long long nvec = p.count / VEC;
+    for (long long i = gtid(); i < nvec; i += gstride()) {
+        float u[VEC], w[VEC];
+        ldv(a, i * VEC, u); ldv(b, i * VEC, w);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { const float v = u[e] + w[e]; u[e] = p.relu ? fmaxf(v, 0.f) : v; }
+        stv(out, i * VEC, u);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void pass_grad_vec_kernel(EwParams p)
+{
+    constexpr int VEC = VecOf<T>::n;
+    const int rep = p.order[blockIdx.y];
+    const T* dout = tptr<T>(p.in, rep, p.in_rep);
+    T* din = tptr<T>(p.out, rep, p.out_rep);
+    const T* mask = p.mask ? tptr<T>(p.mask, rep, p.mask_rep) : nullptr;
+    const long long nvec = p.count / VEC;
+    for (long long i = gtid(); i < nvec; i += gstride()) {
+        float g[VEC];
+        ldv(dout, i * VEC, g);
+        if (mask) {
+            float mk[VEC];
+            ldv(mask, i * VEC, mk);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) if (!(mk[e] > 0.f)) g[e] = 0.f;
+        }
+        if (p.accumulate) {
+            float old[VEC];
+            ldv(din, i * VEC, old);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) g[e] = old[e] + g[e];
+        }
+        stv(din, i * VEC, g);
+    }
+}
+
 // 2 x 2 max pooling, one thread per pooled pixel and group of VEC channels (16-byte accesses); count = pooled elements.
 // Same results as the scalar kernels above, which stay for channel counts that are not a multiple of VEC.
 template <typename T>
@@ -681,11 +728,25 @@ dim3 ew_grid(long long count, int n_active)
         return hipGetLastError(); }
 HADFL_EW_LAUNCH(launch_relu_fwd, relu_fwd_kernel)
 HADFL_EW_LAUNCH(launch_relu_bwd, relu_bwd_kernel)
-HADFL_EW_LAUNCH(launch_add_fwd, add_fwd_kernel)
-HADFL_EW_LAUNCH(launch_pass_grad, pass_grad_kernel)
 HADFL_EW_LAUNCH(launch_gap_fwd, gap_fwd_kernel)
 HADFL_EW_LAUNCH(launch_gap_bwd, gap_bwd_kernel)
 #undef HADFL_EW_LAUNCH
+
+#define HADFL_EW_VEC_LAUNCH(fn, vkern, kern) \
+    hipError_t fn(const EwParams& p, int n_active, hipStream_t s) { \
+        if (n_active < 1 || p.count < 1) return hipSuccess; \
+        const int vec = p.bf16 ? 8 : 4; \
+        if (p.count % vec == 0) { \
+            if (p.bf16) hipLaunchKernelGGL(vkern<__bf16>, ew_grid(p.count / vec, n_active), dim3(256), 0, s, p); \
+            else hipLaunchKernelGGL(vkern<float>, ew_grid(p.count / vec, n_active), dim3(256), 0, s, p); \
+        } else { \
+            if (p.bf16) hipLaunchKernelGGL(kern<__bf16>, ew_grid(p.count, n_active), dim3(256), 0, s, p); \
+            else hipLaunchKernelGGL(kern<float>, ew_grid(p.count, n_active), dim3(256), 0, s, p); \
+        } \
+        return hipGetLastError(); }
+HADFL_EW_VEC_LAUNCH(launch_add_fwd, add_fwd_vec_kernel, add_fwd_kernel)
+HADFL_EW_VEC_LAUNCH(launch_pass_grad, pass_grad_vec_kernel, pass_grad_kernel)
+#undef HADFL_EW_VEC_LAUNCH
 
 hipError_t launch_maxpool_fwd(const EwParams& p, int n_active, hipStream_t s)
 {
