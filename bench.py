@@ -164,6 +164,9 @@ def main():
     ap.add_argument("--workload", type=int, default=5, choices=[1, 2, 3, 4, 5],
                     help="5 (default): the largest training workload, where the utilisation targets apply")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="launch the weight-gradient kernels on the caller's stream instead of the library's second "
+                         "stream: per-kernel durations are then those of each kernel alone on the chip")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (known traffic, to scale rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -173,6 +176,8 @@ def main():
         sys.exit(2)
     import torch
     from paper_2111_08274_amd import hadfl, synth
+    if args.no_overlap:
+        os.environ["HADFL_SIDE_STREAM"] = "0"          # read by the library when a context is created
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
@@ -255,6 +260,9 @@ def main():
         roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(dom, cfg["name"])}
     roof["avg_launch_ms"] = avg_ms
+    overlap = os.environ.get("HADFL_SIDE_STREAM", "1") != "0"
+    roof["overlap"] = ("weight-gradient launches share the chip with the input-gradient and normalisation kernels of "
+                       "the main stream; --no-overlap times each kernel alone") if overlap else "none"
     roof["share_of_kernel_time"] = kd["ms"] / total_ms
     gemm_flops = sum(v["flops"] for n, v in prof.items() if n in GEMM_KERNELS) / n_prof
     out.update(metric="local-SGD samples/s over all replicas, whole aggregation cycles", value=samples_per_cycle / t_cycle,

@@ -132,7 +132,11 @@ HADFL_API hadfl_status hadfl_init_replicas(const hadfl_config *cfg, const void *
 /* Algorithm 1, inner loop, for all replicas at once: replica k runs E_k steps, each = next batch of its shard
  * (rows [(c_k*B) mod n_samples, +B), c_k counts its steps since init), forward, softmax cross-entropy averaged
  * over the batch, backward, buf = momentum*buf + g, w = w - lr*buf (local-update equation of Sec. 2.2).
- * The version of replica k becomes the number of steps it completed in this call. */
+ * The version of replica k becomes the number of steps it completed in this call.
+ * Enqueues on the context's stream and returns without waiting.  Weight-gradient kernels run on a second stream the
+ * context owns (default priority), forked from and joined back into the context's stream inside the call, so work
+ * enqueued on that stream afterwards is ordered after the whole call.  HADFL_SIDE_STREAM=0 in the environment when the
+ * context is created keeps every launch on the context's stream. */
 HADFL_API hadfl_status hadfl_local_steps(hadfl_ctx *ctx);
 
 /* Sec. 3.3, probability-based selection: mu = third quartile of the available replicas' versions,

@@ -25,6 +25,8 @@ public:
     std::vector<int64_t> saved_off;       // per layer (BN): offset of saved mean/istd inside the replica block
     int64_t shared_off = 0;               // start of the region shared by all layers (split-K partials, BN partials)
     int64_t shared_floats = 0;
+    int64_t bn_off = 0;                   // per-chunk partial sums of the batch-norm reductions (their own region: weight
+                                          // gradients may run beside them on the side stream)
     std::vector<int> splits;              // per layer: split-K factor of the weight gradient
     std::vector<int> bn_chunks;           // per layer
     std::vector<char> grad_written;       // scratch for the backward pass
@@ -44,6 +46,12 @@ public:
     // Environment variable HADFL_TILE_HINT, read when the engine is created: 1 makes the lean kernels take their
     // 256 x 256 tiles wherever the layer shape allows, whatever the launch size (lets small problems exercise them).
     int tile_hint = 0;
+    // Weight gradients (and their split-K reduction / fused update) depend only on dY and the stored activations, not on
+    // the data-gradient chain, so they run on a second stream beside it; joined before the update kernel.
+    // HADFL_SIDE_STREAM=0 turns this off.
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    bool use_side = true;
     // Layers whose weight-gradient kernel applies the update itself (lean kernel, no split): their slices of the
     // parameter rows, ascending; the update kernel runs over the segments in between.
     std::vector<char> fused_update;       // per layer
@@ -63,7 +71,7 @@ int ilog2_exact(int v) { int s = 0; while ((1 << s) < v) ++s; return (1 << s) ==
 struct Layout {
     std::vector<int64_t> act_off, grad_off, saved_off;
     std::vector<int> splits, bn_chunks;
-    int64_t rep_block = 0, shared_floats = 0;
+    int64_t rep_block = 0, shared_floats = 0, bn_floats = 0;
     std::vector<char> fast;
     std::vector<int64_t> wf_off, wb_off;
     int64_t wbf_rep = 0;
@@ -91,7 +99,7 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
     L.saved_off.assign(plan.layers.size(), -1);
     L.splits.assign(plan.layers.size(), 1);
     L.bn_chunks.assign(plan.layers.size(), 1);
-    int64_t shared = 0;
+    int64_t shared = 0, bn_shared = 0;
     for (size_t i = 0; i < plan.layers.size(); ++i) {
         const Layer& l = plan.layers[i];
         const TensorShape a = plan.tensors[l.in0], r = plan.tensors[l.out];
@@ -100,7 +108,7 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
             const int64_t rows = B * a.h * a.w;
             int chunks = (int)std::min<int64_t>(128, std::max<int64_t>(1, rows / 128));
             L.bn_chunks[i] = chunks;
-            shared = std::max<int64_t>(shared, (int64_t)cfg.n_replicas * chunks * 2 * a.c);
+            bn_shared = std::max<int64_t>(bn_shared, (int64_t)cfg.n_replicas * chunks * 2 * a.c);
         } else if (l.type == HADFL_OP_CONV || l.type == HADFL_OP_DENSE) {
             // weight gradient: contraction over K = B*Ho*Wo rows; split it until the launch has enough workgroups
             const int64_t K = B * r.h * r.w;
@@ -115,6 +123,7 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
     }
     L.rep_block = up64(off);
     L.shared_floats = up64(shared);
+    L.bn_floats = up64(bn_shared);
     L.fast.assign(plan.layers.size(), 0); L.wf_off.assign(plan.layers.size(), -1); L.wb_off.assign(plan.layers.size(), -1);
     if (cfg.bf16) {
         int64_t woff = 0;
@@ -148,7 +157,7 @@ int64_t train_work_floats(const hadfl_config& cfg, const NetPlan& plan)
 {
     if (cfg.net == HADFL_NET_NONE) return 0;
     const Layout L = make_layout(cfg, plan);
-    return L.rep_block * cfg.n_replicas + L.shared_floats + up64(L.wbf_rep * cfg.n_replicas / 2 + 64) + up64(L.tab_ints);
+    return L.rep_block * cfg.n_replicas + L.shared_floats + L.bn_floats + up64(L.wbf_rep * cfg.n_replicas / 2 + 64) + up64(L.tab_ints);
 }
 
 hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const TrainBuffers& buf,
@@ -169,8 +178,10 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
     e->shared_off = L.rep_block * cfg.n_replicas;
     e->shared_floats = L.shared_floats;
     e->fast = L.fast; e->wf_off = L.wf_off; e->wb_off = L.wb_off; e->wbf_rep = L.wbf_rep;
-    e->wbf_off = e->shared_off + L.shared_floats;
+    e->bn_off = e->shared_off + L.shared_floats;
+    e->wbf_off = e->bn_off + L.bn_floats;
     if (const char* h = std::getenv("HADFL_TILE_HINT")) e->tile_hint = std::atoi(h);
+    if (const char* h = std::getenv("HADFL_SIDE_STREAM")) e->use_side = std::atoi(h) != 0;
     {
         e->fused_update.assign(plan.layers.size(), 0);
         int64_t pos = 0;
@@ -237,7 +248,14 @@ void train_set_steps(TrainEngine* e, const std::vector<int32_t>& steps)
 
 void train_set_lr(TrainEngine* e, float lr) { e->cfg.lr = lr; }
 
-void train_destroy(TrainEngine* e) { delete e; }
+void train_destroy(TrainEngine* e)
+{
+    if (!e) return;
+    if (e->side) { (void)hipStreamSynchronize(e->side); (void)hipStreamDestroy(e->side); }
+    if (e->ev_fork) (void)hipEventDestroy(e->ev_fork);
+    if (e->ev_join) (void)hipEventDestroy(e->ev_join);
+    delete e;
+}
 
 namespace {
 
@@ -253,7 +271,28 @@ struct Runner {
     const float* act(int t) const { return t == 0 ? e.buf.x : e.buf.work + e.act_off[t]; }
     float* actw(int t) const { return e.buf.work + e.act_off[t]; }
     float* grad(int t) const { return e.buf.work + e.grad_off[t]; }
+    hipStream_t main_stream = nullptr;
+    bool forked = false;                  // a flag, not the handle: the caller's stream may be the null stream
+    // the launches that follow go to the side stream, ordered after everything enqueued on the main stream so far
+    void fork()
+    {
+        if (!e.side || rc != hipSuccess) return;
+        rc = hipEventRecord(e.ev_fork, s);
+        if (rc == hipSuccess) rc = hipStreamWaitEvent(e.side, e.ev_fork, 0);
+        if (rc != hipSuccess) { failed = "fork"; return; }
+        main_stream = s; s = e.side; forked = true;
+    }
+    void unfork() { if (forked) { s = main_stream; forked = false; } }
+    // the main stream waits for everything enqueued on the side stream
+    void join()
+    {
+        if (!e.side || rc != hipSuccess) return;
+        rc = hipEventRecord(e.ev_join, e.side);
+        if (rc == hipSuccess) rc = hipStreamWaitEvent(s, e.ev_join, 0);
+        if (rc != hipSuccess) failed = "join";
+    }
     float* shared() const { return e.buf.work + e.shared_off; }
+    float* bn_shared() const { return e.buf.work + e.bn_off; }
     __bf16* wbf() const { return reinterpret_cast<__bf16*>(e.buf.work + e.wbf_off); }
     const int* perm(size_t i) const { return e.tab_idx[i] < 0 ? nullptr : reinterpret_cast<const int*>(e.buf.work + e.tab_off) + e.tab_idx[i]; }
     const unsigned* posmask(size_t i) const
@@ -428,7 +467,7 @@ struct Runner {
         b.rows = (int)((int64_t)e.cfg.batch * a.h * a.w); b.C = a.c;
         b.chunks = e.bn_chunks[i];
         b.chunk_rows = (b.rows + b.chunks - 1) / b.chunks;
-        b.partial = shared(); b.partial_rep = (long long)b.chunks * 2 * a.c;
+        b.partial = bn_shared(); b.partial_rep = (long long)b.chunks * 2 * a.c;
         b.order = e.buf.order; b.bf16 = e.cfg.bf16;
         return b;
     }
@@ -483,6 +522,7 @@ struct Runner {
             } else {
                 p.out = e.buf.grad + l.w_off; p.out_rep = e.plan.row_stride;
             }
+            fork();
             FirstConvParams fc;
             if (first_conv(i, fc)) {
                 fc.dy = grad(ot); fc.dy_rep = e.rep_block;
@@ -507,6 +547,7 @@ struct Runner {
             if (p.splits > 1)
                 run("splitk_reduce", 0, 4.0 * mn * (p.splits + 1), [&] { return launch_splitk_reduce(shared(), p.out_split, p.splits, e.buf.grad + l.w_off,
                                                                        e.plan.row_stride, mn, e.buf.order, na, s); });
+            unfork();
             if (need_din) {
                 GemmParams d = gemm_base(l);
                 d.mode = kDgrad;
@@ -578,6 +619,13 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
         if (rc != hipSuccess) { err = std::string("copy position tables: ") + hipGetErrorString(rc); return HADFL_EDEVICE; }
         e->tables_uploaded = true;
     }
+    if (e->use_side && !e->side) {
+        if (hipStreamCreateWithFlags(&e->side, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&e->ev_fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&e->ev_join, hipEventDisableTiming) != hipSuccess) {
+            err = "side stream"; return HADFL_EDEVICE;
+        }
+    }
     const int T = (int)e->plan.tensors.size();
     for (int step = 0; step < e->e_max && r.rc == hipSuccess; ++step) {
         r.na = e->n_active[step];
@@ -592,6 +640,7 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
         e->grad_written.assign(T, 0);
         e->grad_written[T - 1] = 1;
         for (size_t i = e->plan.layers.size(); i-- > 0;) r.backward_layer(i);
+        r.join();
         SgdParams sp{};
         sp.w = e->buf.replicas; sp.g = e->buf.grad; sp.buf = e->buf.mom; sp.row_stride = e->plan.row_stride;
         sp.lr = e->cfg.lr; sp.momentum = e->cfg.momentum;
