@@ -31,8 +31,8 @@ TRAFFIC = {
     # all weight-gradient launches of a cycle, averaged (the figure includes the fused update's parameter traffic)
     ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_first_bf16.hip"),
-                                       "5e61d2583b1ed54188fd84962be86cc58814a268ec553e83258523bbadb06a49",
-                                       567974220.0),
+                                       "b2a662ed35d34e415ec255b3d66bb5996e6a4f86e617a55ff7279fce2c88a991",
+                                       568237721.0),
 }
 
 

@@ -318,31 +318,45 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
 
     const int taps = p.R * p.S;
     const int off0 = 1 - p.pad;                               // patch border is one pixel: tap (r, s) reads patch pixel + (r + off0, s + off0)
-    u4 rb[NQB];
-    auto load_w = [&](int tap, int cs) {
-        const unsigned kb = (unsigned)(tap * p.C + cs) * 2u;
+    // One step = one tap of one 64-channel slice: 64 contraction indices, too little matrix work to cover the latency of
+    // its own weight load.  The weights of step i are therefore requested D steps ahead, into a ring of register sets.
+    constexpr int D = BN <= 64 ? 4 : 2;
+    const int steps = (p.C / 64) * taps;
+    u4 rb[D][NQB];
+    auto load_w = [&](int step, u4 (&dst)[NQB]) {
+        const int sl = step / taps, tap = step - sl * taps;
+        const unsigned kb = (unsigned)(tap * p.C + sl * 64) * 2u;
 #pragma unroll
-        for (int q = 0; q < NQB; ++q) rb[q] = ldg16(wbase, boff[q] + kb);
+        for (int q = 0; q < NQB; ++q) dst[q] = ldg16(wbase, boff[q] + kb);
     };
-    for (int cs = 0; cs < p.C; cs += 64) {
-        u4 rp[NQP];
 #pragma unroll
-        for (int q = 0; q < NQP; ++q) {
-            u4 v = {0u, 0u, 0u, 0u};
-            if (poff[q] >= 0) v = ldg16(abase, (unsigned)(poff[q] + cs * 2));
-            rp[q] = v;
-        }
-        load_w(0, cs);
-        __syncthreads();                                      // every wave is done with the previous slice
+    for (int d = 0; d < D; ++d)
+        if (d < steps) load_w(d, rb[d]);
+    for (int step0 = 0; step0 < steps; step0 += D) {
 #pragma unroll
-        for (int q = 0; q < NQP; ++q)
-            if (tid + q * 256 < PR * 8) *reinterpret_cast<u4*>(sP + pst[q]) = rp[q];
-        for (int tap = 0; tap < taps; ++tap) {
-            if (tap > 0) __syncthreads();                     // every wave is done reading the previous tap's weights
+        for (int d = 0; d < D; ++d) {
+            const int step = step0 + d;
+            if (step >= steps) break;
+            const int sl = step / taps, tap = step - sl * taps;
+            if (tap == 0) {
+                u4 rp[NQP];
 #pragma unroll
-            for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sB + sb_st[q]) = rb[q];
+                for (int q = 0; q < NQP; ++q) {
+                    u4 v = {0u, 0u, 0u, 0u};
+                    if (poff[q] >= 0) v = ldg16(abase, (unsigned)(poff[q] + sl * 128));
+                    rp[q] = v;
+                }
+                __syncthreads();                              // every wave is done with the previous slice
+#pragma unroll
+                for (int q = 0; q < NQP; ++q)
+                    if (tid + q * 256 < PR * 8) *reinterpret_cast<u4*>(sP + pst[q]) = rp[q];
+            } else {
+                __syncthreads();                              // every wave is done reading the previous tap's weights
+            }
+#pragma unroll
+            for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sB + sb_st[q]) = rb[d][q];
             __syncthreads();
-            if (tap + 1 < taps) load_w(tap + 1, cs);
+            if (step + D < steps) load_w(step + D, rb[d]);
             const int r = tap / p.S, s2 = tap - r * p.S;
             const unsigned toff = (unsigned)(((r + off0) * PW + (s2 + off0)) * LDQ) * 2u;
 #pragma unroll

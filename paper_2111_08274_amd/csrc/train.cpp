@@ -55,6 +55,7 @@ public:
     // Layers whose weight-gradient kernel applies the update itself (lean kernel, no split): their slices of the
     // parameter rows, ascending; the update kernel runs over the segments in between.
     std::vector<char> fused_update;       // per layer
+    std::vector<char> prepped;            // per layer: bf16 copies for the coming sub-step are already written
     std::vector<std::pair<int64_t, int64_t>> update_segments;   // [first, first + count) floats
     // Position tables of the regular convolution layers (see FastConvParams::perm): per layer HW sorted positions
     // followed by HW tap masks, all layers back to back in `tables`; copied to `work` at tab_off by the first run.
@@ -302,18 +303,40 @@ struct Runner {
     }
 
     // bf16 configuration: refresh the bf16 weight matrices of the regular convolution layers from the fp32 master
+    // bf16 copies of layer i's filters (forward layout and flipped/transposed for the data gradient) for the first n
+    // replicas in step order
+    void prep_layer(size_t i, int n)
+    {
+        const int keep_na = na, keep_layer = cur_layer;
+        na = n; cur_layer = (int)i;
+        const Layer& l = e.plan.layers[i];
+        WeightPrepParams w{};
+        w.w = e.buf.replicas + l.w_off; w.w_rep = e.plan.row_stride;
+        w.wf = wbf() + e.wf_off[i]; w.wb = wbf() + e.wb_off[i]; w.wbf_rep = e.wbf_rep;
+        w.C = e.plan.tensors[l.in0].c; w.N = l.cout; w.taps = l.k * l.k; w.order = e.buf.order;
+        run("weight_prep", 0, 8.0 * l.w_count, [&] { return launch_weight_prep(w, na, s); });
+        na = keep_na; cur_layer = keep_layer;
+    }
     void prepare_weights()
     {
         for (size_t i = 0; i < e.plan.layers.size(); ++i) {
             if (!e.fast[i]) continue;
-            cur_layer = (int)i;
-            const Layer& l = e.plan.layers[i];
-            WeightPrepParams w{};
-            w.w = e.buf.replicas + l.w_off; w.w_rep = e.plan.row_stride;
-            w.wf = wbf() + e.wf_off[i]; w.wb = wbf() + e.wb_off[i]; w.wbf_rep = e.wbf_rep;
-            w.C = e.plan.tensors[l.in0].c; w.N = l.cout; w.taps = l.k * l.k; w.order = e.buf.order;
-            run("weight_prep", 0, 8.0 * l.w_count, [&] { return launch_weight_prep(w, na, s); });
+            if (e.prepped[i]) { e.prepped[i] = 0; continue; }      // written during the previous sub-step's backward pass
+            prep_layer(i, na);
         }
+    }
+    // A layer whose update is fused into its weight-gradient kernel has its final weights of this sub-step as soon as
+    // that kernel ends, so the copies for the next sub-step are written right behind it on the same stream, off the
+    // forward pass's critical path.  Not before this sub-step's data gradient of the layer has read the old copy:
+    // the copy of layer i is therefore issued after the next fork, which follows that data gradient on the main stream.
+    int na_next = 0;
+    int pending_prep = -1;
+    void flush_pending_prep()
+    {
+        if (pending_prep < 0) return;
+        prep_layer((size_t)pending_prep, na_next);
+        e.prepped[pending_prep] = 1;
+        pending_prep = -1;
     }
 
     // flops / bytes: algorithmic work of the launch for all active replicas (reported by the profiler)
@@ -523,6 +546,7 @@ struct Runner {
                 p.out = e.buf.grad + l.w_off; p.out_rep = e.plan.row_stride;
             }
             fork();
+            flush_pending_prep();
             FirstConvParams fc;
             if (first_conv(i, fc)) {
                 fc.dy = grad(ot); fc.dy_rep = e.rep_block;
@@ -542,6 +566,7 @@ struct Runner {
                     f.lr = e.cfg.lr; f.momentum = e.cfg.momentum;
                 }
                 run("conv_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return launch_wgrad_fast(f, na, s); });
+                if (e.fused_update[i] && na_next > 0) pending_prep = (int)i;
             } else
             run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return gemm(p); });
             if (p.splits > 1)
@@ -627,6 +652,7 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
         }
     }
     const int T = (int)e->plan.tensors.size();
+    e->prepped.assign(e->plan.layers.size(), 0);       // the weights may have changed since the last call (aggregation)
     for (int step = 0; step < e->e_max && r.rc == hipSuccess; ++step) {
         r.na = e->n_active[step];
         if (e->cfg.bf16) r.prepare_weights();
@@ -639,7 +665,9 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
         r.run("softmax_ce", 0, r.asz() * 8.0 * e->cfg.batch * e->cfg.n_classes, [&] { return launch_softmax_ce(lp, r.na, s); });
         e->grad_written.assign(T, 0);
         e->grad_written[T - 1] = 1;
+        r.na_next = step + 1 < e->e_max ? e->n_active[step + 1] : 0;
         for (size_t i = e->plan.layers.size(); i-- > 0;) r.backward_layer(i);
+        if (r.pending_prep >= 0) { r.fork(); r.flush_pending_prep(); r.unfork(); }
         r.join();
         SgdParams sp{};
         sp.w = e->buf.replicas; sp.g = e->buf.grad; sp.buf = e->buf.mom; sp.row_stride = e->plan.row_stride;
