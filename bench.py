@@ -31,8 +31,8 @@ TRAFFIC = {
     # all weight-gradient launches of a cycle, averaged (the figure includes the fused update's parameter traffic)
     ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_first_bf16.hip"),
-                                       "b2a662ed35d34e415ec255b3d66bb5996e6a4f86e617a55ff7279fce2c88a991",
-                                       568237721.0),
+                                       "46897f2d1e97ab112cc6c60b987fd8f28689f19968c88708d07258bfd1be4459",
+                                       569265620.0),
 }
 
 

@@ -256,18 +256,23 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
 // rows), loads them ONCE per 64-channel slice together with their one-pixel border (zeros outside the image) into
 // LDS, and serves all R*S taps from that patch by shifting the row it reads; only the weights still stream per tap.
 // IW = image width; 3x3-style filters with pad = (R-1)/2 <= 1.
+// With 16-pixel rows the 32 lanes of an operand read span two patch rows; the read only runs at full rate when the
+// second row starts a multiple of 256 bytes after the first (measured: half rate otherwise), so patch rows are padded
+// to kPatchRowBytes<16>.
+template <int IW> constexpr int kPatchRowBytes = IW == 16 ? ((IW + 2) * 144 + 255) / 256 * 256 : (IW + 2) * 144;
 template <int IW, int BN, int WGM, int EPI>
 __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
 {
     constexpr int BMT = 256, LDQ = 72, PW = IW + 2, TR = BMT / IW, PR = (TR + 2) * PW;   // patch: (TR + 2) x (IW + 2) pixels
+    constexpr int RPB = kPatchRowBytes<IW>;                   // bytes per patch row
     constexpr int WGN = 4 / WGM;                              // wave grid WGM x WGN, wave tile (256 / WGM) x (BN / WGN)
     constexpr int TM = 256 / WGM / 32, TN = BN / WGN / 32;
     static_assert(TM >= 1 && TN >= 1, "");
     constexpr int NQB = BN * 8 / 256;
     constexpr int NQP = (PR * 8 + 255) / 256;                 // patch slots per thread
-    constexpr unsigned P_BYTES = PR * LDQ * 2;
+    constexpr unsigned P_BYTES = (TR + 2) * RPB;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    char* const sP = smem;                                    // [PR][LDQ] activations with border
+    char* const sP = smem;                                    // [TR + 2][RPB]: rows of PW pixels x LDQ, activations with border
     char* const sB = smem + P_BYTES;                          // [BN][LDQ] weights of one tap and channel slice
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -291,7 +296,7 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
         const int yy = y0 - 1 + py, xx = px - 1;
         const bool ok = pr < PR && yy >= 0 && yy < p.H && xx >= 0 && xx < IW;
         poff[q] = ok ? (((img * p.H + yy) * IW + xx) * p.C + kq * 8) * 2 : -1;
-        pst[q] = (unsigned)(pr * LDQ + kq * 8) * 2u;
+        pst[q] = (unsigned)(py * RPB + (px * LDQ + kq * 8) * 2);
     }
     unsigned boff[NQB], sb_st[NQB];
 #pragma unroll
@@ -304,7 +309,7 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int pm = wm * (256 / WGM) + i * 32 + (lane & 31);
-        a_rd[i] = (unsigned)(((pm / IW) * PW + (pm % IW)) * LDQ + (lane >> 5) * 8) * 2u;
+        a_rd[i] = (unsigned)((pm / IW) * RPB + ((pm % IW) * LDQ + (lane >> 5) * 8) * 2);
     }
     const unsigned b_rd = (unsigned)((wn * (BN / WGN) + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
 
@@ -358,7 +363,7 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
             __syncthreads();
             if (step + D < steps) load_w(step + D, rb[d]);
             const int r = tap / p.S, s2 = tap - r * p.S;
-            const unsigned toff = (unsigned)(((r + off0) * PW + (s2 + off0)) * LDQ) * 2u;
+            const unsigned toff = (unsigned)((r + off0) * RPB + (s2 + off0) * LDQ * 2);
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {
                 bf16x8 a[TM], b[TN];
@@ -817,7 +822,7 @@ hipError_t launch_conv_fast(const FastConvParams& p0, int epi, int n_active, hip
         const int bn = (p.N % 128 == 0) ? 128 : 64;
         const dim3 grid(die_grid((long long)(p.M / 256) * (p.N / bn) * n_active)), block(256);
 #define HADFL_PATCH(IW_, BN_, WGM_) do { \
-            constexpr size_t lds = (size_t)((256 / IW_ + 2) * (IW_ + 2) + BN_) * 72 * 2; \
+            constexpr size_t lds = (size_t)(256 / IW_ + 2) * kPatchRowBytes<IW_> + (size_t)BN_ * 72 * 2; \
             static const bool ok = hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, WGM_, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess && \
                                    hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, WGM_, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess; \
             if (!ok) return hipErrorInvalidValue; \
@@ -842,8 +847,10 @@ hipError_t launch_conv_fast(const FastConvParams& p0, int epi, int n_active, hip
         }
     }
     const int bn = (p.N % 128 == 0) ? 128 : 64;
-    // tall tiles halve the weight traffic and double the MFMA work per barrier; use them when they still fill the chip
-    const bool tall = (long long)(p.M / 256) * (p.N / bn) * n_active >= 512;
+    // tall tiles halve the weight traffic and double the MFMA work per barrier; use them when they still fill the chip.
+    // Not on layers that could have had 256 x 256 tiles: where those do not fill their last round, 128 x 128 tiles
+    // measured faster than 256 x 128 at every count of active replicas.
+    const bool tall = p.N % 256 != 0 && (long long)(p.M / 256) * (p.N / bn) * n_active >= 512;
     if (bn == 128) {
         if (tall) launch_conv_t<256, 128, 2, 2, 1>(p, epi, n_active, s);
         else launch_conv_t<128, 128, 2, 2, 1>(p, epi, n_active, s);
@@ -876,12 +883,16 @@ hipError_t launch_wgrad_fast(const FastWgradParams& p0, int n_active, hipStream_
     }
     // 256-row tiles (and 256 columns where the layer has them) when the launch still fills the chip
     static const BigTileInfo big = query_big_tile();
+    // Only for long contractions: with few pixels per weight (the deep layers) the kernel's time is in the epilogue
+    // (gradient store or fused update), which the smaller tiles overlap with other workgroups' K loops -- measured 5-30 %
+    // faster there at every count of active replicas.
     int bmt = 128;
-    if (p.N % 256 == 0) {
+    const bool long_k = p.tile_hint == 1 || (p.splits > 1 ? p.kchunk : p.K) >= 4096;
+    if (long_k && p.N % 256 == 0) {
         const long long blocks = (long long)((p.M + 255) / 256) * (p.N / 256) * p.splits * n_active;
         const long long rounds = (blocks + big.n_cu - 1) / big.n_cu;
         if (p.tile_hint == 1 || blocks * 5 >= rounds * big.n_cu * 4) bmt = 256;
-    } else if (p.N % 128 == 0) {
+    } else if (long_k && p.N % 128 == 0) {
         if (p.tile_hint == 1 || (long long)((p.M + 255) / 256) * (p.N / 128) * p.splits * n_active >= 2LL * big.n_cu) bmt = 256;
     }
     const int bkt = bmt == 256 && p.N % 256 == 0 ? 64 : 32;
