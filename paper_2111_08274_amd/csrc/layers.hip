@@ -624,6 +624,195 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_vec_kernel(BnParams p)
     }
 }
 
+// ------------------------------------------------------------------------------------------------------
+// Batch norm whose (ReLU'd) output feeds a 2x2/stride-2 max-pool only: the pool is folded into the BN kernels.
+// A thread walks 2x2 windows instead of single rows.  Forward: it normalises the four pixels, stores them and their
+// maximum (one pass less over the full-resolution tensor than a separate pool).  Backward: the gradient of a pixel
+// is the pooled gradient where the pixel is the window's first maximum in scan order and is positive, else zero; it
+// is formed on the fly from the stored output and the pooled gradient, so the full-resolution gradient tensor is
+// neither written nor read (two passes less).  Window w of chunk c: [c * chunk_windows, (c + 1) * chunk_windows).
+// ------------------------------------------------------------------------------------------------------
+struct PoolWin { long long q[4]; long long o; };
+__device__ __forceinline__ PoolWin pool_window(const BnParams& p, int w, int c)
+{
+    const int Wo = p.W / 2, Ho = p.H / 2;
+    const int xo = w % Wo; int t = w / Wo;
+    const int yo = t % Ho, b = t / Ho;
+    PoolWin r;
+    r.q[0] = (((long long)b * p.H + 2 * yo) * p.W + 2 * xo) * p.C + c;
+    r.q[1] = r.q[0] + p.C; r.q[2] = r.q[0] + (long long)p.W * p.C; r.q[3] = r.q[2] + p.C;
+    r.o = (long long)w * p.C + c;
+    return r;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bn_apply_fwd_pool_vec_kernel(BnParams p)
+{
+    constexpr int VEC = VecOf<T>::n;
+    const int gi = blockIdx.y, rep = p.order[gi];
+    const BnGeo g = bn_geo(p, VEC);
+    if (!g.live) return;
+    const T* x = tptr<T>(p.x, rep, p.x_rep);
+    T* y = tptr<T>(p.y, rep, p.y_rep);
+    T* po = tptr<T>(p.pool_out, rep, p.pool_out_rep);
+    const float* row = p.params + rep * p.row_stride;
+    float sc[VEC], sh[VEC];
+    const float* sv = p.saved + rep * p.saved_rep;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const int c = g.c + e;
+        const float mean = sv[c], istd = sv[p.C + c];
+        const float gamma = row[p.w_off + c], beta = row[p.w_off + p.C + c];
+        sc[e] = gamma * istd; sh[e] = beta - mean * gamma * istd;
+    }
+    const int windows = p.rows / 4, cw = (windows + p.chunks - 1) / p.chunks;
+    const int w0 = g.chunk * cw, w1 = min(windows, w0 + cw);
+#pragma unroll 2
+    for (int w = w0 + g.rl; w < w1; w += g.rl_count) {
+        const PoolWin pw = pool_window(p, w, g.c);
+        float v[4][VEC], m[VEC];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ldv(x, pw.q[j], v[j]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) { const float t = v[j][e] * sc[e] + sh[e]; v[j][e] = p.relu ? fmaxf(t, 0.f) : t; }
+            stv(y, pw.q[j], v[j]);
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) m[e] = fmaxf(fmaxf(v[0][e], v[1][e]), fmaxf(v[2][e], v[3][e]));
+        stv(po, pw.o, m);
+    }
+}
+
+// which of the window's four pixels receives the pooled gradient (per channel), or -1
+template <int VEC>
+__device__ __forceinline__ void pool_argmax(const float (&yv)[4][VEC], bool relu, int (&arg)[VEC])
+{
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        float m = yv[0][e]; arg[e] = 0;
+#pragma unroll
+        for (int j = 1; j < 4; ++j) if (yv[j][e] > m) { m = yv[j][e]; arg[e] = j; }     // first maximum in scan order
+        if (relu && !(m > 0.f)) arg[e] = -1;                                             // the fused ReLU passes nothing there
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bn_sums_pool_vec_kernel(BnParams p)
+{
+    constexpr int VEC = VecOf<T>::n;
+    __shared__ float red[256][2 * VEC + 1];
+    const int gi = blockIdx.y, rep = p.order[gi];
+    const BnGeo g = bn_geo(p, VEC);
+    const T* x = tptr<T>(p.x, rep, p.x_rep);
+    const T* yo = tptr<T>(p.pool_y, rep, p.pool_y_rep);
+    const T* pg = tptr<T>(p.pool_g, rep, p.pool_g_rep);
+    float s0[VEC], s1[VEC], a[VEC], b[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { s0[e] = 0.f; s1[e] = 0.f; a[e] = 0.f; b[e] = 1.f; }
+    if (g.live) {
+        const float* sv = p.saved + rep * p.saved_rep;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { a[e] = sv[g.c + e]; b[e] = sv[p.C + g.c + e]; }
+        const int windows = p.rows / 4, cw = (windows + p.chunks - 1) / p.chunks;
+        const int w0 = g.chunk * cw, w1 = min(windows, w0 + cw);
+#pragma unroll 2
+        for (int w = w0 + g.rl; w < w1; w += g.rl_count) {
+            const PoolWin pw = pool_window(p, w, g.c);
+            float yv[4][VEC], xv[4][VEC], gv[VEC];
+            int arg[VEC];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { ldv(yo, pw.q[j], yv[j]); ldv(x, pw.q[j], xv[j]); }
+            ldv(pg, pw.o, gv);
+            pool_argmax<VEC>(yv, p.relu != 0, arg);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                float xs = xv[0][e];
+#pragma unroll
+                for (int j = 1; j < 4; ++j) xs = arg[e] == j ? xv[j][e] : xs;
+                const float d = arg[e] >= 0 ? gv[e] : 0.f;
+                s0[e] += d; s1[e] += d * ((xs - a[e]) * b[e]);
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { red[threadIdx.x][e] = s0[e]; red[threadIdx.x][VEC + e] = s1[e]; }
+    __syncthreads();
+    for (int w = g.rl_count / 2; w > 0; w >>= 1) {           // fixed-order tree over the row lanes
+        if (g.rl < w) {
+#pragma unroll
+            for (int e = 0; e < 2 * VEC; ++e) red[threadIdx.x][e] += red[threadIdx.x + w * g.cvb][e];
+        }
+        __syncthreads();
+    }
+    if (g.rl == 0 && g.live) {
+        float* part = p.partial + gi * p.partial_rep + (long long)g.chunk * 2 * p.C;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { part[g.c + e] = red[threadIdx.x][e]; part[p.C + g.c + e] = red[threadIdx.x][VEC + e]; }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bn_apply_bwd_pool_vec_kernel(BnParams p)
+{
+    constexpr int VEC = VecOf<T>::n;
+    const int gi = blockIdx.y, rep = p.order[gi];
+    const BnGeo g = bn_geo(p, VEC);
+    if (!g.live) return;
+    const T* x = tptr<T>(p.x, rep, p.x_rep);
+    const T* yo = tptr<T>(p.pool_y, rep, p.pool_y_rep);
+    const T* pg = tptr<T>(p.pool_g, rep, p.pool_g_rep);
+    T* dx = tptr<T>(p.y, rep, p.y_rep);
+    const T* mask = p.mask ? tptr<T>(p.mask, rep, p.mask_rep) : nullptr;
+    const float* part = p.partial + gi * p.partial_rep;
+    const float* sv = p.saved + rep * p.saved_rep;
+    const float inv_n = 1.0f / (float)p.rows;
+    float mean[VEC], istd[VEC], k1[VEC], kb[VEC], kg[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const int c = g.c + e;
+        const float db = part[c], dg = part[p.C + c];       // totals left in chunk 0 by bn_finalize_kernel<1>
+        mean[e] = sv[c]; istd[e] = sv[p.C + c];
+        k1[e] = p.params[rep * p.row_stride + p.w_off + c] * istd[e];
+        kb[e] = db * inv_n; kg[e] = dg * inv_n;
+    }
+    const int windows = p.rows / 4, cw = (windows + p.chunks - 1) / p.chunks;
+    const int w0 = g.chunk * cw, w1 = min(windows, w0 + cw);
+#pragma unroll 2
+    for (int w = w0 + g.rl; w < w1; w += g.rl_count) {
+        const PoolWin pw = pool_window(p, w, g.c);
+        float yv[4][VEC], xv[4][VEC], gv[VEC];
+        int arg[VEC];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { ldv(yo, pw.q[j], yv[j]); ldv(x, pw.q[j], xv[j]); }
+        ldv(pg, pw.o, gv);
+        pool_argmax<VEC>(yv, p.relu != 0, arg);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float o[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const float d = arg[e] == j ? gv[e] : 0.f;
+                o[e] = k1[e] * (d - kb[e] - ((xv[j][e] - mean[e]) * istd[e]) * kg[e]);
+            }
+            if (mask) {
+                float mk[VEC];
+                ldv(mask, pw.q[j], mk);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) if (!(mk[e] > 0.f)) o[e] = 0.f;
+            }
+            if (p.accumulate) {
+                float old[VEC];
+                ldv(dx, pw.q[j], old);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) o[e] += old[e];
+            }
+            stv(dx, pw.q[j], o);
+        }
+    }
+}
+
 // One workgroup per replica, one thread per sample: softmax, loss, d(loss)/d(logits); loss summed by an LDS tree.
 template <typename T>
 __global__ __launch_bounds__(1024) void softmax_ce_kernel(LossParams p)
@@ -799,17 +988,21 @@ hipError_t launch_bn_fwd(const BnParams& p0, int n_active, hipStream_t s)
         p.cvb = bn_cvb(p.C, vec);
         const int cgroups = (p.C / vec + p.cvb - 1) / p.cvb;
         const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 31) / 32), (unsigned)n_active);
+        if (p.pool && (p.H % 2 != 0 || p.W % 2 != 0 || p.rows % 4 != 0 || !p.pool_out)) return hipErrorInvalidValue;
         if (p.bf16) {
             hipLaunchKernelGGL((bn_sums_vec_kernel<0, __bf16>), grid, block, 0, s, p);
             hipLaunchKernelGGL((bn_finalize_kernel<0, __bf16>), fgrid, block, 0, s, p);
-            hipLaunchKernelGGL(bn_apply_fwd_vec_kernel<__bf16>, grid, block, 0, s, p);
+            if (p.pool) hipLaunchKernelGGL(bn_apply_fwd_pool_vec_kernel<__bf16>, grid, block, 0, s, p);
+            else hipLaunchKernelGGL(bn_apply_fwd_vec_kernel<__bf16>, grid, block, 0, s, p);
         } else {
             hipLaunchKernelGGL((bn_sums_vec_kernel<0, float>), grid, block, 0, s, p);
             hipLaunchKernelGGL((bn_finalize_kernel<0, float>), fgrid, block, 0, s, p);
-            hipLaunchKernelGGL(bn_apply_fwd_vec_kernel<float>, grid, block, 0, s, p);
+            if (p.pool) hipLaunchKernelGGL(bn_apply_fwd_pool_vec_kernel<float>, grid, block, 0, s, p);
+            else hipLaunchKernelGGL(bn_apply_fwd_vec_kernel<float>, grid, block, 0, s, p);
         }
         return hipGetLastError();
     }
+    if (p.pool) return hipErrorInvalidValue;                 // the caller folds a pool only where the vector kernels apply
     const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active);
     if (p.bf16) {
         hipLaunchKernelGGL((bn_reduce_kernel<0, __bf16>), grid, block, 0, s, p);
@@ -833,17 +1026,23 @@ hipError_t launch_bn_bwd(const BnParams& p0, int n_active, hipStream_t s)
         p.cvb = bn_cvb(p.C, vec);
         const int cgroups = (p.C / vec + p.cvb - 1) / p.cvb;
         const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 31) / 32), (unsigned)n_active);
+        if (p.pool && (p.H % 2 != 0 || p.W % 2 != 0 || p.rows % 4 != 0 || !p.pool_y || !p.pool_g)) return hipErrorInvalidValue;
         if (p.bf16) {
-            hipLaunchKernelGGL((bn_sums_vec_kernel<1, __bf16>), grid, block, 0, s, p);
+            if (p.pool) hipLaunchKernelGGL(bn_sums_pool_vec_kernel<__bf16>, grid, block, 0, s, p);
+            else hipLaunchKernelGGL((bn_sums_vec_kernel<1, __bf16>), grid, block, 0, s, p);
             hipLaunchKernelGGL((bn_finalize_kernel<1, __bf16>), fgrid, block, 0, s, p);
-            hipLaunchKernelGGL(bn_apply_bwd_vec_kernel<__bf16>, grid, block, 0, s, p);
+            if (p.pool) hipLaunchKernelGGL(bn_apply_bwd_pool_vec_kernel<__bf16>, grid, block, 0, s, p);
+            else hipLaunchKernelGGL(bn_apply_bwd_vec_kernel<__bf16>, grid, block, 0, s, p);
         } else {
-            hipLaunchKernelGGL((bn_sums_vec_kernel<1, float>), grid, block, 0, s, p);
+            if (p.pool) hipLaunchKernelGGL(bn_sums_pool_vec_kernel<float>, grid, block, 0, s, p);
+            else hipLaunchKernelGGL((bn_sums_vec_kernel<1, float>), grid, block, 0, s, p);
             hipLaunchKernelGGL((bn_finalize_kernel<1, float>), fgrid, block, 0, s, p);
-            hipLaunchKernelGGL(bn_apply_bwd_vec_kernel<float>, grid, block, 0, s, p);
+            if (p.pool) hipLaunchKernelGGL(bn_apply_bwd_pool_vec_kernel<float>, grid, block, 0, s, p);
+            else hipLaunchKernelGGL(bn_apply_bwd_vec_kernel<float>, grid, block, 0, s, p);
         }
         return hipGetLastError();
     }
+    if (p.pool) return hipErrorInvalidValue;
     const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active);
     if (p.bf16) {
         hipLaunchKernelGGL((bn_reduce_kernel<2, __bf16>), grid, block, 0, s, p);

@@ -38,6 +38,10 @@ public:
     std::vector<char> skip;               // per layer: fused away
     std::vector<char> fused_relu;         // per layer: applies max(., 0) in its store
     std::vector<char> masked;             // per tensor: gradient writers must apply the (value > 0) mask
+    // Pool fusion: a 2x2 max-pool that is the only consumer of a batch-norm layer's (ReLU'd) output is folded into the
+    // BN kernels: forward writes the pooled tensor as well, backward forms the full-resolution gradient on the fly from
+    // the pooled gradient.  The pool layer itself issues nothing.
+    std::vector<int> pool_of;             // per layer: index of the folded pool layer, or -1
     // bf16 configuration: regular convolution layers keep two bf16 weight matrices (forward / data-gradient order)
     std::vector<char> fast;               // per layer: the lean bf16 kernels apply
     std::vector<int64_t> wf_off, wb_off;  // per layer: offsets (bf16 elements) inside one replica's bf16 weight block
@@ -232,6 +236,19 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
             const int pt = plan.layers[i].type;
             if (pt != HADFL_OP_CONV && pt != HADFL_OP_DENSE && pt != HADFL_OP_BN && pt != HADFL_OP_ADD) continue;
             e->out_tensor[i] = r.out; e->fused_relu[i] = 1; e->skip[j] = 1; e->masked[r.out] = 1;
+        }
+        e->pool_of.assign(nl, -1);
+        const int vec = cfg.bf16 ? 8 : 4;
+        for (int j = 0; j < nl; ++j) {
+            const Layer& q = plan.layers[j];
+            if (q.type != HADFL_OP_MAXPOOL || q.in0 < 1 || consumers[q.in0] != 1) continue;
+            int i = -1;                                    // the BN layer that writes the pool's input
+            for (int k = 0; k < nl; ++k)
+                if (!e->skip[k] && e->out_tensor[k] == q.in0 && plan.layers[k].type == HADFL_OP_BN) i = k;
+            if (i < 0) continue;
+            const TensorShape t = plan.tensors[q.in0];
+            if (t.c % vec != 0 || t.h % 2 != 0 || t.w % 2 != 0) continue;
+            e->pool_of[i] = j; e->skip[j] = 1;
         }
     }
     *out = e;
@@ -454,6 +471,10 @@ struct Runner {
         case HADFL_OP_BN: {
             BnParams b = bn_params(i);
             b.y = actw(ot); b.relu = e.fused_relu[i];
+            if (e.pool_of[i] >= 0) {
+                b.pool = 1; b.H = a.h; b.W = a.w;
+                b.pool_out = actw(e.plan.layers[e.pool_of[i]].out); b.pool_out_rep = e.rep_block;
+            }
             run("bn_fwd", 0, asz() * (8.0 * B * a.numel()), [&] { return launch_bn_fwd(b, na, s); });
             break; }
         }
@@ -625,6 +646,11 @@ struct Runner {
             b.y = grad(l.in0); b.y_rep = e.rep_block;
             b.accumulate = acc0;
             b.mask = mask0; b.mask_rep = e.rep_block;
+            if (e.pool_of[i] >= 0) {
+                b.pool = 1; b.H = a.h; b.W = a.w; b.relu = e.fused_relu[i];
+                b.pool_y = act(ot); b.pool_y_rep = e.rep_block;
+                b.pool_g = grad(e.plan.layers[e.pool_of[i]].out); b.pool_g_rep = e.rep_block;
+            }
             run("bn_bwd", 0, asz() * (12.0 * B * a.numel()), [&] { return launch_bn_bwd(b, na, s); });
             break; }
         }

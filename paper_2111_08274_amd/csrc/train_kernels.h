@@ -148,6 +148,12 @@ struct BnParams {
     const float* mask; long long mask_rep; // backward: zero dx where mask <= 0
     int bf16;
     const int* order;
+    // a 2x2 / stride-2 max-pool folded into the layer (vector kernels only; H, W even): forward also writes the pooled
+    // output; backward takes the gradient of the pooled output and the stored forward output instead of dy
+    int pool, H, W;
+    float* pool_out; long long pool_out_rep;
+    const float* pool_y; long long pool_y_rep;
+    const float* pool_g; long long pool_g_rep;
 };
 hipError_t launch_bn_fwd(const BnParams& p, int n_active, hipStream_t s);
 hipError_t launch_bn_bwd(const BnParams& p, int n_active, hipStream_t s);

@@ -37,6 +37,9 @@ def _layer_cases():
     c["maxpool"] = (b.array(), (8, 12, 3), 6)
     b = nets._Builder(); b.dense(b.relu(b.bn(b.conv(0, 16, bias=False))), 5)
     c["bn"] = (b.array(), (8, 8, 3), 16)
+    # BN -> ReLU -> pool and BN -> pool (no ReLU): the pool is folded into the BN kernels; ragged chunks of windows
+    b = nets._Builder(); b.dense(b.maxpool(b.bn(b.conv(b.maxpool(b.relu(b.bn(b.conv(0, 16, bias=False)))), 8, bias=False))), 5)
+    c["bn_pool"] = (b.array(), (12, 8, 3), 6)
     b = nets._Builder()
     t = b.relu(b.bn(b.conv(0, 16, bias=False)))
     u = b.bn(b.conv(b.relu(b.bn(b.conv(t, 16, bias=False))), 16, bias=False))
