@@ -80,6 +80,78 @@ __device__ __forceinline__ unsigned tile_taps(const FastConvParams& p, int m0, i
     return u & all;
 }
 
+// Per-channel totals over a workgroup's output tile, for the forward statistics of a batch norm that follows the
+// convolution.  ss[j][4g + e] / qq[..] are the lane's own sums (values, squares) over its rows for channel
+// j*32 + 8g + 4*(lane >> 5) + e of the wave's column range.  Per wave the 32 row lanes of each half are added through a
+// wave-private LDS area of 64 rows x kStatPitch(TN) floats: 16-byte writes, then lane (c4 = lane & 7, rg = lane >> 3) adds
+// rows 8 rg .. 8 rg + 7 of four columns and two xor-shuffles join the four row groups of a half.  The WGM wave rows of
+// the tile are then added in wave order through a second small area, and the waves of row 0 store the tile's entry:
+// stat_slot[entry * 2 * N + n] = sum, [.. + N + n] = sum of squares.  Every order is fixed: the result is deterministic.
+template <int TN> constexpr int kStatPitch = 16 * TN + 4;     // floats; 16 TN + 4 = 4 mod 32: conflict-free 16-byte accesses
+template <int TN, int WGM, int WGN>
+__device__ __forceinline__ void store_column_stats(const float (&ss)[TN][16], const float (&qq)[TN][16], float* smem_f, int wave, int lane,
+                                                   float* stat_slot, int entry, int n_base, int N)
+{
+    constexpr int P = kStatPitch<TN>, NW = WGM * WGN;
+    const int wm = wave / WGN;
+    float* const area = smem_f + wave * (64 * P);
+    float* const cross = smem_f + NW * (64 * P);              // [NW][2][16 TN][2 halves]
+    float tot[2][4];
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float (&v)[TN][16] = which ? qq : ss;
+                *reinterpret_cast<f4*>(area + lane * P + j * 16 + 4 * g) = f4{v[j][4 * g], v[j][4 * g + 1], v[j][4 * g + 2], v[j][4 * g + 3]};
+            }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        // TN = 2: 8 column quads x 8 row groups; TN = 1: 4 column quads, lanes with (lane & 7) >= 4 idle
+        const int c4 = lane & 7, rg = lane >> 3;
+        f4 t = {0.f, 0.f, 0.f, 0.f};
+        if (c4 < 4 * TN) {
+#pragma unroll
+            for (int r = 0; r < 8; ++r) t += *reinterpret_cast<const f4*>(area + (rg * 8 + r) * P + c4 * 4);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float x = t[e];
+            x += __shfl_xor(x, 8);                            // row groups rg ^ 1
+            x += __shfl_xor(x, 16);                           // row groups rg ^ 2: lanes of one half now agree
+            tot[which][e] = x;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+    // lanes with (rg & 3) == 0 hold the wave's totals of column quad c4 for half h = rg >> 2
+    const int c4 = lane & 7, rg = lane >> 3, h = rg >> 2;
+    const bool owner = (rg & 3) == 0 && c4 < 4 * TN;
+    if (owner) {
+#pragma unroll
+        for (int which = 0; which < 2; ++which)
+            *reinterpret_cast<f4*>(cross + ((wave * 2 + which) * (4 * TN) + c4) * 8 + h * 4) = f4{tot[which][0], tot[which][1], tot[which][2], tot[which][3]};
+    }
+    __syncthreads();
+    if (owner && wm == 0) {
+        const int wn = wave % WGN;
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            f4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int r = 0; r < WGM; ++r)
+                a += *reinterpret_cast<const f4*>(cross + (((r * WGN + wn) * 2 + which) * (4 * TN) + c4) * 8 + h * 4);
+            // column quad c4 of the area = (j, g) = (c4 / 4, c4 % 4): channels j*32 + 8g + 4h + {0..3}
+            const int n = n_base + (c4 / 4) * 32 + 8 * (c4 % 4) + 4 * h;
+            *reinterpret_cast<f4*>(stat_slot + (long long)entry * 2 * N + which * N + n) = a;
+        }
+    }
+}
+template <int TN, int WGM, int WGN> constexpr size_t kStatLdsBytes = ((size_t)WGM * WGN * 64 * kStatPitch<TN> + (size_t)WGM * WGN * 2 * 4 * TN * 8) * 4;
+
 // Tile BMT x BN, slabs of 64 along K, WGM x WGN waves (wave tile BMT/WGM x BN/WGN).  Eight neighbouring lanes read the
 // full 128-byte line a row contributes to a slab.  NBUF = 1: one LDS buffer, the next slab waits in registers while the
 // current one is multiplied, two barriers per slab.  NBUF = 2: the next slab is written to the other buffer before the
@@ -214,6 +286,12 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
     char* obase = (char*)p.out + (long long)rep * p.out_rep * 4;
     const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
     const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
+    const bool stats = EPI == 0 && p.stat != nullptr;
+    float ss[TN][16], qq[TN][16];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int k = 0; k < 16; ++k) { ss[j][k] = 0.f; qq[j][k] = 0.f; }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int mm = m0 + wm * (BMT / WGM) + i * 32 + (lane & 31);
@@ -246,8 +324,19 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
 #pragma unroll
                 for (int e = 0; e < 4; ++e) r[e] = (__bf16)v[e];
                 *reinterpret_cast<bf16x4*>(obase + o) = r;
+                if (stats) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { const float f = (float)r[e]; ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * f; }
+                }
             }
         }
+    }
+    if (stats) {
+        // (the launcher asks for the larger of the K loop's LDS and kStatLdsBytes)
+        __syncthreads();                                      // every wave is past its last operand read
+        const int slot = (int)(item / (tiles_m * tiles_n));
+        store_column_stats<TN, WGM, WGN>(ss, qq, reinterpret_cast<float*>(smem), wave, lane, p.stat + (long long)slot * p.stat_rep,
+                                         m0 / BMT, n0 + wn * (BN / WGN), p.N);
     }
 }
 
@@ -384,6 +473,12 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
     char* obase = (char*)p.out + (long long)rep * p.out_rep * 4;
     const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
     const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
+    const bool stats = EPI == 0 && p.stat != nullptr;
+    float ss[TN][16], qq[TN][16];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) { ss[j][kk] = 0.f; qq[j][kk] = 0.f; }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int mm = m0 + wm * (256 / WGM) + i * 32 + (lane & 31);
@@ -413,8 +508,19 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) r[e] = (__bf16)v[e];
                 *reinterpret_cast<bf16x4*>(obase + o) = r;
+                if (stats) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { const float f = (float)r[e]; ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * f; }
+                }
             }
         }
+    }
+    if (stats) {
+        static_assert(kStatLdsBytes<TN, WGM, WGN> <= (size_t)P_BYTES, "statistics area does not fit the patch");
+        __syncthreads();                                      // every wave is past its last operand read
+        const int slot = (int)(item / (tiles_m * tiles_n));
+        store_column_stats<TN, WGM, WGN>(ss, qq, reinterpret_cast<float*>(smem), wave, lane, p.stat + (long long)slot * p.stat_rep,
+                                         m0 / BMT, n0 + wn * (BN / WGN), p.N);
     }
 }
 
@@ -785,7 +891,8 @@ __global__ __launch_bounds__(256) void weight_prep_kernel(WeightPrepParams p)
 template <int BMT, int BN, int WGM, int WGN, int NBUF>
 void launch_conv_t(const FastConvParams& p, int epi, int n_active, hipStream_t s)
 {
-    constexpr size_t lds = (size_t)NBUF * (BMT + BN) * 72 * 2;
+    constexpr size_t loop_lds = (size_t)NBUF * (BMT + BN) * 72 * 2, stat_lds = kStatLdsBytes<BN / WGN / 32, WGM, WGN>;
+    constexpr size_t lds = loop_lds > stat_lds ? loop_lds : stat_lds;
     const dim3 grid(die_grid((long long)((p.M + BMT - 1) / BMT) * (p.N / BN) * n_active)), block(WGM * WGN * 64);
     if (epi == 0) hipLaunchKernelGGL((conv_kernel<BMT, BN, WGM, WGN, NBUF, 0>), grid, block, lds, s, p);
     else hipLaunchKernelGGL((conv_kernel<BMT, BN, WGM, WGN, NBUF, 1>), grid, block, lds, s, p);
@@ -810,8 +917,10 @@ BigTileInfo query_big_tile()
 
 }  // namespace
 
-hipError_t launch_conv_fast(const FastConvParams& p0, int epi, int n_active, hipStream_t s)
+hipError_t launch_conv_fast(const FastConvParams& p0, int epi, int n_active, hipStream_t s, int* stat_rows)
 {
+    int rows_dummy = 0;
+    int& srows = stat_rows ? *stat_rows : rows_dummy;          // rows per statistics entry = rows per tile of the kernel
     if (n_active < 1) return hipSuccess;
     FastConvParams p = p0;
     p.n_active = n_active;
@@ -829,6 +938,7 @@ hipError_t launch_conv_fast(const FastConvParams& p0, int epi, int n_active, hip
             if (epi == 0) hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, WGM_, 0>), grid, block, lds, s, p); \
             else hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, WGM_, 1>), grid, block, lds, s, p); } while (0)
         // 128 output channels: waves 2 x 2 (128 x 64 each); 64: waves 4 x 1 (64 x 64 each)
+        srows = 256;
         if (p.W == 32 && bn == 128) HADFL_PATCH(32, 128, 2);
         else if (p.W == 32) HADFL_PATCH(32, 64, 4);
         else if (bn == 128) HADFL_PATCH(16, 128, 2);
@@ -842,6 +952,7 @@ hipError_t launch_conv_fast(const FastConvParams& p0, int epi, int n_active, hip
         const long long blocks = (long long)((p.M + 255) / 256) * (p.N / 256) * n_active;
         const long long rounds = (blocks + big.n_cu - 1) / big.n_cu;
         if (big.lds_ok && (p.tile_hint == 1 || blocks * 5 >= rounds * big.n_cu * 4)) {
+            srows = 256;
             launch_conv_t<256, 256, 2, 4, 2>(p, epi, n_active, s);
             return hipGetLastError();
         }
@@ -851,6 +962,7 @@ hipError_t launch_conv_fast(const FastConvParams& p0, int epi, int n_active, hip
     // Not on layers that could have had 256 x 256 tiles: where those do not fill their last round, 128 x 128 tiles
     // measured faster than 256 x 128 at every count of active replicas.
     const bool tall = p.N % 256 != 0 && (long long)(p.M / 256) * (p.N / bn) * n_active >= 512;
+    srows = tall ? 256 : 128;
     if (bn == 128) {
         if (tall) launch_conv_t<256, 128, 2, 2, 1>(p, epi, n_active, s);
         else launch_conv_t<128, 128, 2, 2, 1>(p, epi, n_active, s);

@@ -516,9 +516,10 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(BnParams p)
     const int c = blockIdx.x * 32 + cl;
     const bool live = c < p.C;
     float* part = p.partial + gi * p.partial_rep;
+    const int nk = (MODE == 0 && p.stats_done) ? p.stat_entries : p.chunks;
     float s = 0.f, q = 0.f;
     if (live)
-        for (int k = kl; k < p.chunks; k += 8) { s += part[(long long)k * 2 * p.C + c]; q += part[(long long)k * 2 * p.C + p.C + c]; }
+        for (int k = kl; k < nk; k += 8) { s += part[(long long)k * 2 * p.C + c]; q += part[(long long)k * 2 * p.C + p.C + c]; }
     red[kl][cl][0] = s; red[kl][cl][1] = q;
     __syncthreads();
     for (int w = 4; w > 0; w >>= 1) {
@@ -529,7 +530,7 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(BnParams p)
     s = red[0][cl][0]; q = red[0][cl][1];
     if (MODE == 0) {
         const float n = (float)p.rows;
-        const float x0 = ldf(tptr<T>(p.x, rep, p.x_rep), c);
+        const float x0 = p.stats_done ? 0.f : ldf(tptr<T>(p.x, rep, p.x_rep), c);   // the shift the sums were taken with
         const float md = s / n;                               // mean of the shifted values
         const float cen = fmaxf(q - s * md, 0.f);             // sum of squared deviations from the mean
         const float mean = x0 + md, var = cen / n;
@@ -990,19 +991,19 @@ hipError_t launch_bn_fwd(const BnParams& p0, int n_active, hipStream_t s)
         const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 31) / 32), (unsigned)n_active);
         if (p.pool && (p.H % 2 != 0 || p.W % 2 != 0 || p.rows % 4 != 0 || !p.pool_out)) return hipErrorInvalidValue;
         if (p.bf16) {
-            hipLaunchKernelGGL((bn_sums_vec_kernel<0, __bf16>), grid, block, 0, s, p);
+            if (!p.stats_done) hipLaunchKernelGGL((bn_sums_vec_kernel<0, __bf16>), grid, block, 0, s, p);
             hipLaunchKernelGGL((bn_finalize_kernel<0, __bf16>), fgrid, block, 0, s, p);
             if (p.pool) hipLaunchKernelGGL(bn_apply_fwd_pool_vec_kernel<__bf16>, grid, block, 0, s, p);
             else hipLaunchKernelGGL(bn_apply_fwd_vec_kernel<__bf16>, grid, block, 0, s, p);
         } else {
-            hipLaunchKernelGGL((bn_sums_vec_kernel<0, float>), grid, block, 0, s, p);
+            if (!p.stats_done) hipLaunchKernelGGL((bn_sums_vec_kernel<0, float>), grid, block, 0, s, p);
             hipLaunchKernelGGL((bn_finalize_kernel<0, float>), fgrid, block, 0, s, p);
             if (p.pool) hipLaunchKernelGGL(bn_apply_fwd_pool_vec_kernel<float>, grid, block, 0, s, p);
             else hipLaunchKernelGGL(bn_apply_fwd_vec_kernel<float>, grid, block, 0, s, p);
         }
         return hipGetLastError();
     }
-    if (p.pool) return hipErrorInvalidValue;                 // the caller folds a pool only where the vector kernels apply
+    if (p.pool || p.stats_done) return hipErrorInvalidValue;  // the caller asks for these only where the vector kernels apply
     const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active);
     if (p.bf16) {
         hipLaunchKernelGGL((bn_reduce_kernel<0, __bf16>), grid, block, 0, s, p);

@@ -42,6 +42,11 @@ public:
     // BN kernels: forward writes the pooled tensor as well, backward forms the full-resolution gradient on the fly from
     // the pooled gradient.  The pool layer itself issues nothing.
     std::vector<int> pool_of;             // per layer: index of the folded pool layer, or -1
+    // Statistics fusion (bf16 configuration): a lean convolution whose output feeds a batch norm only leaves the per-channel
+    // sums of its output in the BN partial region, and that BN's forward skips its own sums pass.
+    std::vector<int> stat_for;            // per layer: the BN layer fed by this convolution's statistics, or -1
+    std::vector<int> stat_from;           // per layer (BN): the convolution that supplies them, or -1
+    std::vector<int> stat_rows;           // per layer (BN): rows per statistics entry of the latest forward launch
     // bf16 configuration: regular convolution layers keep two bf16 weight matrices (forward / data-gradient order)
     std::vector<char> fast;               // per layer: the lean bf16 kernels apply
     std::vector<int64_t> wf_off, wb_off;  // per layer: offsets (bf16 elements) inside one replica's bf16 weight block
@@ -128,7 +133,6 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
     }
     L.rep_block = up64(off);
     L.shared_floats = up64(shared);
-    L.bn_floats = up64(bn_shared);
     L.fast.assign(plan.layers.size(), 0); L.wf_off.assign(plan.layers.size(), -1); L.wb_off.assign(plan.layers.size(), -1);
     if (cfg.bf16) {
         int64_t woff = 0;
@@ -143,7 +147,15 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
             L.wb_off[i] = woff; woff += up64(l.w_count);
         }
         L.wbf_rep = woff;
+        // a lean convolution in front of a batch norm leaves one statistics entry per 128 output rows (at most)
+        for (size_t k = 0; k < plan.layers.size(); ++k) {
+            const Layer& l = plan.layers[k];
+            if (l.type != HADFL_OP_BN || l.in0 < 1 || !L.fast[l.in0 - 1]) continue;
+            const TensorShape a = plan.tensors[l.in0];
+            bn_shared = std::max<int64_t>(bn_shared, (int64_t)cfg.n_replicas * ((B * a.h * a.w + 127) / 128) * 2 * a.c);
+        }
     }
+    L.bn_floats = up64(bn_shared);
     // position tables: worth it for small images (many border pixels), and the weight gradient needs slabs of 32
     // contraction indices to hold a single position
     L.tab_idx.assign(plan.layers.size(), -1);
@@ -236,6 +248,14 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
             const int pt = plan.layers[i].type;
             if (pt != HADFL_OP_CONV && pt != HADFL_OP_DENSE && pt != HADFL_OP_BN && pt != HADFL_OP_ADD) continue;
             e->out_tensor[i] = r.out; e->fused_relu[i] = 1; e->skip[j] = 1; e->masked[r.out] = 1;
+        }
+        e->stat_for.assign(nl, -1); e->stat_from.assign(nl, -1); e->stat_rows.assign(nl, 0);
+        for (int k = 0; k < nl; ++k) {
+            const Layer& b = plan.layers[k];
+            if (b.type != HADFL_OP_BN || b.in0 < 1 || consumers[b.in0] != 1) continue;
+            const int i = b.in0 - 1;                        // layer i writes tensor i + 1
+            if (!e->fast[i] || plan.layers[i].type != HADFL_OP_CONV || e->out_tensor[i] != b.in0) continue;
+            e->stat_for[i] = k; e->stat_from[k] = i;
         }
         e->pool_of.assign(nl, -1);
         const int vec = cfg.bf16 ? 8 : 4;
@@ -448,7 +468,12 @@ struct Runner {
                 f.bias = l.bias ? e.buf.replicas + l.b_off : nullptr; f.bias_rep = e.plan.row_stride;
                 f.relu = p.relu; f.order = e.buf.order; f.tile_hint = e.tile_hint;
                 f.perm = perm(i); f.posmask = posmask(i);
-                run("conv_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_conv_fast(f, 0, na, s); });
+                int* srows = nullptr;
+                if (e.stat_for[i] >= 0) {
+                    f.stat = bn_shared(); f.stat_rep = ((int64_t)p.M + 127) / 128 * 2 * p.Cout;
+                    srows = &e.stat_rows[e.stat_for[i]];
+                }
+                run("conv_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_conv_fast(f, 0, na, s, srows); });
                 break;
             }
             if (l.type == HADFL_OP_DENSE && l.cout <= 16 && l.in0 != 0 && !p.relu) {
@@ -471,6 +496,10 @@ struct Runner {
         case HADFL_OP_BN: {
             BnParams b = bn_params(i);
             b.y = actw(ot); b.relu = e.fused_relu[i];
+            if (e.stat_from[i] >= 0 && e.stat_rows[i] > 0) {          // the convolution in front left the sums
+                b.stats_done = 1; b.stat_entries = (b.rows + e.stat_rows[i] - 1) / e.stat_rows[i];
+                b.partial_rep = ((int64_t)b.rows + 127) / 128 * 2 * b.C;
+            }
             if (e.pool_of[i] >= 0) {
                 b.pool = 1; b.H = a.h; b.W = a.w;
                 b.pool_out = actw(e.plan.layers[e.pool_of[i]].out); b.pool_out_rep = e.rep_block;

@@ -56,9 +56,14 @@ struct FastConvParams {      // out[m][n] = sum_k act[pixel(m) + tap(k)][c(k)] *
     // bit r * S + s set when tap (r, s) of that pixel lies inside the image
     const int* perm; const unsigned* posmask;
     int n_active;                              // set by the launcher
+    // forward only, optional: per-channel sums of the stored outputs for the batch norm that follows.  Entry e of slot g
+    // covers GEMM rows [e * R, (e + 1) * R), R = the chosen kernel's rows per tile (reported by the launcher):
+    // stat[g * stat_rep + e * 2 * N + n] = sum of out[m][n], [.. + N + n] = sum of out[m][n]^2 (values as rounded to bf16)
+    float* stat; long long stat_rep;
 };
 // epi 0: forward (+bias, ReLU); epi 1: data gradient (mask, accumulate).  Needs C % 64 == 0 and N % 64 == 0.
-hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s);
+// stat_rows (may be null): receives the rows per statistics entry of the kernel that was launched (128 or 256).
+hipError_t launch_conv_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s, int* stat_rows = nullptr);
 
 struct FastWgradParams {     // dW[(tap, ci) | bias row][co] over pixels; needs C % 8 == 0, N % 64 == 0, H, W powers of two
     int B, H, W, C, N, R, S, pad, M, K, kchunk, splits, w_shift, has_bias;
@@ -151,6 +156,9 @@ struct BnParams {
     // a 2x2 / stride-2 max-pool folded into the layer (vector kernels only; H, W even): forward also writes the pooled
     // output; backward takes the gradient of the pooled output and the stored forward output instead of dy
     int pool, H, W;
+    // forward: the producing convolution already left per-entry sums of x and x^2 in `partial` ([stat_entries][2][C]); the
+    // sums pass is skipped and the shift of the one-pass variance is zero
+    int stats_done, stat_entries;
     float* pool_out; long long pool_out_rep;
     const float* pool_y; long long pool_y_rep;
     const float* pool_g; long long pool_g_rep;

@@ -153,7 +153,7 @@ def test_regular_layer_bf16_256_tiles(monkeypatch):
     b = nets._Builder()
     t = b.relu(b.conv(0, 64))
     t = b.relu(b.conv(t, 256))
-    t = b.relu(b.conv(t, 256))
+    t = b.relu(b.bn(b.conv(t, 256, bias=False)))         # the convolution also leaves the BN's sums (ragged last tile)
     b.dense(b.gap(t), 5)
     ops, shape, batch = b.array(), (8, 8, 3), 5          # 320 rows per replica: one full and one ragged 256-row tile
     N = 3
