@@ -31,8 +31,8 @@ TRAFFIC = {
     # all weight-gradient launches of a cycle, averaged (the figure includes the fused update's parameter traffic)
     ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_first_bf16.hip"),
-                                       "46897f2d1e97ab112cc6c60b987fd8f28689f19968c88708d07258bfd1be4459",
-                                       569265620.0),
+                                       "94dc362f9ffa2b2477867e99ecc285e04177a5dd2533186662343bd1f1071294",
+                                       569391985.0),
 }
 
 
