@@ -413,6 +413,28 @@ __global__ __launch_bounds__(256) void splitk_reduce_vec_kernel(const float* __r
     }
 }
 
+// The same sum, applied as the parameter update instead of being stored: buf = momentum*buf + g; w = w - lr*buf
+// (local-update equation of Sec. 2.2).  w and buf point at the layer's parameters inside the replica rows.
+__global__ __launch_bounds__(256) void splitk_reduce_update_kernel(const float* __restrict__ partial, long long split_stride,
+                                                                   int splits, float* __restrict__ w, float* __restrict__ buf,
+                                                                   long long row_stride, long long count4, float lr, float momentum,
+                                                                   const int* __restrict__ order)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const int g = blockIdx.y, rep = order[g];
+    const f4* src = reinterpret_cast<const f4*>(partial + (long long)g * split_stride * splits);
+    f4* wd = reinterpret_cast<f4*>(w + (long long)rep * row_stride);
+    f4* bd = buf ? reinterpret_cast<f4*>(buf + (long long)rep * row_stride) : nullptr;
+    const long long stride4 = split_stride / 4;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < count4; i += (long long)gridDim.x * 256) {
+        f4 acc = src[i];
+#pragma unroll 4
+        for (int k = 1; k < splits; ++k) acc = acc + src[(long long)k * stride4 + i];
+        if (bd) { acc = bd[i] * momentum + acc; bd[i] = acc; }
+        wd[i] = wd[i] - acc * lr;
+    }
+}
+
 template <int BM, int BN, int WM, int WN>
 hipError_t launch_tile(const GemmParams& p0, int n_active, hipStream_t s)
 {
@@ -465,6 +487,20 @@ hipError_t launch_splitk_reduce(const float* partial, long long split_stride, in
     if (bx > 4096) bx = 4096;
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)bx, (unsigned)n_active), dim3(256), 0, s, partial,
                        split_stride, splits, out, out_rep, count, order);
+    return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce_update(const float* partial, long long split_stride, int splits, float* w, float* buf,
+                                       long long row_stride, long long count, float lr, float momentum, const int* order,
+                                       int n_active, hipStream_t s)
+{
+    if (n_active < 1 || count < 1) return hipSuccess;
+    if (count % 4 != 0 || split_stride % 4 != 0 || row_stride % 4 != 0 ||
+        (((uintptr_t)partial | (uintptr_t)w | (uintptr_t)buf) & 15) != 0) return hipErrorInvalidValue;
+    long long bx = (count / 4 + 255) / 256;
+    if (bx > 2048) bx = 2048;
+    hipLaunchKernelGGL(splitk_reduce_update_kernel, dim3((unsigned)bx, (unsigned)n_active), dim3(256), 0, s, partial,
+                       split_stride, splits, w, buf, row_stride, count / 4, lr, momentum, order);
     return hipGetLastError();
 }
 

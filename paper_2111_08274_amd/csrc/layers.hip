@@ -851,14 +851,18 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(256) void sgd_kernel(SgdParams p)
 {
     const int rep = p.order[blockIdx.y];
-    f4* w = reinterpret_cast<f4*>(p.w + rep * p.row_stride + p.first);
-    const f4* g = reinterpret_cast<const f4*>(p.g + rep * p.row_stride + p.first);
-    f4* buf = p.buf ? reinterpret_cast<f4*>(p.buf + rep * p.row_stride + p.first) : nullptr;
-    const long long n4 = p.count / 4;
+    float* const w = p.w + rep * p.row_stride;
+    const float* const g = p.g + rep * p.row_stride;
+    float* const buf = p.buf ? p.buf + rep * p.row_stride : nullptr;
+    long long n4 = 0;
+    for (int k = 0; k < p.n_seg; ++k) n4 += p.count[k] / 4;
     for (long long i = gtid(); i < n4; i += gstride()) {
-        f4 d = g[i];
-        if (buf) { d = buf[i] * p.momentum + d; buf[i] = d; }
-        w[i] = w[i] - d * p.lr;
+        long long j = i; int k = 0;
+        while (j >= p.count[k] / 4) { j -= p.count[k] / 4; ++k; }       // piece k, vector j of it
+        const long long o = p.first[k] + 4 * j;
+        f4 d = *reinterpret_cast<const f4*>(g + o);
+        if (buf) { d = *reinterpret_cast<const f4*>(buf + o) * p.momentum + d; *reinterpret_cast<f4*>(buf + o) = d; }
+        *reinterpret_cast<f4*>(w + o) = *reinterpret_cast<const f4*>(w + o) - d * p.lr;
     }
     if (p.bump && blockIdx.x == 0 && threadIdx.x == 0) { p.cursor[rep] += 1; p.versions[rep] += 1; }
 }
@@ -1068,8 +1072,13 @@ hipError_t launch_softmax_ce(const LossParams& p, int n_active, hipStream_t s)
 hipError_t launch_sgd(const SgdParams& p, int n_active, hipStream_t s)
 {
     if (n_active < 1) return hipSuccess;
-    if (p.count % 4 != 0 || p.first % 4 != 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(sgd_kernel, ew_grid(p.count / 4 > 0 ? p.count / 4 : 1, n_active), dim3(256), 0, s, p);
+    if (p.n_seg < 0 || p.n_seg > kMaxSgdSegments) return hipErrorInvalidValue;
+    long long n4 = 0;
+    for (int k = 0; k < p.n_seg; ++k) {
+        if (p.count[k] % 4 != 0 || p.first[k] % 4 != 0 || p.count[k] < 0) return hipErrorInvalidValue;
+        n4 += p.count[k] / 4;
+    }
+    hipLaunchKernelGGL(sgd_kernel, ew_grid(n4 > 0 ? n4 : 1, n_active), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

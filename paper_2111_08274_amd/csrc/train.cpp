@@ -204,7 +204,13 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
         int64_t pos = 0;
         for (size_t i = 0; i < plan.layers.size(); ++i) {
             const Layer& l = plan.layers[i];
-            if (!e->fast[i] || e->splits[i] != 1) continue;
+            if (l.type != HADFL_OP_CONV && l.type != HADFL_OP_DENSE) continue;
+            // in the weight-gradient epilogue (lean kernels, K not split), or in the split-K reduction of a layer whose
+            // fp32 weights nothing reads between its weight gradient and the update: the lean layers' data gradients
+            // read the bf16 copies, a layer on the data set has no data gradient
+            const bool in_epilogue = e->fast[i] && e->splits[i] == 1;
+            const bool in_reduce = e->splits[i] > 1 && (e->fast[i] || l.in0 == 0);
+            if (!in_epilogue && !in_reduce) continue;
             const int64_t cnt = l.w_count + (l.bias ? l.cout : 0);      // bias sits directly behind the weights
             if (l.w_off % 4 != 0 || cnt % 4 != 0 || l.w_off < pos || (l.bias && l.b_off != l.w_off + l.w_count)) continue;
             e->fused_update[i] = 1;
@@ -619,7 +625,12 @@ struct Runner {
                 if (e.fused_update[i] && na_next > 0) pending_prep = (int)i;
             } else
             run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return gemm(p); });
-            if (p.splits > 1)
+            if (p.splits > 1 && e.fused_update[i])
+                run("splitk_reduce", 0, 4.0 * mn * (p.splits + 4), [&] {
+                    return launch_splitk_reduce_update(shared(), p.out_split, p.splits, e.buf.replicas + l.w_off,
+                                                       e.buf.mom ? e.buf.mom + l.w_off : nullptr, e.plan.row_stride, mn, e.cfg.lr,
+                                                       e.cfg.momentum, e.buf.order, na, s); });
+            else if (p.splits > 1)
                 run("splitk_reduce", 0, 4.0 * mn * (p.splits + 1), [&] { return launch_splitk_reduce(shared(), p.out_split, p.splits, e.buf.grad + l.w_off,
                                                                        e.plan.row_stride, mn, e.buf.order, na, s); });
             unfork();
@@ -729,10 +740,19 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
         sp.lr = e->cfg.lr; sp.momentum = e->cfg.momentum;
         sp.cursor = e->buf.cursor; sp.versions = e->buf.versions; sp.order = e->buf.order;
         r.cur_layer = 0;
-        for (size_t k = 0; k < e->update_segments.size(); ++k) {
-            sp.first = e->update_segments[k].first; sp.count = e->update_segments[k].second;
-            sp.bump = k + 1 == e->update_segments.size();
-            r.run("sgd", 0, (e->buf.mom ? 20.0 : 12.0) * sp.count, [&] { return launch_sgd(sp, r.na, s); });
+        // the pieces of the row no weight-gradient kernel has updated already, several per launch; the last launch (there
+        // is always one) also advances the replicas' batch cursors and versions
+        const size_t nseg = e->update_segments.size();
+        for (size_t k0 = 0; k0 < std::max<size_t>(nseg, 1); k0 += kMaxSgdSegments) {
+            const size_t k1 = std::min(nseg, k0 + kMaxSgdSegments);
+            double floats = 0.0;
+            sp.n_seg = (int)(k1 - k0);
+            for (size_t k = k0; k < k1; ++k) {
+                sp.first[k - k0] = e->update_segments[k].first; sp.count[k - k0] = e->update_segments[k].second;
+                floats += (double)e->update_segments[k].second;
+            }
+            sp.bump = k1 == nseg;
+            r.run("sgd", 0, (e->buf.mom ? 20.0 : 12.0) * floats, [&] { return launch_sgd(sp, r.na, s); });
         }
     }
     if (r.rc != hipSuccess) {

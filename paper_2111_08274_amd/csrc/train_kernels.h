@@ -40,6 +40,11 @@ hipError_t launch_gemm_bf16(const GemmParams& p, int n_active, hipStream_t s);
 // out[rep][i] = sum_s partial[g][s][i], s ascending
 hipError_t launch_splitk_reduce(const float* partial, long long split_stride, int splits, float* out, long long out_rep,
                                 long long count, const int* order, int n_active, hipStream_t s);
+// The same sum applied as the update of the layer's parameters (w, buf: first parameter of the layer in replica row 0;
+// buf may be null).  Needs count, split_stride and row_stride multiples of 4 and 16-byte aligned pointers.
+hipError_t launch_splitk_reduce_update(const float* partial, long long split_stride, int splits, float* w, float* buf,
+                                       long long row_stride, long long count, float lr, float momentum, const int* order,
+                                       int n_active, hipStream_t s);
 
 // ---- lean bf16 kernels for regular stride-1 "same" convolutions (conv_bf16_fast.hip) ----
 struct FastConvParams {      // out[m][n] = sum_k act[pixel(m) + tap(k)][c(k)] * wmat[n][k]; M = B*H*W, K = R*S*C
@@ -176,11 +181,14 @@ struct LossParams {
 };
 hipError_t launch_softmax_ce(const LossParams& p, int n_active, hipStream_t s);
 
+constexpr int kMaxSgdSegments = 16;
 struct SgdParams {
-    float* w; const float* g; float* buf; long long row_stride; long long count;   // count = trainable extent (multiple of 4)
+    float* w; const float* g; float* buf; long long row_stride;
     float lr, momentum;
     long long* cursor; int* versions;      // bumped once per replica per step (when bump is set)
-    long long first; int bump;             // the launch covers floats [first, first + count) of each row
+    int bump;
+    // the launch covers n_seg pieces of each row: floats [first[k], first[k] + count[k]), all multiples of 4
+    int n_seg; long long first[kMaxSgdSegments], count[kMaxSgdSegments];
     const int* order;
 };
 hipError_t launch_sgd(const SgdParams& p, int n_active, hipStream_t s);
