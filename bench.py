@@ -31,8 +31,8 @@ TRAFFIC = {
     # all weight-gradient launches of a cycle, averaged (the figure includes the fused update's parameter traffic)
     ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_first_bf16.hip"),
-                                       "94dc362f9ffa2b2477867e99ecc285e04177a5dd2533186662343bd1f1071294",
-                                       569391985.0),
+                                       "5d4f3c82bbe122a4c60f2d1590258b333dfc7c206e4157af505ed4ccb245194b",
+                                       579785905.0),
 }
 
 

@@ -582,6 +582,50 @@ __device__ __forceinline__ void store_block32(const f16& acc, float* stage, int 
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The fused update of one 32 x 32 block in two steps, so that the parameter and momentum loads of the NEXT block are in
+// flight while the current one is staged, updated and stored: a wave that loads, computes and stores block after block
+// keeps only 2 KiB in flight and the epilogue of the short-contraction layers runs at a fraction of the memory rate.
+struct UpdateOperands { f4 w[4], b[4]; };
+__device__ __forceinline__ void fetch_update_operands(UpdateOperands& u, int lane, int m_base, int m_end, int n_base, int N,
+                                                      const float* sgd_w, const float* sgd_buf)
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int mm = m_base + (lane >> 3) + 8 * t;
+        const long long o = (long long)mm * N + n_base + (lane & 7) * 4;
+        u.w[t] = f4{0.f, 0.f, 0.f, 0.f}; u.b[t] = f4{0.f, 0.f, 0.f, 0.f};
+        if (mm < m_end) {
+            u.w[t] = *reinterpret_cast<const f4*>(sgd_w + o);
+            if (sgd_buf) u.b[t] = *reinterpret_cast<const f4*>(sgd_buf + o);
+        }
+    }
+}
+__device__ __forceinline__ void update_block32(const f16& acc, const UpdateOperands& u, float* stage, int lane, int m_base, int m_end,
+                                               int n_base, const FastWgradParams& p, float* sgd_w, float* sgd_buf)
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const f4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+        *reinterpret_cast<f4*>(stage + (lane & 31) * kStagePitch + 8 * q + 4 * (lane >> 5)) = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int rr = (lane >> 3) + 8 * t, cc = (lane & 7) * 4;
+        f4 d = *reinterpret_cast<const f4*>(stage + rr * kStagePitch + cc);
+        const int mm = m_base + rr;
+        if (mm >= m_end) continue;
+        const long long o = (long long)mm * p.N + n_base + cc;
+        if (sgd_buf) { d = u.b[t] * p.momentum + d; *reinterpret_cast<f4*>(sgd_buf + o) = d; }
+        *reinterpret_cast<f4*>(sgd_w + o) = u.w[t] - d * p.lr;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Tile BMT x BN, WGM x WGN waves, slabs of BKT contraction indices, two LDS buffers.
 template <int BMT, int BN, int WGM, int WGN, int BKT>
 __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN == 8 ? 1 : 2) void wgrad_kernel(FastWgradParams p)
@@ -727,6 +771,18 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN == 8 ? 1 : 2) void wgrad_
     float* const sgd_buf = (sgd_w && p.sgd_buf) ? p.sgd_buf + (long long)rep * p.out_rep : nullptr;
     static_assert((size_t)NT / 64 * 32 * kStagePitch * 4 <= 2 * (size_t)(A_BUF + B_BUF), "staging area does not fit the LDS of the K loop");
     float* const stage = reinterpret_cast<float*>(smem) + wave * (32 * kStagePitch);
+    if (sgd_w) {
+        const int mb = m0 + wm * (BMT / WGM), nb = n0 + wn * (BN / WGN);
+        UpdateOperands u[2];
+        fetch_update_operands(u[0], lane, mb, p.M, nb, p.N, sgd_w, sgd_buf);
+#pragma unroll
+        for (int k = 0; k < TM * TN; ++k) {
+            if (k + 1 < TM * TN)
+                fetch_update_operands(u[(k + 1) & 1], lane, mb + ((k + 1) / TN) * 32, p.M, nb + ((k + 1) % TN) * 32, p.N, sgd_w, sgd_buf);
+            update_block32(acc[k / TN][k % TN], u[k & 1], stage, lane, mb + (k / TN) * 32, p.M, nb + (k % TN) * 32, p, sgd_w, sgd_buf);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
