@@ -267,3 +267,23 @@ def test_vgg16_workload_launch_shape_properties_and_sampled_replica():
         del ctx
         torch.cuda.empty_cache()
     assert np.array_equal(outs[0], outs[1])
+
+
+def test_deep_narrow_net_more_update_pieces_than_one_launch_takes():
+    """20 x (conv 64 -> BN -> ReLU): every convolution applies its own update (epilogue or split-K reduction), which
+    leaves 21 separate pieces of the parameter row (the BN parameters between them, the classifier) for the update
+    kernel: more than one launch's table holds.  Two steps, so the second runs on weights every path has updated."""
+    b = nets._Builder()
+    t = b.relu(b.bn(b.conv(0, 64, bias=False)))
+    for _ in range(19):
+        t = b.relu(b.bn(b.conv(t, 64, bias=False)))
+    b.dense(b.gap(t), 5)
+    ops, shape, batch = b.array(), (4, 4, 3), 8
+    N = 2
+    x, y = _data(N, 2 * batch, shape, 5, seed=91)
+    p = Pair(ops, shape, N, 1, x, y, batch, 0.01, 0.9, [2, 1], bf16=True)
+    p.local_steps()
+    d = p.max_rel_diff()
+    print("deep narrow bf16 rel", d, "loss", p.gpu.losses(), p.cpu.loss, flush=True)
+    assert d <= REL
+    p.close()
