@@ -31,8 +31,8 @@ TRAFFIC = {
     # all weight-gradient launches of a cycle, averaged (the figure includes the fused update's parameter traffic)
     ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_first_bf16.hip"),
-                                       "5d4f3c82bbe122a4c60f2d1590258b333dfc7c206e4157af505ed4ccb245194b",
-                                       579785905.0),
+                                       "97aed0522c56ddd91c1d678a4bafb8ae1b3211911ac0997d2f5aa7590bdd1feb",
+                                       547766557.0),
 }
 
 

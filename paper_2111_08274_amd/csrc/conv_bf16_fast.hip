@@ -595,8 +595,8 @@ __device__ __forceinline__ void fetch_update_operands(UpdateOperands& u, int lan
         const long long o = (long long)mm * N + n_base + (lane & 7) * 4;
         u.w[t] = f4{0.f, 0.f, 0.f, 0.f}; u.b[t] = f4{0.f, 0.f, 0.f, 0.f};
         if (mm < m_end) {
-            u.w[t] = *reinterpret_cast<const f4*>(sgd_w + o);
-            if (sgd_buf) u.b[t] = *reinterpret_cast<const f4*>(sgd_buf + o);
+            u.w[t] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(sgd_w + o));          // streamed once per step
+            if (sgd_buf) u.b[t] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(sgd_buf + o));
         }
     }
 }
@@ -618,8 +618,8 @@ __device__ __forceinline__ void update_block32(const f16& acc, const UpdateOpera
         const int mm = m_base + rr;
         if (mm >= m_end) continue;
         const long long o = (long long)mm * p.N + n_base + cc;
-        if (sgd_buf) { d = u.b[t] * p.momentum + d; *reinterpret_cast<f4*>(sgd_buf + o) = d; }
-        *reinterpret_cast<f4*>(sgd_w + o) = u.w[t] - d * p.lr;
+        if (sgd_buf) { d = u.b[t] * p.momentum + d; __builtin_nontemporal_store(d, reinterpret_cast<f4*>(sgd_buf + o)); }
+        __builtin_nontemporal_store(u.w[t] - d * p.lr, reinterpret_cast<f4*>(sgd_w + o));
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -1055,7 +1055,7 @@ hipError_t launch_wgrad_fast(const FastWgradParams& p0, int n_active, hipStream_
     // (gradient store or fused update), which the smaller tiles overlap with other workgroups' K loops -- measured 5-30 %
     // faster there at every count of active replicas.
     int bmt = 128;
-    const bool long_k = p.tile_hint == 1 || (p.splits > 1 ? p.kchunk : p.K) >= 4096;
+    const bool long_k = p.tile_hint == 1 || p.K >= 4096;
     if (long_k && p.N % 256 == 0) {
         const long long blocks = (long long)((p.M + 255) / 256) * (p.N / 256) * p.splits * n_active;
         const long long rounds = (blocks + big.n_cu - 1) / big.n_cu;

@@ -427,11 +427,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_update_kernel(const float* 
     f4* bd = buf ? reinterpret_cast<f4*>(buf + (long long)rep * row_stride) : nullptr;
     const long long stride4 = split_stride / 4;
     for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < count4; i += (long long)gridDim.x * 256) {
-        f4 acc = src[i];
+        f4 acc = __builtin_nontemporal_load(src + i);              // partial sums, parameters, momentum: each touched once
 #pragma unroll 4
-        for (int k = 1; k < splits; ++k) acc = acc + src[(long long)k * stride4 + i];
-        if (bd) { acc = bd[i] * momentum + acc; bd[i] = acc; }
-        wd[i] = wd[i] - acc * lr;
+        for (int k = 1; k < splits; ++k) acc = acc + __builtin_nontemporal_load(src + (long long)k * stride4 + i);
+        if (bd) { acc = __builtin_nontemporal_load(bd + i) * momentum + acc; __builtin_nontemporal_store(acc, bd + i); }
+        __builtin_nontemporal_store(__builtin_nontemporal_load(wd + i) - acc * lr, wd + i);
     }
 }
 

@@ -295,9 +295,11 @@ __device__ __forceinline__ void ldv(const float* p, long long i, float (&o)[4])
     const f4v v = *reinterpret_cast<const f4v*>(p + i);
     o[0] = v[0]; o[1] = v[1]; o[2] = v[2]; o[3] = v[3];
 }
+// (bf16 tensors of the large configuration are streamed once per pass and exceed the caches: non-temporal accesses
+// measured 3 % faster over the BN kernels; the fp32 tensors of the smaller configurations measured slower with them)
 __device__ __forceinline__ void ldv(const __bf16* p, long long i, float (&o)[8])
 {
-    const bf8v v = *reinterpret_cast<const bf8v*>(p + i);
+    const bf8v v = __builtin_nontemporal_load(reinterpret_cast<const bf8v*>(p + i));
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = (float)v[e];
 }
@@ -311,7 +313,7 @@ __device__ __forceinline__ void stv(__bf16* p, long long i, const float (&o)[8])
     bf8v v;
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = (__bf16)o[e];
-    *reinterpret_cast<bf8v*>(p + i) = v;
+    __builtin_nontemporal_store(v, reinterpret_cast<bf8v*>(p + i));
 }
 
 // Element-wise kernels with 16-byte accesses for counts that are a multiple of VEC (same results as the scalar ones).
