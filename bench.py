@@ -31,8 +31,8 @@ TRAFFIC = {
     # all weight-gradient launches of a cycle, averaged (the figure includes the fused update's parameter traffic)
     ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_first_bf16.hip"),
-                                       "97aed0522c56ddd91c1d678a4bafb8ae1b3211911ac0997d2f5aa7590bdd1feb",
-                                       547766557.0),
+                                       "b9e406a473107cf8a0246c1310e6cb6c7c0e431ba50bbd5542babba1536f27bc",
+                                       547780556.0),
 }
 
 

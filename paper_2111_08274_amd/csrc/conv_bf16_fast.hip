@@ -932,7 +932,7 @@ __global__ __launch_bounds__(256) void weight_prep_kernel(WeightPrepParams p)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int ci = ci0 + ty + 4 * r;
-        const float v = w[(long long)ci * p.N + co0 + tx];
+        const float v = __builtin_nontemporal_load(w + (long long)ci * p.N + co0 + tx);    // the master weights are read once
         tile[ty + 4 * r][tx] = v;
         wb[(long long)ci * Kb + (taps - 1 - tap) * p.N + co0 + tx] = (__bf16)v;
     }
