@@ -549,127 +549,25 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(BnParams p)
     }
 }
 
-// The finalising step folded into the apply kernels (BnParams::fold, set by the launchers when there are at most
-// kBnFoldEntries partial entries): every workgroup adds the entries of its own channels itself -- thread (channel vector,
-// row lane rl) takes entries rl, rl + lanes, ... in ascending order, a fixed-order tree joins the row lanes -- so all
-// workgroups of a channel group get bit-identical totals, and the tiny finalising launch between the two passes goes
-// away.  The workgroup of chunk 0 stores what outlives the kernel (saved statistics, running statistics, gradients of
-// gamma and beta).  Every thread of the workgroup must call these (they contain barriers when folding).
-constexpr int kBnFoldEntries = 128;
-template <int VEC>
-__device__ __forceinline__ void bn_block_totals(const BnParams& p, const BnGeo& g, const float* part, int nk,
-                                                float (&red)[256][2 * VEC + 1], float (&s)[VEC], float (&q)[VEC])
-{
-    float a0[VEC], a1[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) { a0[e] = 0.f; a1[e] = 0.f; }
-    if (g.live)
-        for (int k = g.rl; k < nk; k += g.rl_count) {
-            const float* en = part + (long long)k * 2 * p.C + g.c;
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) { a0[e] += en[e]; a1[e] += en[p.C + e]; }
-        }
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) { red[threadIdx.x][e] = a0[e]; red[threadIdx.x][VEC + e] = a1[e]; }
-    __syncthreads();
-    for (int w = g.rl_count / 2; w > 0; w >>= 1) {
-        if (g.rl < w) {
-#pragma unroll
-            for (int e = 0; e < 2 * VEC; ++e) red[threadIdx.x][e] += red[threadIdx.x + w * g.cvb][e];
-        }
-        __syncthreads();
-    }
-    const int owner = threadIdx.x % g.cvb;                    // the row-lane-0 thread of this thread's channel vector
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) { s[e] = red[owner][e]; q[e] = red[owner][VEC + e]; }
-}
-
-// forward: y = x * sc + sh for the thread's VEC channels
-template <typename T, int VEC>
-__device__ __forceinline__ void bn_fwd_coeffs(const BnParams& p, const BnGeo& g, int gi, int rep, float (&sc)[VEC], float (&sh)[VEC])
-{
-    float mean[VEC], istd[VEC];
-    if (p.fold) {
-        __shared__ float red[256][2 * VEC + 1];
-        float s[VEC], q[VEC];
-        bn_block_totals<VEC>(p, g, p.partial + gi * p.partial_rep, p.stats_done ? p.stat_entries : p.chunks, red, s, q);
-        if (!g.live) return;
-        const float n = (float)p.rows;
-        const bool keeper = g.chunk == 0 && g.rl == 0;
-        float* sv = p.saved + rep * p.saved_rep;
-        float* rm = p.params + rep * p.row_stride + p.stat_off;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            const int c = g.c + e;
-            const float x0 = p.stats_done ? 0.f : ldf(tptr<T>(p.x, rep, p.x_rep), c);   // the shift the sums were taken with
-            const float md = s[e] / n;                            // mean of the shifted values
-            const float cen = fmaxf(q[e] - s[e] * md, 0.f);       // sum of squared deviations from the mean
-            const float var = cen / n;
-            mean[e] = x0 + md; istd[e] = 1.0f / sqrtf(var + kBnEps);
-            if (keeper) {
-                sv[c] = mean[e]; sv[p.C + c] = istd[e];
-                const float unb = p.rows > 1 ? cen / (n - 1.f) : var;
-                rm[c] = (1.f - kBnStatMomentum) * rm[c] + kBnStatMomentum * mean[e];
-                rm[p.C + c] = (1.f - kBnStatMomentum) * rm[p.C + c] + kBnStatMomentum * unb;
-            }
-        }
-    } else {
-        if (!g.live) return;
-        const float* sv = p.saved + rep * p.saved_rep;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) { mean[e] = sv[g.c + e]; istd[e] = sv[p.C + g.c + e]; }
-    }
-    const float* row = p.params + rep * p.row_stride;
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-        const float gamma = row[p.w_off + g.c + e], beta = row[p.w_off + p.C + g.c + e];
-        sc[e] = gamma * istd[e]; sh[e] = beta - mean[e] * gamma * istd[e];
-    }
-}
-
-// backward: dx = k1 * (dy - kb - ((x - mean) * istd) * kg) for the thread's VEC channels
-template <int VEC>
-__device__ __forceinline__ void bn_bwd_coeffs(const BnParams& p, const BnGeo& g, int gi, int rep, float (&mean)[VEC], float (&istd)[VEC],
-                                              float (&k1)[VEC], float (&kb)[VEC], float (&kg)[VEC])
-{
-    float db[VEC], dg[VEC];
-    const float* part = p.partial + gi * p.partial_rep;
-    if (p.fold) {
-        __shared__ float red[256][2 * VEC + 1];
-        bn_block_totals<VEC>(p, g, part, p.chunks, red, db, dg);
-        if (!g.live) return;
-        if (g.chunk == 0 && g.rl == 0) {
-            float* gr = p.grads + rep * p.row_stride + p.w_off;
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) { gr[g.c + e] = dg[e]; gr[p.C + g.c + e] = db[e]; }
-        }
-    } else {
-        if (!g.live) return;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) { db[e] = part[g.c + e]; dg[e] = part[p.C + g.c + e]; }   // totals left in chunk 0 by bn_finalize_kernel<1>
-    }
-    const float* sv = p.saved + rep * p.saved_rep;
-    const float inv_n = 1.0f / (float)p.rows;
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-        const int c = g.c + e;
-        mean[e] = sv[c]; istd[e] = sv[p.C + c];
-        k1[e] = p.params[rep * p.row_stride + p.w_off + c] * istd[e];
-        kb[e] = db[e] * inv_n; kg[e] = dg[e] * inv_n;
-    }
-}
-
 template <typename T>
 __global__ __launch_bounds__(256) void bn_apply_fwd_vec_kernel(BnParams p)
 {
     constexpr int VEC = VecOf<T>::n;
     const int gi = blockIdx.y, rep = p.order[gi];
     const BnGeo g = bn_geo(p, VEC);
-    float sc[VEC], sh[VEC];
-    bn_fwd_coeffs<T, VEC>(p, g, gi, rep, sc, sh);
     if (!g.live) return;
     const T* x = tptr<T>(p.x, rep, p.x_rep);
     T* y = tptr<T>(p.y, rep, p.y_rep);
+    const float* row = p.params + rep * p.row_stride;
+    float sc[VEC], sh[VEC];
+    const float* sv = p.saved + rep * p.saved_rep;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const int c = g.c + e;
+        const float mean = sv[c], istd = sv[p.C + c];
+        const float gamma = row[p.w_off + c], beta = row[p.w_off + p.C + c];
+        sc[e] = gamma * istd; sh[e] = beta - mean * gamma * istd;
+    }
     const int r0 = g.chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
 #pragma unroll 4
     for (int r = r0 + g.rl; r < r1; r += g.rl_count) {
@@ -688,13 +586,23 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_vec_kernel(BnParams p)
     constexpr int VEC = VecOf<T>::n;
     const int gi = blockIdx.y, rep = p.order[gi];
     const BnGeo g = bn_geo(p, VEC);
-    float mean[VEC], istd[VEC], k1[VEC], kb[VEC], kg[VEC];
-    bn_bwd_coeffs<VEC>(p, g, gi, rep, mean, istd, k1, kb, kg);
     if (!g.live) return;
     const T* x = tptr<T>(p.x, rep, p.x_rep);
     const T* dy = tptr<T>(p.dy, rep, p.dy_rep);
     T* dx = tptr<T>(p.y, rep, p.y_rep);
     const T* mask = p.mask ? tptr<T>(p.mask, rep, p.mask_rep) : nullptr;
+    const float* part = p.partial + gi * p.partial_rep;
+    const float* sv = p.saved + rep * p.saved_rep;
+    const float inv_n = 1.0f / (float)p.rows;
+    float mean[VEC], istd[VEC], k1[VEC], kb[VEC], kg[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const int c = g.c + e;
+        const float db = part[c], dg = part[p.C + c];       // totals left in chunk 0 by bn_finalize_kernel<1>
+        mean[e] = sv[c]; istd[e] = sv[p.C + c];
+        k1[e] = p.params[rep * p.row_stride + p.w_off + c] * istd[e];
+        kb[e] = db * inv_n; kg[e] = dg * inv_n;
+    }
     const int r0 = g.chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
 #pragma unroll 4
     for (int r = r0 + g.rl; r < r1; r += g.rl_count) {
@@ -746,12 +654,20 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_pool_vec_kernel(BnParams p)
     constexpr int VEC = VecOf<T>::n;
     const int gi = blockIdx.y, rep = p.order[gi];
     const BnGeo g = bn_geo(p, VEC);
-    float sc[VEC], sh[VEC];
-    bn_fwd_coeffs<T, VEC>(p, g, gi, rep, sc, sh);
     if (!g.live) return;
     const T* x = tptr<T>(p.x, rep, p.x_rep);
     T* y = tptr<T>(p.y, rep, p.y_rep);
     T* po = tptr<T>(p.pool_out, rep, p.pool_out_rep);
+    const float* row = p.params + rep * p.row_stride;
+    float sc[VEC], sh[VEC];
+    const float* sv = p.saved + rep * p.saved_rep;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const int c = g.c + e;
+        const float mean = sv[c], istd = sv[p.C + c];
+        const float gamma = row[p.w_off + c], beta = row[p.w_off + p.C + c];
+        sc[e] = gamma * istd; sh[e] = beta - mean * gamma * istd;
+    }
     const int windows = p.rows / 4, cw = (windows + p.chunks - 1) / p.chunks;
     const int w0 = g.chunk * cw, w1 = min(windows, w0 + cw);
 #pragma unroll 2
@@ -846,14 +762,24 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_pool_vec_kernel(BnParams p)
     constexpr int VEC = VecOf<T>::n;
     const int gi = blockIdx.y, rep = p.order[gi];
     const BnGeo g = bn_geo(p, VEC);
-    float mean[VEC], istd[VEC], k1[VEC], kb[VEC], kg[VEC];
-    bn_bwd_coeffs<VEC>(p, g, gi, rep, mean, istd, k1, kb, kg);
     if (!g.live) return;
     const T* x = tptr<T>(p.x, rep, p.x_rep);
     const T* yo = tptr<T>(p.pool_y, rep, p.pool_y_rep);
     const T* pg = tptr<T>(p.pool_g, rep, p.pool_g_rep);
     T* dx = tptr<T>(p.y, rep, p.y_rep);
     const T* mask = p.mask ? tptr<T>(p.mask, rep, p.mask_rep) : nullptr;
+    const float* part = p.partial + gi * p.partial_rep;
+    const float* sv = p.saved + rep * p.saved_rep;
+    const float inv_n = 1.0f / (float)p.rows;
+    float mean[VEC], istd[VEC], k1[VEC], kb[VEC], kg[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        const int c = g.c + e;
+        const float db = part[c], dg = part[p.C + c];       // totals left in chunk 0 by bn_finalize_kernel<1>
+        mean[e] = sv[c]; istd[e] = sv[p.C + c];
+        k1[e] = p.params[rep * p.row_stride + p.w_off + c] * istd[e];
+        kb[e] = db * inv_n; kg[e] = dg * inv_n;
+    }
     const int windows = p.rows / 4, cw = (windows + p.chunks - 1) / p.chunks;
     const int w0 = g.chunk * cw, w1 = min(windows, w0 + cw);
 #pragma unroll 2
@@ -1070,15 +996,14 @@ hipError_t launch_bn_fwd(const BnParams& p0, int n_active, hipStream_t s)
         const int cgroups = (p.C / vec + p.cvb - 1) / p.cvb;
         const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 31) / 32), (unsigned)n_active);
         if (p.pool && (p.H % 2 != 0 || p.W % 2 != 0 || p.rows % 4 != 0 || !p.pool_out)) return hipErrorInvalidValue;
-        p.fold = (p.stats_done ? p.stat_entries : p.chunks) <= kBnFoldEntries;
         if (p.bf16) {
             if (!p.stats_done) hipLaunchKernelGGL((bn_sums_vec_kernel<0, __bf16>), grid, block, 0, s, p);
-            if (!p.fold) hipLaunchKernelGGL((bn_finalize_kernel<0, __bf16>), fgrid, block, 0, s, p);
+            hipLaunchKernelGGL((bn_finalize_kernel<0, __bf16>), fgrid, block, 0, s, p);
             if (p.pool) hipLaunchKernelGGL(bn_apply_fwd_pool_vec_kernel<__bf16>, grid, block, 0, s, p);
             else hipLaunchKernelGGL(bn_apply_fwd_vec_kernel<__bf16>, grid, block, 0, s, p);
         } else {
             if (!p.stats_done) hipLaunchKernelGGL((bn_sums_vec_kernel<0, float>), grid, block, 0, s, p);
-            if (!p.fold) hipLaunchKernelGGL((bn_finalize_kernel<0, float>), fgrid, block, 0, s, p);
+            hipLaunchKernelGGL((bn_finalize_kernel<0, float>), fgrid, block, 0, s, p);
             if (p.pool) hipLaunchKernelGGL(bn_apply_fwd_pool_vec_kernel<float>, grid, block, 0, s, p);
             else hipLaunchKernelGGL(bn_apply_fwd_vec_kernel<float>, grid, block, 0, s, p);
         }
@@ -1109,17 +1034,16 @@ hipError_t launch_bn_bwd(const BnParams& p0, int n_active, hipStream_t s)
         const int cgroups = (p.C / vec + p.cvb - 1) / p.cvb;
         const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 31) / 32), (unsigned)n_active);
         if (p.pool && (p.H % 2 != 0 || p.W % 2 != 0 || p.rows % 4 != 0 || !p.pool_y || !p.pool_g)) return hipErrorInvalidValue;
-        p.fold = p.chunks <= kBnFoldEntries;
         if (p.bf16) {
             if (p.pool) hipLaunchKernelGGL(bn_sums_pool_vec_kernel<__bf16>, grid, block, 0, s, p);
             else hipLaunchKernelGGL((bn_sums_vec_kernel<1, __bf16>), grid, block, 0, s, p);
-            if (!p.fold) hipLaunchKernelGGL((bn_finalize_kernel<1, __bf16>), fgrid, block, 0, s, p);
+            hipLaunchKernelGGL((bn_finalize_kernel<1, __bf16>), fgrid, block, 0, s, p);
             if (p.pool) hipLaunchKernelGGL(bn_apply_bwd_pool_vec_kernel<__bf16>, grid, block, 0, s, p);
             else hipLaunchKernelGGL(bn_apply_bwd_vec_kernel<__bf16>, grid, block, 0, s, p);
         } else {
             if (p.pool) hipLaunchKernelGGL(bn_sums_pool_vec_kernel<float>, grid, block, 0, s, p);
             else hipLaunchKernelGGL((bn_sums_vec_kernel<1, float>), grid, block, 0, s, p);
-            if (!p.fold) hipLaunchKernelGGL((bn_finalize_kernel<1, float>), fgrid, block, 0, s, p);
+            hipLaunchKernelGGL((bn_finalize_kernel<1, float>), fgrid, block, 0, s, p);
             if (p.pool) hipLaunchKernelGGL(bn_apply_bwd_pool_vec_kernel<float>, grid, block, 0, s, p);
             else hipLaunchKernelGGL(bn_apply_bwd_vec_kernel<float>, grid, block, 0, s, p);
         }

@@ -164,7 +164,6 @@ struct BnParams {
     // forward: the producing convolution already left per-entry sums of x and x^2 in `partial` ([stat_entries][2][C]); the
     // sums pass is skipped and the shift of the one-pass variance is zero
     int stats_done, stat_entries;
-    int fold;                              // set by the launcher: the apply kernels finalise the partial sums themselves
     float* pool_out; long long pool_out_rep;
     const float* pool_y; long long pool_y_rep;
     const float* pool_g; long long pool_g_rep;
