@@ -49,6 +49,7 @@ public:
     std::vector<int> stat_rows;           // per layer (BN): rows per statistics entry of the latest forward launch
     // bf16 configuration: regular convolution layers keep two bf16 weight matrices (forward / data-gradient order)
     std::vector<char> fast;               // per layer: the lean bf16 kernels apply
+    std::vector<char> fast32;             // per layer (fp32 configuration): lean fp32 forward / data-gradient kernels apply
     std::vector<int64_t> wf_off, wb_off;  // per layer: offsets (bf16 elements) inside one replica's bf16 weight block
     int64_t wbf_rep = 0;                  // bf16 elements per replica
     int64_t wbf_off = 0;                  // start of the bf16 weight region inside `work` (floats)
@@ -82,8 +83,8 @@ struct Layout {
     std::vector<int64_t> act_off, grad_off, saved_off;
     std::vector<int> splits, bn_chunks;
     int64_t rep_block = 0, shared_floats = 0, bn_floats = 0;
-    std::vector<char> fast;
-    std::vector<int64_t> wf_off, wb_off;
+    std::vector<char> fast, fast32;
+    std::vector<int64_t> wf_off, wb_off;       // in 2-byte units inside one replica's block of weight copies
     int64_t wbf_rep = 0;
     std::vector<int64_t> tab_idx;
     int64_t tab_ints = 0;
@@ -133,7 +134,8 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
     }
     L.rep_block = up64(off);
     L.shared_floats = up64(shared);
-    L.fast.assign(plan.layers.size(), 0); L.wf_off.assign(plan.layers.size(), -1); L.wb_off.assign(plan.layers.size(), -1);
+    L.fast.assign(plan.layers.size(), 0); L.fast32.assign(plan.layers.size(), 0);
+    L.wf_off.assign(plan.layers.size(), -1); L.wb_off.assign(plan.layers.size(), -1);
     if (cfg.bf16) {
         int64_t woff = 0;
         for (size_t i = 0; i < plan.layers.size(); ++i) {
@@ -155,12 +157,28 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
             bn_shared = std::max<int64_t>(bn_shared, (int64_t)cfg.n_replicas * ((B * a.h * a.w + 127) / 128) * 2 * a.c);
         }
     }
+    if (!cfg.bf16) {
+        // fp32 configuration: forward and data gradient of the regular layers run in the lean fp32 kernels, which read
+        // K-contiguous fp32 copies of the weights (two floats = four 2-byte units per weight and copy pair)
+        int64_t woff = 0;
+        for (size_t i = 0; i < plan.layers.size(); ++i) {
+            const Layer& l = plan.layers[i];
+            if (l.type != HADFL_OP_CONV || l.in0 == 0) continue;
+            const TensorShape a = plan.tensors[l.in0];
+            if (l.stride != 1 || 2 * l.pad != l.k - 1 || l.k * l.k > 32) continue;
+            if (a.c % 64 != 0 || l.cout % 64 != 0) continue;      // the data gradient swaps the two channel counts
+            L.fast32[i] = 1;
+            L.wf_off[i] = woff; woff += up64(2 * l.w_count);
+            L.wb_off[i] = woff; woff += up64(2 * l.w_count);
+        }
+        L.wbf_rep = woff;
+    }
     L.bn_floats = up64(bn_shared);
     // position tables: worth it for small images (many border pixels), and the weight gradient needs slabs of 32
     // contraction indices to hold a single position
     L.tab_idx.assign(plan.layers.size(), -1);
     for (size_t i = 0; i < plan.layers.size(); ++i) {
-        if (!L.fast[i] || cfg.batch % 32 != 0) continue;
+        if ((!L.fast[i] && !L.fast32[i]) || cfg.batch % 32 != 0) continue;
         const TensorShape a = plan.tensors[plan.layers[i].in0];
         if (a.h * a.w > kMaxTablePositions) continue;
         L.tab_idx[i] = L.tab_ints; L.tab_ints += 2 * (int64_t)a.h * a.w;
@@ -194,7 +212,7 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
     e->rep_block = L.rep_block;
     e->shared_off = L.rep_block * cfg.n_replicas;
     e->shared_floats = L.shared_floats;
-    e->fast = L.fast; e->wf_off = L.wf_off; e->wb_off = L.wb_off; e->wbf_rep = L.wbf_rep;
+    e->fast = L.fast; e->fast32 = L.fast32; e->wf_off = L.wf_off; e->wb_off = L.wb_off; e->wbf_rep = L.wbf_rep;
     e->bn_off = e->shared_off + L.shared_floats;
     e->wbf_off = e->bn_off + L.bn_floats;
     if (const char* h = std::getenv("HADFL_TILE_HINT")) e->tile_hint = std::atoi(h);
@@ -207,9 +225,9 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
             if (l.type != HADFL_OP_CONV && l.type != HADFL_OP_DENSE) continue;
             // in the weight-gradient epilogue (lean kernels, K not split), or in the split-K reduction of a layer whose
             // fp32 weights nothing reads between its weight gradient and the update: the lean layers' data gradients
-            // read the bf16 copies, a layer on the data set has no data gradient
+            // read the bf16 (fp32 configuration: fp32) copies, a layer on the data set has no data gradient
             const bool in_epilogue = e->fast[i] && e->splits[i] == 1;
-            const bool in_reduce = e->splits[i] > 1 && (e->fast[i] || l.in0 == 0);
+            const bool in_reduce = e->splits[i] > 1 && (e->fast[i] || e->fast32[i] || l.in0 == 0);
             if (!in_epilogue && !in_reduce) continue;
             const int64_t cnt = l.w_count + (l.bias ? l.cout : 0);      // bias sits directly behind the weights
             if (l.w_off % 4 != 0 || cnt % 4 != 0 || l.w_off < pos || (l.bias && l.b_off != l.w_off + l.w_count)) continue;
@@ -360,9 +378,20 @@ struct Runner {
         run("weight_prep", 0, 8.0 * l.w_count, [&] { return launch_weight_prep(w, na, s); });
         na = keep_na; cur_layer = keep_layer;
     }
+    float* wcopy32(int64_t off) const { return reinterpret_cast<float*>(wbf() + off); }
     void prepare_weights()
     {
         for (size_t i = 0; i < e.plan.layers.size(); ++i) {
+            if (e.fast32[i]) {                               // fp32 configuration: K-contiguous fp32 copies, every sub-step
+                cur_layer = (int)i;
+                const Layer& l = e.plan.layers[i];
+                WeightPrepF32Params w{};
+                w.w = e.buf.replicas + l.w_off; w.w_rep = e.plan.row_stride;
+                w.wf = wcopy32(e.wf_off[i]); w.wb = wcopy32(e.wb_off[i]); w.wcopy_rep = e.wbf_rep / 2;
+                w.C = e.plan.tensors[l.in0].c; w.N = l.cout; w.taps = l.k * l.k; w.order = e.buf.order;
+                run("weight_prep", 0, 12.0 * l.w_count, [&] { return launch_weight_prep_f32(w, na, s); });
+                continue;
+            }
             if (!e.fast[i]) continue;
             if (e.prepped[i]) { e.prepped[i] = 0; continue; }      // written during the previous sub-step's backward pass
             prep_layer(i, na);
@@ -480,6 +509,19 @@ struct Runner {
                     srows = &e.stat_rows[e.stat_for[i]];
                 }
                 run("conv_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_conv_fast(f, 0, na, s, srows); });
+                break;
+            }
+            if (e.fast32[i]) {
+                FastConvParams f{};
+                f.B = p.B; f.H = p.H; f.W = p.W; f.C = p.Cin; f.N = p.Cout; f.R = p.R; f.S = p.S; f.pad = p.pad;
+                f.M = p.M; f.K = p.K;
+                f.a = act(l.in0); f.a_rep = e.rep_block;
+                f.wmat = reinterpret_cast<const __bf16*>(wcopy32(e.wf_off[i])); f.wmat_rep = e.wbf_rep / 2;
+                f.out = actw(ot); f.out_rep = e.rep_block;
+                f.bias = l.bias ? e.buf.replicas + l.b_off : nullptr; f.bias_rep = e.plan.row_stride;
+                f.relu = p.relu; f.order = e.buf.order; f.tile_hint = e.tile_hint;
+                f.perm = perm(i); f.posmask = posmask(i);
+                run("conv_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_conv_f32_fast(f, 0, na, s); });
                 break;
             }
             if (l.type == HADFL_OP_DENSE && l.cout <= 16 && l.in0 != 0 && !p.relu) {
@@ -652,6 +694,16 @@ struct Runner {
                     f.mask = mask0; f.mask_rep = e.rep_block; f.accumulate = acc0; f.order = e.buf.order; f.tile_hint = e.tile_hint;
                     f.perm = perm(i); f.posmask = posmask(i);
                     run("conv_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return launch_conv_fast(f, 1, na, s); });
+                } else if (e.fast32[i]) {
+                    FastConvParams f{};
+                    f.B = d.B; f.H = d.H; f.W = d.W; f.C = d.Cout; f.N = d.Cin; f.R = d.R; f.S = d.S; f.pad = d.R - 1 - d.pad;
+                    f.M = d.M; f.K = d.K;
+                    f.a = grad(ot); f.a_rep = e.rep_block;
+                    f.wmat = reinterpret_cast<const __bf16*>(wcopy32(e.wb_off[i])); f.wmat_rep = e.wbf_rep / 2;
+                    f.out = grad(l.in0); f.out_rep = e.rep_block;
+                    f.mask = mask0; f.mask_rep = e.rep_block; f.accumulate = acc0; f.order = e.buf.order; f.tile_hint = e.tile_hint;
+                    f.perm = perm(i); f.posmask = posmask(i);
+                    run("conv_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return launch_conv_f32_fast(f, 1, na, s); });
                 } else
                 run(l.type == HADFL_OP_CONV ? "conv_dgrad" : "dense_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return gemm(d); });
             }
@@ -721,7 +773,7 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
     e->prepped.assign(e->plan.layers.size(), 0);       // the weights may have changed since the last call (aggregation)
     for (int step = 0; step < e->e_max && r.rc == hipSuccess; ++step) {
         r.na = e->n_active[step];
-        if (e->cfg.bf16) r.prepare_weights();
+        r.prepare_weights();
         for (size_t i = 0; i < e->plan.layers.size(); ++i) r.forward_layer(i);
         LossParams lp{};
         lp.logits = r.act(T - 1); lp.logits_rep = e->rep_block;

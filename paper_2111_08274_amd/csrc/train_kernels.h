@@ -108,6 +108,17 @@ struct WeightPrepParams {    // fp32 W[tap][C][N] -> bf16 Wf[N][tap*C + ci] and 
 };
 hipError_t launch_weight_prep(const WeightPrepParams& p, int n_active, hipStream_t s);
 
+// fp32 configuration: the same kernel plan in fp32 (conv_f32_fast.hip).  FastConvParams with a, wmat, out, mask pointing at
+// floats (wmat_rep in floats); needs C % 32 == 0, N % 64 == 0; no statistics output.
+hipError_t launch_conv_f32_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s);
+struct WeightPrepF32Params {    // fp32 W[tap][C][N] -> fp32 Wf[N][tap*C + ci] and Wb[C][(taps-1-tap)*N + co]
+    const float* w; long long w_rep;
+    float* wf; float* wb; long long wcopy_rep;
+    int C, N, taps;
+    const int* order;
+};
+hipError_t launch_weight_prep_f32(const WeightPrepF32Params& p, int n_active, hipStream_t s);
+
 struct DenseSmallParams {     // out[m][n] = sum_k x[m][k] w[k][n] + bias[n], N <= 16
     const float* x; long long x_rep;
     const float* w; long long w_rep;     // weights [K][N] followed by bias [N]
