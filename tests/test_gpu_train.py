@@ -208,3 +208,27 @@ def test_resnet18_workload_launch_shape_properties():
         del ctx
         torch.cuda.empty_cache()
     assert np.array_equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("hint", ["0", "1"])
+def test_lean_fp32_kernels_position_sorted_rows(monkeypatch, hint):
+    """fp32 configuration, layers with 64 / 128 channels on 8x8, 4x4 and 2x2 images at batch 32: forward and data gradient
+    run in the lean fp32 kernels with rows ordered by pixel position and out-of-range taps skipped (hint 1: 256-row
+    tiles); bias + ReLU, BN and pooling around them; the weight gradient stays in the generic kernel."""
+    monkeypatch.setenv("HADFL_TILE_HINT", hint)
+    b = nets._Builder()
+    t = b.relu(b.conv(0, 64))
+    t = b.maxpool(b.relu(b.bn(b.conv(t, 64, bias=False))))
+    t = b.maxpool(b.relu(b.conv(t, 128)))
+    t = b.relu(b.conv(t, 128))
+    b.dense(b.gap(t), 5)
+    ops, shape, batch = b.array(), (8, 8, 3), 32
+    N = 3
+    x, y = _data(N, 2 * batch, shape, 5, seed=92)
+    p = Pair(ops, shape, N, 2, x, y, batch, 0.01, 0.9, [2, 1, 1])
+    p.local_steps()
+    d = p.max_param_diff()
+    print("lean fp32 kernels max|dw|", d, "loss", p.gpu.losses(), p.cpu.loss, flush=True)
+    assert d <= TOL
+    assert np.abs(p.gpu.losses() - p.cpu.loss).max() <= 1e-4
+    p.close()
