@@ -363,36 +363,34 @@ struct Runner {
         return e.tab_idx[i] < 0 ? nullptr : reinterpret_cast<const unsigned*>(e.buf.work + e.tab_off) + e.tab_idx[i] + a.h * a.w;
     }
 
-    // bf16 configuration: refresh the bf16 weight matrices of the regular convolution layers from the fp32 master
-    // bf16 copies of layer i's filters (forward layout and flipped/transposed for the data gradient) for the first n
-    // replicas in step order
+    // K-contiguous copies of layer i's filters for the lean kernels (forward layout and flipped/transposed for the data
+    // gradient; bf16, or fp32 in the fp32 configuration), refreshed from the fp32 master for the first n replicas in step
+    // order
     void prep_layer(size_t i, int n)
     {
         const int keep_na = na, keep_layer = cur_layer;
         na = n; cur_layer = (int)i;
         const Layer& l = e.plan.layers[i];
-        WeightPrepParams w{};
-        w.w = e.buf.replicas + l.w_off; w.w_rep = e.plan.row_stride;
-        w.wf = wbf() + e.wf_off[i]; w.wb = wbf() + e.wb_off[i]; w.wbf_rep = e.wbf_rep;
-        w.C = e.plan.tensors[l.in0].c; w.N = l.cout; w.taps = l.k * l.k; w.order = e.buf.order;
-        run("weight_prep", 0, 8.0 * l.w_count, [&] { return launch_weight_prep(w, na, s); });
+        if (e.fast32[i]) {                                   // fp32 configuration: K-contiguous fp32 copies
+            WeightPrepF32Params w{};
+            w.w = e.buf.replicas + l.w_off; w.w_rep = e.plan.row_stride;
+            w.wf = wcopy32(e.wf_off[i]); w.wb = wcopy32(e.wb_off[i]); w.wcopy_rep = e.wbf_rep / 2;
+            w.C = e.plan.tensors[l.in0].c; w.N = l.cout; w.taps = l.k * l.k; w.order = e.buf.order;
+            run("weight_prep", 0, 12.0 * l.w_count, [&] { return launch_weight_prep_f32(w, na, s); });
+        } else {
+            WeightPrepParams w{};
+            w.w = e.buf.replicas + l.w_off; w.w_rep = e.plan.row_stride;
+            w.wf = wbf() + e.wf_off[i]; w.wb = wbf() + e.wb_off[i]; w.wbf_rep = e.wbf_rep;
+            w.C = e.plan.tensors[l.in0].c; w.N = l.cout; w.taps = l.k * l.k; w.order = e.buf.order;
+            run("weight_prep", 0, 8.0 * l.w_count, [&] { return launch_weight_prep(w, na, s); });
+        }
         na = keep_na; cur_layer = keep_layer;
     }
     float* wcopy32(int64_t off) const { return reinterpret_cast<float*>(wbf() + off); }
     void prepare_weights()
     {
         for (size_t i = 0; i < e.plan.layers.size(); ++i) {
-            if (e.fast32[i]) {                               // fp32 configuration: K-contiguous fp32 copies, every sub-step
-                cur_layer = (int)i;
-                const Layer& l = e.plan.layers[i];
-                WeightPrepF32Params w{};
-                w.w = e.buf.replicas + l.w_off; w.w_rep = e.plan.row_stride;
-                w.wf = wcopy32(e.wf_off[i]); w.wb = wcopy32(e.wb_off[i]); w.wcopy_rep = e.wbf_rep / 2;
-                w.C = e.plan.tensors[l.in0].c; w.N = l.cout; w.taps = l.k * l.k; w.order = e.buf.order;
-                run("weight_prep", 0, 12.0 * l.w_count, [&] { return launch_weight_prep_f32(w, na, s); });
-                continue;
-            }
-            if (!e.fast[i]) continue;
+            if (!e.fast[i] && !e.fast32[i]) continue;
             if (e.prepped[i]) { e.prepped[i] = 0; continue; }      // written during the previous sub-step's backward pass
             prep_layer(i, na);
         }
@@ -666,7 +664,10 @@ struct Runner {
                 run("conv_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return launch_wgrad_fast(f, na, s); });
                 if (e.fused_update[i] && na_next > 0) pending_prep = (int)i;
             } else
-            run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return gemm(p); });
+            {
+                run(l.type == HADFL_OP_CONV ? "conv_wgrad" : "dense_wgrad", gemm_flops(p), gemm_bytes(p), [&] { return gemm(p); });
+                if (e.fast32[i] && e.fused_update[i] && na_next > 0) pending_prep = (int)i;
+            }
             if (p.splits > 1 && e.fused_update[i])
                 run("splitk_reduce", 0, 4.0 * mn * (p.splits + 4), [&] {
                     return launch_splitk_reduce_update(shared(), p.out_split, p.splits, e.buf.replicas + l.w_off,
