@@ -156,23 +156,33 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
         __syncthreads();
     }
 
-    if (lane == 0) {
-        // aggregation weights a_k and the ascending list the aggregate kernel walks
-        double denom = 0.0;
-        for (int k = 0; k < N; ++k)
-            if (s_flag[k]) denom += (a.weight_mode == 1) ? s_f[k] : 1.0;
-        int c = 0;
-        for (int k = 0; k < N; ++k) {
+    // aggregation weights a_k and the ascending list the aggregate kernel walks.  The denominator adds the selected
+    // replicas' terms in ascending index, one after another (the same chain as the draws above); everything else is
+    // one element per lane.
+    double denom = 0.0;
+    for (int c = 0; c < chunks; ++c) {
+        const int idx = c * 64 + lane;
+        const double mine = (idx < N && s_flag[idx]) ? ((a.weight_mode == 1) ? s_f[idx] : 1.0) : 0.0;
+        const int lim = min(64, N - c * 64);
+        for (int k = 0; k < lim; ++k) denom = denom + lane_value(mine, k);
+    }
+    int before = 0;                                        // selected replicas in earlier chunks
+    for (int c = 0; c < chunks; ++c) {
+        const int idx = c * 64 + lane;
+        const bool on = idx < N && s_flag[idx];
+        const unsigned long long m = __ballot(on);
+        if (idx < N) {
             float w = 0.f;
-            if (s_flag[k]) {
-                w = (float)(((a.weight_mode == 1) ? s_f[k] : 1.0) / denom);
-                a.sel_sorted[c] = k;
-                a.sel_weight[c] = w;
-                ++c;
+            if (on) {
+                w = (float)(((a.weight_mode == 1) ? s_f[idx] : 1.0) / denom);
+                const int pos = before + __popcll(m & ((1ull << lane) - 1ull));
+                a.sel_sorted[pos] = idx;
+                a.sel_weight[pos] = w;
             }
-            a.flag[k] = s_flag[k];
-            a.weights[k] = w;
+            a.flag[idx] = s_flag[idx];
+            a.weights[idx] = w;
         }
+        before += __popcll(m);
     }
 }
 
