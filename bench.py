@@ -30,9 +30,10 @@ TRAFFIC = {
                                       402288103.0),
     # all weight-gradient launches of a cycle, averaged (the figure includes the fused update's parameter traffic)
     ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
-                                        "paper_2111_08274_amd/csrc/conv_first_bf16.hip"),
-                                       "b9e406a473107cf8a0246c1310e6cb6c7c0e431ba50bbd5542babba1536f27bc",
-                                       547780556.0),
+                                        "paper_2111_08274_amd/csrc/conv_first_bf16.hip",
+                                        "paper_2111_08274_amd/csrc/conv_stats.h"),
+                                       "d78fd9aa4c1e9d65725e24af3a24aa46b63359f9e285fc3cd45236bc0e4960ff",
+                                       547779490.0),
 }
 
 

@@ -13,6 +13,7 @@
 //     with four 16-byte LDS reads (the generic kernel issues one 4-byte read per instruction and operand);
 //   * operands are swapped (C^T = B^T A^T): 4 consecutive output channels per lane, 16-byte stores.
 #include "train_kernels.h"
+#include "conv_stats.h"
 
 namespace hadfl {
 namespace {
@@ -20,6 +21,8 @@ namespace {
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+using conv_stats::store_column_stats;
+using conv_stats::kStatLdsBytes;
 
 // die d (workgroup i runs on die i % 8) takes the consecutive logical items [d * chunk, (d + 1) * chunk)
 constexpr int kDies = 8;
@@ -182,6 +185,12 @@ __global__ __launch_bounds__(WGM * WGN * 64, 2) void conv_f32_kernel(FastConvPar
     float* obase = (float*)p.out + (long long)rep * p.out_rep;
     const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
     const float* mask = (EPI == 1 && p.mask) ? (const float*)p.mask + (long long)rep * p.mask_rep : nullptr;
+    const bool stats = EPI == 0 && p.stat != nullptr;         // per-channel sums of the outputs for a batch norm that follows
+    float ss[TN][16], qq[TN][16];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int k = 0; k < 16; ++k) { ss[j][k] = 0.f; qq[j][k] = 0.f; }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int mm = m0 + wm * (BMT / WGM) + i * 32 + (lane & 31);
@@ -207,8 +216,18 @@ __global__ __launch_bounds__(WGM * WGN * 64, 2) void conv_f32_kernel(FastConvPar
                     if (p.accumulate) v += *reinterpret_cast<const f4*>(obase + o);
                 }
                 *reinterpret_cast<f4*>(obase + o) = v;
+                if (stats) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { ss[j][4 * g + e] += v[e]; qq[j][4 * g + e] += v[e] * v[e]; }
+                }
             }
         }
+    }
+    if (stats) {                                              // (the launcher asks for the larger of the K loop's LDS and kStatLdsBytes)
+        __syncthreads();                                      // every wave is past its last operand read
+        const int slot = (int)(item / (tiles_m * tiles_n));
+        store_column_stats<TN, WGM, WGN>(ss, qq, reinterpret_cast<float*>(smem), wave, lane, p.stat + (long long)slot * p.stat_rep,
+                                         m0 / BMT, n0 + wn * (BN / WGN), p.N);
     }
 }
 
@@ -247,7 +266,8 @@ __global__ __launch_bounds__(256) void weight_prep_f32_kernel(WeightPrepF32Param
 template <int BMT, int BN, int WGM, int WGN>
 void launch_t(const FastConvParams& p, int epi, int n_active, hipStream_t s)
 {
-    constexpr size_t lds = (size_t)(BMT + BN) * 144;
+    constexpr size_t loop_lds = (size_t)(BMT + BN) * 144, stat_lds = kStatLdsBytes<BN / WGN / 32, WGM, WGN>;
+    constexpr size_t lds = loop_lds > stat_lds ? loop_lds : stat_lds;
     const dim3 grid(die_grid((long long)((p.M + BMT - 1) / BMT) * (p.N / BN) * n_active)), block(WGM * WGN * 64);
     if (epi == 0) hipLaunchKernelGGL((conv_f32_kernel<BMT, BN, WGM, WGN, 0>), grid, block, lds, s, p);
     else hipLaunchKernelGGL((conv_f32_kernel<BMT, BN, WGM, WGN, 1>), grid, block, lds, s, p);
@@ -255,15 +275,16 @@ void launch_t(const FastConvParams& p, int epi, int n_active, hipStream_t s)
 
 }  // namespace
 
-hipError_t launch_conv_f32_fast(const FastConvParams& p0, int epi, int n_active, hipStream_t s)
+hipError_t launch_conv_f32_fast(const FastConvParams& p0, int epi, int n_active, hipStream_t s, int* stat_rows)
 {
     if (n_active < 1) return hipSuccess;
     FastConvParams p = p0;
     p.n_active = n_active;
-    if (p.C % 32 != 0 || p.N % 64 != 0 || p.stat) return hipErrorInvalidValue;
+    if (p.C % 32 != 0 || p.N % 64 != 0) return hipErrorInvalidValue;
     // tall tiles halve the weight traffic and double the MFMA work per barrier; use them when they still fill the chip
     const int bn = (p.N % 128 == 0) ? 128 : 64;
     const bool tall = p.tile_hint == 1 || (long long)(p.M / 256) * (p.N / bn) * n_active >= 512;
+    if (stat_rows) *stat_rows = tall ? 256 : 128;             // rows per statistics entry = rows per tile
     if (bn == 128) {
         if (tall) launch_t<256, 128, 2, 2>(p, epi, n_active, s);
         else launch_t<128, 128, 2, 2>(p, epi, n_active, s);

@@ -149,13 +149,6 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
             L.wb_off[i] = woff; woff += up64(l.w_count);
         }
         L.wbf_rep = woff;
-        // a lean convolution in front of a batch norm leaves one statistics entry per 128 output rows (at most)
-        for (size_t k = 0; k < plan.layers.size(); ++k) {
-            const Layer& l = plan.layers[k];
-            if (l.type != HADFL_OP_BN || l.in0 < 1 || !L.fast[l.in0 - 1]) continue;
-            const TensorShape a = plan.tensors[l.in0];
-            bn_shared = std::max<int64_t>(bn_shared, (int64_t)cfg.n_replicas * ((B * a.h * a.w + 127) / 128) * 2 * a.c);
-        }
     }
     if (!cfg.bf16) {
         // fp32 configuration: forward and data gradient of the regular layers run in the lean fp32 kernels, which read
@@ -172,6 +165,13 @@ Layout make_layout(const hadfl_config& cfg, const NetPlan& plan)
             L.wb_off[i] = woff; woff += up64(2 * l.w_count);
         }
         L.wbf_rep = woff;
+    }
+    // a lean convolution in front of a batch norm leaves one statistics entry per 128 output rows (at most)
+    for (size_t k = 0; k < plan.layers.size(); ++k) {
+        const Layer& l = plan.layers[k];
+        if (l.type != HADFL_OP_BN || l.in0 < 1 || (!L.fast[l.in0 - 1] && !L.fast32[l.in0 - 1])) continue;
+        const TensorShape a = plan.tensors[l.in0];
+        bn_shared = std::max<int64_t>(bn_shared, (int64_t)cfg.n_replicas * ((B * a.h * a.w + 127) / 128) * 2 * a.c);
     }
     L.bn_floats = up64(bn_shared);
     // position tables: worth it for small images (many border pixels), and the weight gradient needs slabs of 32
@@ -278,7 +278,7 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
             const Layer& b = plan.layers[k];
             if (b.type != HADFL_OP_BN || b.in0 < 1 || consumers[b.in0] != 1) continue;
             const int i = b.in0 - 1;                        // layer i writes tensor i + 1
-            if (!e->fast[i] || plan.layers[i].type != HADFL_OP_CONV || e->out_tensor[i] != b.in0) continue;
+            if ((!e->fast[i] && !e->fast32[i]) || plan.layers[i].type != HADFL_OP_CONV || e->out_tensor[i] != b.in0) continue;
             e->stat_for[i] = k; e->stat_from[k] = i;
         }
         e->pool_of.assign(nl, -1);
@@ -519,7 +519,12 @@ struct Runner {
                 f.bias = l.bias ? e.buf.replicas + l.b_off : nullptr; f.bias_rep = e.plan.row_stride;
                 f.relu = p.relu; f.order = e.buf.order; f.tile_hint = e.tile_hint;
                 f.perm = perm(i); f.posmask = posmask(i);
-                run("conv_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_conv_f32_fast(f, 0, na, s); });
+                int* srows = nullptr;
+                if (e.stat_for[i] >= 0) {
+                    f.stat = bn_shared(); f.stat_rep = ((int64_t)p.M + 127) / 128 * 2 * p.Cout;
+                    srows = &e.stat_rows[e.stat_for[i]];
+                }
+                run("conv_fwd", gemm_flops(p), gemm_bytes(p), [&] { return launch_conv_f32_fast(f, 0, na, s, srows); });
                 break;
             }
             if (l.type == HADFL_OP_DENSE && l.cout <= 16 && l.in0 != 0 && !p.relu) {

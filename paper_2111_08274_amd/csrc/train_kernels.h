@@ -109,8 +109,8 @@ struct WeightPrepParams {    // fp32 W[tap][C][N] -> bf16 Wf[N][tap*C + ci] and 
 hipError_t launch_weight_prep(const WeightPrepParams& p, int n_active, hipStream_t s);
 
 // fp32 configuration: the same kernel plan in fp32 (conv_f32_fast.hip).  FastConvParams with a, wmat, out, mask pointing at
-// floats (wmat_rep in floats); needs C % 32 == 0, N % 64 == 0; no statistics output.
-hipError_t launch_conv_f32_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s);
+// floats (wmat_rep in floats); needs C % 32 == 0, N % 64 == 0.  stat / stat_rows as in launch_conv_fast.
+hipError_t launch_conv_f32_fast(const FastConvParams& p, int epi, int n_active, hipStream_t s, int* stat_rows = nullptr);
 struct WeightPrepF32Params {    // fp32 W[tap][C][N] -> fp32 Wf[N][tap*C + ci] and Wb[C][(taps-1-tap)*N + co]
     const float* w; long long w_rep;
     float* wf; float* wb; long long wcopy_rep;
