@@ -100,8 +100,9 @@ def time_cycles(fn, steps, warmup):
 
 def cpu_baseline_training(c, data, budget_s=20.0):
     """The oracle as it stands, timed on the same workload's inputs.  Workloads 1-2: whole cycles until about
-    budget_s.  Workloads 3 and 5 (170 / 690 TFLOP of fp64 loops for the full run): a bounded sample -- one local step
-    of a small batch on as many replicas as there are threads."""
+    budget_s.  Workloads 3 and 5 (170 / 690 TFLOP of fp64 loops for the full run): a bounded sample -- ONE local step at
+    the workload's own batch size on as many replicas as the oracle has threads (it parallelises over replicas only),
+    i.e. that many replica-steps of the cycle's sum(E_k); the cycle figure is the extrapolation stated in `sample`."""
     import oracle
     from oracle import nets
     from paper_2111_08274_amd import synth
@@ -113,17 +114,20 @@ def cpu_baseline_training(c, data, budget_s=20.0):
     threads = oracle.lib().hadfl_oracle_num_threads()
     if c in (3, 5):
         n_rep = min(threads, N)
-        small = 16 if c == 3 else 32
-        xs = np.ascontiguousarray(x[:n_rep, :small]).reshape(n_rep, small, -1)
-        ys = np.ascontiguousarray(y[:n_rep, :small])
-        cyc = oracle.Cycle(net, n_rep, 1, w0, xs, ys, small, cfg["lr"], cfg["momentum"], np.ones(n_rep, dtype=np.int32),
+        B = cfg["batch"]
+        xs = np.ascontiguousarray(x[:n_rep, :B]).reshape(n_rep, B, -1)
+        ys = np.ascontiguousarray(y[:n_rep, :B])
+        cyc = oracle.Cycle(net, n_rep, 1, w0, xs, ys, B, cfg["lr"], cfg["momentum"], np.ones(n_rep, dtype=np.int32),
                            seed=synth.SELECT_SEED)
         t0 = time.perf_counter()
         cyc.local_steps()
         el = time.perf_counter() - t0
-        return {"value": n_rep * small / el, "unit": "samples/s", "cores": n_rep, "kind": "oracle",
-                "sample": "one local step of batch %d on %d replicas of workload %d (%d samples) in %.1f s"
-                          % (small, n_rep, c, n_rep * small, el)}
+        ratio = synth.compute_ratios(N, *cfg["ratio_range"], seed=200 + c)
+        steps_per_cycle = int(oracle.step_counts(ratio).sum())
+        return {"value": n_rep * B / el, "unit": "samples/s", "cores": n_rep, "kind": "oracle",
+                "sample": "one local step at the workload's batch %d on %d replicas of workload %d (%d of the cycle's %d "
+                          "replica-steps) in %.1f s; a whole cycle at this rate: %.0f s"
+                          % (B, n_rep, c, n_rep, steps_per_cycle, el, steps_per_cycle * el / n_rep)}
     ratio = cfg["ratio"]
     cyc = oracle.Cycle(net, N, cfg["n_select"], w0, x.reshape(N, x.shape[1], -1), y, cfg["batch"], cfg["lr"],
                        cfg["momentum"], ratio, seed=synth.SELECT_SEED)
@@ -157,6 +161,62 @@ def cpu_baseline_aggregation(cfg, budget_s=15.0):
             "sample": "%d aggregate(s) of 8 x %d fp32 rows in %.1f s" % (done, m, el)}
 
 
+def measure_training(c, steps, warmup, overlap=True):
+    """Times whole cycles of training workload c and, in a separate pass, every kernel class with HIP events on the
+    stream it is launched on.  -> (result dict, data for the CPU baseline)."""
+    from paper_2111_08274_amd import hadfl
+    cfg, ctx, data = build_training(c)
+    if not overlap:
+        ctx.set_option(hadfl.OPT_SIDE_STREAM, 0)
+    samples_per_cycle = int(cfg["batch"] * ctx.steps().sum())
+    def cycle(i):
+        ctx.local_steps()
+        ctx.select(i)
+        ctx.aggregate(resync=True)
+    t_cycle = time_cycles(cycle, steps, warmup)
+    t_local = time_cycles(lambda i: ctx.local_steps(), max(2, steps // 2), 1)
+    ctx.profile(True)
+    n_prof = max(2, min(steps, 10))
+    for i in range(n_prof):
+        cycle(10000 + i)
+    prof = ctx.profile_read()
+    ctx.profile(False)
+    total_ms = sum(v["ms"] for v in prof.values())
+    dom = max(prof, key=lambda n: prof[n]["ms"])
+    kd = prof[dom]
+    avg_ms = kd["ms"] / kd["launches"]
+    dtype = "bf16" if cfg["bf16"] else "f32"
+    if dom in GEMM_KERNELS:
+        ach = kd["flops"] / kd["launches"] / (avg_ms * 1e-3) / 1e12
+        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
+                "frac": ach / MFMA_PEAK_TFLOPS[dtype], "traffic": measured_traffic(dom, cfg["name"])}
+    else:
+        ach = kd["bytes"] / kd["launches"] / (avg_ms * 1e-3) / 1e9
+        roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(dom, cfg["name"])}
+    roof["avg_launch_ms"] = avg_ms
+    roof["overlap"] = ("weight-gradient launches share the chip with the input-gradient and normalisation kernels of "
+                       "the main stream; --no-overlap times each kernel alone") if overlap else "none"
+    roof["share_of_kernel_time"] = kd["ms"] / total_ms
+    gemm_flops = sum(v["flops"] for n, v in prof.items() if n in GEMM_KERNELS) / n_prof
+    res = {"metric": "local-SGD samples/s over all replicas, whole aggregation cycles", "value": samples_per_cycle / t_cycle,
+           "unit": "samples/s", "steps": steps, "warmup": warmup, "ms_per_step": t_cycle * 1e3, "dtype": dtype,
+           "config": {"workload": cfg["name"], "net": cfg["net"], "n_replicas": cfg["n_replicas"],
+                      "n_select": cfg["n_select"], "batch": cfg["batch"], "steps_per_replica": ctx.steps().tolist(),
+                      "samples_per_cycle": samples_per_cycle},
+           "roofline": roof,
+           "local_steps": {"ms_per_cycle": t_local * 1e3, "samples/s": samples_per_cycle / t_local,
+                           "algorithmic_TFLOP_per_cycle": gemm_flops / 1e12,
+                           "mfma_utilisation": gemm_flops / t_local / 1e12 / MFMA_PEAK_TFLOPS[dtype]},
+           "kernels": {n: {"launches_per_cycle": v["launches"] / n_prof, "ms_per_cycle": v["ms"] / n_prof}
+                       for n, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"])}}
+    ctx.close()
+    return res, data
+
+
+DEFAULT_STEPS = {1: (200, 20), 2: (100, 10), 3: (10, 2), 5: (10, 2)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -165,6 +225,8 @@ def main():
     ap.add_argument("--workload", type=int, default=5, choices=[1, 2, 3, 4, 5],
                     help="5 (default): the largest training workload, where the utilisation targets apply")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="skip the short measurements of the other training workloads reported under `workloads`")
     ap.add_argument("--no-overlap", action="store_true",
                     help="launch the weight-gradient kernels on the caller's stream instead of the library's second "
                          "stream: per-kernel durations are then those of each kernel alone on the chip")
@@ -177,8 +239,6 @@ def main():
         sys.exit(2)
     import torch
     from paper_2111_08274_amd import hadfl, synth
-    if args.no_overlap:
-        os.environ["HADFL_SIDE_STREAM"] = "0"          # read by the library when a context is created
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
@@ -210,15 +270,20 @@ def main():
     k = prof["aggregate"]
     agg_ms = k["ms"] / k["launches"]
     agg_gbs = k["bytes"] / k["launches"] / (agg_ms * 1e-3) / 1e9
+    cycle_gbs = (k["bytes"] / k["launches"]) / t_agg / 1e9
     aggregation = {"workload": acfg["name"], "ms_per_cycle": t_agg * 1e3, "kernel_ms": agg_ms,
+                   "select_kernel_ms": prof["select"]["ms"] / prof["select"]["launches"],
                    "algorithmic_bytes": k["bytes"] / k["launches"], "GB/s": agg_gbs, "frac_of_hbm_peak": agg_gbs / HBM_PEAK_GBS,
-                   "mode": "no broadcast: (n_select+1)*4*M bytes"}
+                   "cycle_GB/s": cycle_gbs, "cycle_frac_of_hbm_peak": cycle_gbs / HBM_PEAK_GBS,
+                   "mode": "no broadcast: (n_select+1)*4*M bytes; cycle = select + aggregate, timed end to end"}
     if c == 4:
-        out.update(metric="aggregation HBM GB/s over one select+aggregate cycle", value=(k["bytes"] / k["launches"]) / t_agg / 1e9,
+        out.update(metric="aggregation HBM GB/s over one select+aggregate cycle", value=cycle_gbs,
                    unit="GB/s", steps=a_steps, warmup=a_warm, ms_per_step=t_agg * 1e3, dtype="f32",
                    config={"workload": acfg["name"], "n_replicas": acfg["n_replicas"], "n_select": acfg["n_select"], "m": acfg["m"]})
         out["roofline"] = {"kernel": "aggregate", "bound": "hbm", "achieved": agg_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                           "frac": agg_gbs / HBM_PEAK_GBS, "traffic": measured_traffic("aggregate", acfg["name"])}
+                           "frac": agg_gbs / HBM_PEAK_GBS, "traffic": measured_traffic("aggregate", acfg["name"]),
+                           "avg_launch_ms": agg_ms}
+        out["aggregation"] = aggregation
         if not args.no_cpu_baseline:
             out["cpu_baseline"] = cpu_baseline_aggregation(acfg)
         actx.close()
@@ -229,58 +294,28 @@ def main():
     torch.cuda.empty_cache()
 
     # ---- the training workload: whole cycles ----
-    cfg, ctx, data = build_training(c)
-    steps = args.steps if args.steps else {1: 200, 2: 100, 3: 10, 5: 10}[c]
-    warmup = args.warmup if args.warmup is not None else {1: 20, 2: 10, 3: 2, 5: 2}[c]
-    samples_per_cycle = int(cfg["batch"] * ctx.steps().sum())
-    def cycle(i):
-        ctx.local_steps()
-        ctx.select(i)
-        ctx.aggregate(resync=True)
-    t_cycle = time_cycles(cycle, steps, warmup)
-    t_local = time_cycles(lambda i: ctx.local_steps(), max(2, steps // 2), 1)
-
-    # per-kernel durations from HIP events on the library's stream, a separate pass over the same cycles
-    ctx.profile(True)
-    n_prof = max(2, min(steps, 10))
-    for i in range(n_prof):
-        cycle(10000 + i)
-    prof = ctx.profile_read()
-    ctx.profile(False)
-    total_ms = sum(v["ms"] for v in prof.values())
-    dom = max(prof, key=lambda n: prof[n]["ms"])
-    kd = prof[dom]
-    avg_ms = kd["ms"] / kd["launches"]
-    dtype = "bf16" if cfg["bf16"] else "f32"
-    if dom in GEMM_KERNELS:
-        ach = kd["flops"] / kd["launches"] / (avg_ms * 1e-3) / 1e12
-        roof = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
-                "frac": ach / MFMA_PEAK_TFLOPS[dtype], "traffic": measured_traffic(dom, cfg["name"])}
-    else:
-        ach = kd["bytes"] / kd["launches"] / (avg_ms * 1e-3) / 1e9
-        roof = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": measured_traffic(dom, cfg["name"])}
-    roof["avg_launch_ms"] = avg_ms
-    overlap = os.environ.get("HADFL_SIDE_STREAM", "1") != "0"
-    roof["overlap"] = ("weight-gradient launches share the chip with the input-gradient and normalisation kernels of "
-                       "the main stream; --no-overlap times each kernel alone") if overlap else "none"
-    roof["share_of_kernel_time"] = kd["ms"] / total_ms
-    gemm_flops = sum(v["flops"] for n, v in prof.items() if n in GEMM_KERNELS) / n_prof
-    out.update(metric="local-SGD samples/s over all replicas, whole aggregation cycles", value=samples_per_cycle / t_cycle,
-               unit="samples/s", steps=steps, warmup=warmup, ms_per_step=t_cycle * 1e3, dtype=dtype,
-               config={"workload": cfg["name"], "net": cfg["net"], "n_replicas": cfg["n_replicas"],
-                       "n_select": cfg["n_select"], "batch": cfg["batch"], "steps_per_replica": ctx.steps().tolist(),
-                       "samples_per_cycle": samples_per_cycle})
-    out["roofline"] = roof
-    out["local_steps"] = {"ms_per_cycle": t_local * 1e3, "samples/s": samples_per_cycle / t_local,
-                          "algorithmic_TFLOP_per_cycle": gemm_flops / 1e12,
-                          "mfma_utilisation": gemm_flops / t_local / 1e12 / MFMA_PEAK_TFLOPS[dtype]}
+    steps = args.steps if args.steps else DEFAULT_STEPS[c][0]
+    warmup = args.warmup if args.warmup is not None else DEFAULT_STEPS[c][1]
+    res, data = measure_training(c, steps, warmup, overlap=not args.no_overlap)
+    out.update(res)
     out["aggregation"] = aggregation
-    out["kernels"] = {n: {"launches_per_cycle": v["launches"] / n_prof, "ms_per_cycle": v["ms"] / n_prof}
-                      for n, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"])}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_training(c, data)
-    ctx.close()
+    del data
+    # ---- the other training workloads, shortly: every configuration has a measured line ----
+    if not args.no_others:
+        others = {}
+        for oc in (1, 2, 3, 5):
+            if oc == c:
+                continue
+            torch.cuda.empty_cache()
+            k_steps, k_warm = {1: (50, 5), 2: (30, 5), 3: (5, 2), 5: (5, 2)}[oc]
+            r, _ = measure_training(oc, k_steps, k_warm, overlap=not args.no_overlap)
+            others[r["config"]["workload"]] = {"ms_per_cycle": r["ms_per_step"], "samples/s": r["value"], "dtype": r["dtype"],
+                                               "steps": k_steps, "warmup": k_warm,
+                                               "mfma_utilisation": r["local_steps"]["mfma_utilisation"],
+                                               "roofline": r["roofline"]}
+        out["workloads"] = others
     print(json.dumps(out))
 
 

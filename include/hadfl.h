@@ -15,9 +15,13 @@
  *     call only.  The library owns the host-side context and a few small
  *     pinned staging buffers, nothing else.
  *   - All device work is enqueued on the hipStream_t given at init, in call
- *     order, asynchronously.  Only the hadfl_get_* calls synchronise.
- *   - No global state; several contexts may coexist.  Calls on one context
- *     must not overlap in time.
+ *     order, asynchronously.  The calls that synchronise that stream say so:
+ *     every hadfl_get_* and hadfl_set_params / hadfl_set_momentum /
+ *     hadfl_set_steps (host arrays cross the boundary), hadfl_aggregate_group,
+ *     and hadfl_profile_*.  hadfl_select* with a host mask waits only for the
+ *     selection that last used the same staging slot (two calls back).
+ *   - No global state and no environment variables; several contexts may
+ *     coexist.  Calls on one context must not overlap in time.
  *
  * Data layout
  *   - Activations are channels-last: a batch is [B][H][W][C].
@@ -135,8 +139,8 @@ HADFL_API hadfl_status hadfl_init_replicas(const hadfl_config *cfg, const void *
  * The version of replica k becomes the number of steps it completed in this call.
  * Enqueues on the context's stream and returns without waiting.  Weight-gradient kernels run on a second stream the
  * context owns (default priority), forked from and joined back into the context's stream inside the call, so work
- * enqueued on that stream afterwards is ordered after the whole call.  HADFL_SIDE_STREAM=0 in the environment when the
- * context is created keeps every launch on the context's stream. */
+ * enqueued on that stream afterwards is ordered after the whole call.  hadfl_set_option(HADFL_OPT_SIDE_STREAM, 0)
+ * keeps every launch on the context's stream. */
 HADFL_API hadfl_status hadfl_local_steps(hadfl_ctx *ctx);
 
 /* Sec. 3.3, probability-based selection: mu = third quartile of the available replicas' versions,
@@ -144,9 +148,18 @@ HADFL_API hadfl_status hadfl_local_steps(hadfl_ctx *ctx);
  * proportion to f over those remaining, with uniforms from Philox4x32-10 keyed by cfg.seed at counter
  * (cycle, draw).  The result stays on the device for hadfl_aggregate.
  *   versions_dev  dev, [n_replicas] int32, or NULL for the versions hadfl_local_steps recorded
- *   avail_host    host, [n_replicas] bytes (0 = device absent this round, never selected), or NULL = all
+ *   avail_host    host, [n_replicas] bytes (0 = device absent this round, never selected), or NULL = all; copied
+ *                 during the call into one of two pinned staging slots used in turn, so the call waits (on an event,
+ *                 not on the whole stream) only if the selection two calls back has not started yet
  * Errors: EINVAL if fewer than n_select replicas are available. */
 HADFL_API hadfl_status hadfl_select(hadfl_ctx *ctx, const int32_t *versions_dev, const uint8_t *avail_host, uint64_t cycle);
+
+/* The step-count rule on its own (Sec. 2.3, Sec. 3.3; the rule hadfl_init_replicas applies):
+ *   steps_host[k] = t_sync * steps_per_unit * ratio_host[k] / gcd(ratio_host[0..n)).
+ * Host arrays only; no context and no GPU work.  EINVAL on a null pointer, n < 1, a non-positive ratio, t_sync or
+ * steps_per_unit, or a step count above 2^20. */
+HADFL_API hadfl_status hadfl_step_counts(const int32_t *ratio_host, int32_t n, int32_t t_sync, int32_t steps_per_unit,
+                                         int32_t *steps_host);
 
 /* Sec. 3.2 (mutual-negotiation phase) with Sec. 3.3 (hyperperiod): step counts from measured calculation times.
  * Device k reports the time times_host[k] it needed for e_warmup warm-up units.  Its time per unit,
@@ -211,10 +224,34 @@ HADFL_API hadfl_status hadfl_aggregate_group(hadfl_ctx *ctx, const uint8_t *memb
 /* Read-back; each synchronises the stream.  All outputs are host arrays. */
 HADFL_API hadfl_status hadfl_get_steps(hadfl_ctx *ctx, int32_t *steps /* [n_replicas] E_k */);
 HADFL_API hadfl_status hadfl_get_versions(hadfl_ctx *ctx, int32_t *versions /* [n_replicas] */, int64_t *cursors /* [n_replicas] or NULL */);
-HADFL_API hadfl_status hadfl_get_selected(hadfl_ctx *ctx, int32_t *selected /* [n_select], draw order */,
+/* The last selection: its size to *count (cfg.n_select, or the n_select of the last hadfl_select_group) and its
+ * members in draw order to selected[0..*count); entries of selected beyond that are left untouched.  selected must
+ * have room for cfg.n_select entries; count may be NULL.  ESTATE before the first selection. */
+HADFL_API hadfl_status hadfl_get_selected(hadfl_ctx *ctx, int32_t *selected /* [cfg.n_select] */, int32_t *count,
                                 uint8_t *flag /* [n_replicas] or NULL */, float *weights /* [n_replicas] a_k or NULL */);
 /* replica in [0, n_replicas), or -1 for the last aggregate; n values (<= m_total) in the vector layout */
 HADFL_API hadfl_status hadfl_get_params(hadfl_ctx *ctx, int32_t replica, float *out, size_t n);
+
+/* Sec. 3.1, step 4 (model backup): the model manager fetches the latest model (hadfl_get_params, and
+ * hadfl_get_momentum for the local optimiser state of Sec. 2.2's update with momentum) and can put it back.
+ * hadfl_set_params: the first n values (<= m_total, vector layout) of replica's parameters <- in (host).
+ * hadfl_get_momentum / hadfl_set_momentum: the momentum buffer of replica, n <= m_train values in the order of the
+ * trainable part of the vector; ESTATE when the context trains without momentum or has no trainable network.
+ * replica in [0, n_replicas).  Each synchronises the stream; the next hadfl_local_steps starts from the new state. */
+HADFL_API hadfl_status hadfl_set_params(hadfl_ctx *ctx, int32_t replica, const float *in, size_t n);
+HADFL_API hadfl_status hadfl_get_momentum(hadfl_ctx *ctx, int32_t replica, float *out, size_t n);
+HADFL_API hadfl_status hadfl_set_momentum(hadfl_ctx *ctx, int32_t replica, const float *in, size_t n);
+
+/* Execution options of one context (they change how the work is issued, never a bit of the result):
+ *   HADFL_OPT_SIDE_STREAM  1 (default): weight-gradient kernels of hadfl_local_steps run on a second stream owned by
+ *                          the context; 0: every launch goes to the context's stream
+ *   HADFL_OPT_TILE_HINT    0 (default): tile shapes chosen per launch; 1: the bf16 / fp32 lean convolution kernels take
+ *                          their 256-row tiles wherever the layer shape allows, whatever the launch size; 2: layers on
+ *                          16- and 32-pixel-wide images stay on the general kernels
+ * Takes effect from the next hadfl_local_steps.  EINVAL for an unknown option or value; ESTATE without a
+ * trainable network. */
+typedef enum { HADFL_OPT_SIDE_STREAM = 0, HADFL_OPT_TILE_HINT = 1 } hadfl_option;
+HADFL_API hadfl_status hadfl_set_option(hadfl_ctx *ctx, int32_t option, int32_t value);
 HADFL_API hadfl_status hadfl_get_losses(hadfl_ctx *ctx, float *loss /* [n_replicas] batch-mean loss of each replica's last step */);
 
 /* Per-kernel timing with HIP events on the context's stream.  While enabled, every kernel launch is bracketed

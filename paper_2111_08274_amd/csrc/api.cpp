@@ -33,7 +33,12 @@ struct hadfl_ctx {
     // host state
     std::vector<int32_t> steps, order, bcast_h;
     int last_n_select = 0;           // size of the last selection (cfg.n_select, or a group's)
-    uint8_t* avail_pinned = nullptr;
+    // availability masks cross the boundary through two pinned slots used in turn; ev_slot[i] marks the end of the
+    // copy out of slot i, so refilling a slot waits for that copy alone, not for the stream
+    uint8_t* avail_pinned = nullptr;         // [2][N]
+    hipEvent_t ev_slot[2] = {nullptr, nullptr};
+    bool slot_used[2] = {false, false};
+    int next_slot = 0;
     bool have_selection = false, have_agg = false, have_forecast = false;
     TrainEngine* engine = nullptr;
     Profiler prof;
@@ -118,7 +123,59 @@ hadfl_status hip_fail(hadfl_ctx* ctx, hipError_t e, const char* what)
     return fail(ctx, HADFL_EDEVICE, std::string(what) + ": " + hipGetErrorString(e));
 }
 
+// Nothing may propagate out of a C entry point: a failed host allocation becomes HADFL_ENOMEM.
+template <typename F> hadfl_status guard(hadfl_ctx* ctx, F&& body) noexcept
+{
+    try { return body(); }
+    catch (const std::bad_alloc&) {
+        try { return fail(ctx, HADFL_ENOMEM, "out of host memory"); } catch (...) { return HADFL_ENOMEM; }
+    }
+    catch (...) {
+        try { return fail(ctx, HADFL_ENOMEM, "unexpected host exception"); } catch (...) { return HADFL_ENOMEM; }
+    }
+}
+
 #define HIP_TRY(ctx, expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return hip_fail((ctx), e_, #expr); } while (0)
+
+// one replica's row <-> a dense host vector, segment by segment (the row pads every layer's slice to 256 bytes)
+hadfl_status copy_row(hadfl_ctx* ctx, float* row, float* host, size_t n, bool to_device)
+{
+    for (const NetPlan::Seg& sg : ctx->plan.segs) {
+        if ((size_t)sg.if_off >= n) break;
+        const size_t cnt = std::min<size_t>((size_t)sg.count, n - (size_t)sg.if_off);
+        if (to_device) HIP_TRY(ctx, hipMemcpyAsync(row + sg.row_off, host + sg.if_off, cnt * sizeof(float), hipMemcpyHostToDevice, ctx->stream));
+        else HIP_TRY(ctx, hipMemcpyAsync(host + sg.if_off, row + sg.row_off, cnt * sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
+    }
+    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+    return HADFL_OK;
+}
+
+// E_k = t_sync * steps_per_unit * r_k / gcd(r)  (Sec. 2.3, Sec. 3.3)
+hadfl_status step_counts(const int32_t* ratio, int n, int t_sync, int steps_per_unit, std::vector<int32_t>& steps, std::string& err)
+{
+    if (n < 1 || t_sync < 1 || steps_per_unit < 1) { err = "n, t_sync and steps_per_unit must be positive"; return HADFL_EINVAL; }
+    int64_t g = 0;
+    for (int k = 0; k < n; ++k) {
+        if (ratio[k] <= 0) { err = "computing-power ratios must be positive"; return HADFL_EINVAL; }
+        g = std::gcd<int64_t, int64_t>(g, ratio[k]);
+    }
+    steps.resize((size_t)n);
+    for (int k = 0; k < n; ++k) {
+        const int64_t e = (int64_t)t_sync * steps_per_unit * (ratio[k] / g);
+        if (e > (1 << 20)) { err = "step count above 2^20"; return HADFL_EINVAL; }
+        steps[k] = (int32_t)e;
+    }
+    return HADFL_OK;
+}
+
+hadfl_status momentum_args(hadfl_ctx* ctx, int32_t replica, const void* p, size_t n)
+{
+    if (!ctx || !p) return fail(ctx, HADFL_EINVAL, "null argument");
+    if (!ctx->engine || !ctx->tb.mom) return fail(ctx, HADFL_ESTATE, "this context keeps no momentum buffers");
+    if (replica < 0 || replica >= ctx->cfg.n_replicas) return fail(ctx, HADFL_EINVAL, "replica out of range");
+    if (n > (size_t)ctx->plan.m_train) return fail(ctx, HADFL_EINVAL, "n exceeds m_train");
+    return HADFL_OK;
+}
 
 }  // namespace
 
@@ -162,6 +219,7 @@ extern "C" {
 
 hadfl_status hadfl_param_count(const hadfl_config* cfg, int64_t* m_train, int64_t* m_total, int64_t* row_stride)
 {
+    return guard(nullptr, [&]() -> hadfl_status {
     std::string err;
     hadfl_status st = validate(cfg, err);
     if (st != HADFL_OK) return fail(nullptr, st, err);
@@ -172,10 +230,12 @@ hadfl_status hadfl_param_count(const hadfl_config* cfg, int64_t* m_train, int64_
     if (m_total) *m_total = plan.m_total;
     if (row_stride) *row_stride = plan.row_stride;
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_param_layout(const hadfl_config* cfg, hadfl_tensor_info* out, int32_t cap, int32_t* n)
 {
+    return guard(nullptr, [&]() -> hadfl_status {
     std::string err;
     hadfl_status st = validate(cfg, err);
     if (st != HADFL_OK) return fail(nullptr, st, err);
@@ -208,10 +268,12 @@ hadfl_status hadfl_param_layout(const hadfl_config* cfg, hadfl_tensor_info* out,
     if (out) for (int32_t i = 0; i < cap && i < (int32_t)rows.size(); ++i) out[i] = rows[i];
     *n = (int32_t)rows.size();
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_workspace_bytes(const hadfl_config* cfg, size_t* params_bytes, size_t* scratch_bytes)
 {
+    return guard(nullptr, [&]() -> hadfl_status {
     std::string err;
     hadfl_status st = validate(cfg, err);
     if (st != HADFL_OK) return fail(nullptr, st, err);
@@ -221,12 +283,14 @@ hadfl_status hadfl_workspace_bytes(const hadfl_config* cfg, size_t* params_bytes
     if (params_bytes) *params_bytes = (size_t)cfg->n_replicas * (size_t)plan.row_stride * sizeof(float);
     if (scratch_bytes) *scratch_bytes = carve(*cfg, plan).total;
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_init_replicas(const hadfl_config* cfg, const void* w0_dev, void* replicas_dev, void* scratch_dev,
                                  const void* x_dev, const int32_t* y_dev, const int32_t* ratio_host, void* stream,
                                  hadfl_ctx** out)
 {
+    return guard(nullptr, [&]() -> hadfl_status {
     std::string err;
     hadfl_status st = validate(cfg, err);
     if (st != HADFL_OK) return fail(nullptr, st, err);
@@ -242,28 +306,19 @@ hadfl_status hadfl_init_replicas(const hadfl_config* cfg, const void* w0_dev, vo
 
     hadfl_ctx* ctx = new (std::nothrow) hadfl_ctx();
     if (!ctx) return fail(nullptr, HADFL_ENOMEM, "out of host memory");
+    struct Holder { hadfl_ctx* p; ~Holder() { if (p) hadfl_destroy(p); } } holder{ctx};   // freed on every early return
     ctx->cfg = *cfg;
     if (cfg->net == HADFL_NET_CUSTOM && cfg->custom_ops && cfg->n_custom_ops > 0) {
         ctx->custom.assign(cfg->custom_ops, cfg->custom_ops + cfg->n_custom_ops);
         ctx->cfg.custom_ops = ctx->custom.data();
     }
-    auto bail = [&](hadfl_status s, const std::string& m) { hadfl_destroy(ctx); return fail(nullptr, s, m); };
+    auto bail = [&](hadfl_status s, const std::string& m) { return fail(nullptr, s, m); };
     st = build_plan(ctx->cfg, ctx->plan, err);
     if (st != HADFL_OK) return bail(st, err);
 
-    // step-count rule: E_k = t_sync * steps_per_unit * r_k / gcd(r)
     const int N = cfg->n_replicas;
-    int64_t g = 0;
-    for (int k = 0; k < N; ++k) {
-        if (ratio_host[k] <= 0) return bail(HADFL_EINVAL, "computing-power ratios must be positive");
-        g = std::gcd<int64_t, int64_t>(g, ratio_host[k]);
-    }
-    ctx->steps.resize(N);
-    for (int k = 0; k < N; ++k) {
-        const int64_t e = (int64_t)cfg->t_sync * cfg->steps_per_unit * (ratio_host[k] / g);
-        if (e > (1 << 20)) return bail(HADFL_EINVAL, "step count above 2^20");
-        ctx->steps[k] = (int32_t)e;
-    }
+    st = step_counts(ratio_host, N, cfg->t_sync, cfg->steps_per_unit, ctx->steps, err);
+    if (st != HADFL_OK) return bail(st, err);
     ctx->order.resize(N);
     std::iota(ctx->order.begin(), ctx->order.end(), 0);
     std::stable_sort(ctx->order.begin(), ctx->order.end(), [&](int a, int b) { return ctx->steps[a] > ctx->steps[b]; });
@@ -301,7 +356,9 @@ hadfl_status hadfl_init_replicas(const hadfl_config* cfg, const void* w0_dev, vo
         err = std::string(what) + ": " + hipGetErrorString(e);
         return false;
     };
-    if (!dev(hipHostMalloc((void**)&ctx->avail_pinned, (size_t)N, hipHostMallocDefault), "hipHostMalloc")) return bail(HADFL_EDEVICE, err);
+    if (!dev(hipHostMalloc((void**)&ctx->avail_pinned, 2 * (size_t)N, hipHostMallocDefault), "hipHostMalloc")) return bail(HADFL_EDEVICE, err);
+    for (int i = 0; i < 2; ++i)
+        if (!dev(hipEventCreateWithFlags(&ctx->ev_slot[i], hipEventDisableTiming), "hipEventCreate")) return bail(HADFL_EDEVICE, err);
     // small state: everything after the work area starts at zero (versions, cursors, flags, losses)
     {
         const size_t small_bytes = c.total - c.order;
@@ -327,18 +384,22 @@ hadfl_status hadfl_init_replicas(const hadfl_config* cfg, const void* w0_dev, vo
         st = train_create(ctx->cfg, ctx->plan, ctx->tb, ctx->steps, ctx->order, &ctx->engine, err);
         if (st != HADFL_OK) return bail(st, err);
     }
+    holder.p = nullptr;
     *out = ctx;
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_local_steps(hadfl_ctx* ctx)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
     if (!ctx->engine) return fail(ctx, HADFL_ESTATE, "this context has no trainable network");
     std::string err;
     hadfl_status st = train_run(ctx->engine, ctx->stream, &ctx->prof, err);
     if (st != HADFL_OK) return fail(ctx, st, err);
     return HADFL_OK;
+    });
 }
 
 static hadfl_status select_common(hadfl_ctx* ctx, const int32_t* versions_i32, const double* versions_f64,
@@ -350,10 +411,17 @@ static hadfl_status select_common(hadfl_ctx* ctx, const int32_t* versions_i32, c
         int na = 0;
         for (int k = 0; k < N; ++k) na += avail_host[k] ? 1 : 0;
         if (na < n_select) return fail(ctx, HADFL_EINVAL, "fewer available replicas than n_select");
-        // the pinned staging buffer is reused: wait for the previous copy out of it
-        HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-        for (int k = 0; k < N; ++k) ctx->avail_pinned[k] = avail_host[k] ? 1 : 0;
-        HIP_TRY(ctx, hipMemcpyAsync(ctx->avail_d, ctx->avail_pinned, (size_t)N, hipMemcpyHostToDevice, ctx->stream));
+        // two pinned staging slots used in turn: before refilling one, wait for the copy that last read it
+        const int slot = ctx->next_slot;
+        ctx->next_slot ^= 1;
+        if (ctx->slot_used[slot]) HIP_TRY(ctx, hipEventSynchronize(ctx->ev_slot[slot]));
+        uint8_t* stage = ctx->avail_pinned + (size_t)slot * N;
+        for (int k = 0; k < N; ++k) stage[k] = avail_host[k] ? 1 : 0;
+        // the device copy of the mask is read by the selection kernel of this call and rewritten by the next call's copy,
+        // both on the context's stream, in order
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->avail_d, stage, (size_t)N, hipMemcpyHostToDevice, ctx->stream));
+        HIP_TRY(ctx, hipEventRecord(ctx->ev_slot[slot], ctx->stream));
+        ctx->slot_used[slot] = true;
         avail_d = ctx->avail_d;
     }
     SelectArgs a{};
@@ -375,22 +443,27 @@ static hadfl_status select_common(hadfl_ctx* ctx, const int32_t* versions_i32, c
 
 hadfl_status hadfl_select(hadfl_ctx* ctx, const int32_t* versions_dev, const uint8_t* avail_host, uint64_t cycle)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
     return select_common(ctx, versions_dev ? versions_dev : ctx->tb.versions, nullptr, avail_host, cycle, ctx->cfg.n_select);
+    });
 }
 
 hadfl_status hadfl_select_real(hadfl_ctx* ctx, const double* versions_dev, const uint8_t* avail_host, uint64_t cycle)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
     if (!versions_dev && !ctx->have_forecast)
         return fail(ctx, HADFL_ESTATE, "hadfl_select_real without versions needs a preceding hadfl_predict_versions");
     if (versions_dev && ((uintptr_t)versions_dev & 7)) return fail(ctx, HADFL_EINVAL, "versions_dev must be 8-byte aligned");
     return select_common(ctx, nullptr, versions_dev ? versions_dev : ctx->pred + 2 * (size_t)ctx->cfg.n_replicas, avail_host, cycle,
                          ctx->cfg.n_select);
+    });
 }
 
 hadfl_status hadfl_predict_versions(hadfl_ctx* ctx, const int32_t* versions_dev, double alpha, int32_t horizon)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
     if (!(alpha > 0.0) || !(alpha < 1.0)) return fail(ctx, HADFL_EINVAL, "alpha must be in (0, 1)");
     if (horizon < 0 || horizon > (1 << 20)) return fail(ctx, HADFL_EINVAL, "horizon must be in [0, 2^20]");
@@ -400,21 +473,38 @@ hadfl_status hadfl_predict_versions(hadfl_ctx* ctx, const int32_t* versions_dev,
     if (e != hipSuccess) return hip_fail(ctx, e, "predict kernel");
     ctx->have_forecast = true;
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_get_predicted(hadfl_ctx* ctx, double* predicted)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx || !predicted) return fail(ctx, HADFL_EINVAL, "null argument");
     if (!ctx->have_forecast) return fail(ctx, HADFL_ESTATE, "no forecast yet");
     const size_t N = (size_t)ctx->cfg.n_replicas;
     HIP_TRY(ctx, hipMemcpyAsync(predicted, ctx->pred + 2 * N, sizeof(double) * N, hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     return HADFL_OK;
+    });
+}
+
+hadfl_status hadfl_step_counts(const int32_t* ratio_host, int32_t n, int32_t t_sync, int32_t steps_per_unit, int32_t* steps_host)
+{
+    return guard(nullptr, [&]() -> hadfl_status {
+    if (!ratio_host || !steps_host) return fail(nullptr, HADFL_EINVAL, "null argument");
+    std::vector<int32_t> st;
+    std::string err;
+    const hadfl_status rc = step_counts(ratio_host, n, t_sync, steps_per_unit, st, err);
+    if (rc != HADFL_OK) return fail(nullptr, rc, err);
+    for (int32_t k = 0; k < n; ++k) steps_host[k] = st[k];
+    return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_steps_from_times(const double* times_host, int32_t n, int32_t e_warmup, double quantum, int32_t t_sync,
                                     int32_t steps_per_unit, int32_t* steps_host)
 {
+    return guard(nullptr, [&]() -> hadfl_status {
     if (!times_host || !steps_host) return fail(nullptr, HADFL_EINVAL, "null argument");
     if (n < 1 || e_warmup < 1 || t_sync < 1 || steps_per_unit < 1 || !(quantum > 0.0))
         return fail(nullptr, HADFL_EINVAL, "n, e_warmup, quantum, t_sync and steps_per_unit must be positive");
@@ -437,20 +527,24 @@ hadfl_status hadfl_steps_from_times(const double* times_host, int32_t n, int32_t
     }
     for (int32_t k = 0; k < n; ++k) steps_host[k] = st[k];
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_set_lr(hadfl_ctx* ctx, float lr)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
     if (!ctx->engine) return fail(ctx, HADFL_ESTATE, "this context has no trainable network");
     if (!(lr > 0.f)) return fail(ctx, HADFL_EINVAL, "lr must be positive");
     ctx->cfg.lr = lr;
     train_set_lr(ctx->engine, lr);
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_set_steps(hadfl_ctx* ctx, const int32_t* steps_host)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx || !steps_host) return fail(ctx, HADFL_EINVAL, "null argument");
     const int N = ctx->cfg.n_replicas;
     for (int k = 0; k < N; ++k)
@@ -465,10 +559,12 @@ hadfl_status hadfl_set_steps(hadfl_ctx* ctx, const int32_t* steps_host)
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     if (ctx->engine) train_set_steps(ctx->engine, ctx->steps);
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_aggregate(hadfl_ctx* ctx, int32_t resync)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
     if (!ctx->have_selection) return fail(ctx, HADFL_ESTATE, "hadfl_aggregate needs a preceding hadfl_select");
     // algorithmic traffic: n_select rows read, the aggregate written (+ every replica row written when broadcasting)
@@ -481,18 +577,22 @@ hadfl_status hadfl_aggregate(hadfl_ctx* ctx, int32_t resync)
     if (e != hipSuccess) return hip_fail(ctx, e, "aggregate kernel");
     ctx->have_agg = true;
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_select_group(hadfl_ctx* ctx, const int32_t* versions_dev, const uint8_t* member_host, int32_t n_select,
                                 uint64_t cycle)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx || !member_host) return fail(ctx, HADFL_EINVAL, "null argument");
     if (n_select < 1 || n_select > ctx->cfg.n_select) return fail(ctx, HADFL_EINVAL, "n_select must be in [1, cfg.n_select]");
     return select_common(ctx, versions_dev ? versions_dev : ctx->tb.versions, nullptr, member_host, cycle, n_select);
+    });
 }
 
 hadfl_status hadfl_aggregate_group(hadfl_ctx* ctx, const uint8_t* member_host)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx || !member_host) return fail(ctx, HADFL_EINVAL, "null argument");
     if (!ctx->have_selection) return fail(ctx, HADFL_ESTATE, "hadfl_aggregate_group needs a preceding selection");
     const int N = ctx->cfg.n_replicas;
@@ -511,74 +611,131 @@ hadfl_status hadfl_aggregate_group(hadfl_ctx* ctx, const uint8_t* member_host)
     if (e != hipSuccess) return hip_fail(ctx, e, "aggregate kernel");
     ctx->have_agg = true;
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_get_steps(hadfl_ctx* ctx, int32_t* steps)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx || !steps) return fail(ctx, HADFL_EINVAL, "null argument");
     HIP_TRY(ctx, hipMemcpyAsync(steps, ctx->steps_d, sizeof(int32_t) * ctx->cfg.n_replicas, hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_get_versions(hadfl_ctx* ctx, int32_t* versions, int64_t* cursors)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx || !versions) return fail(ctx, HADFL_EINVAL, "null argument");
     const size_t N = (size_t)ctx->cfg.n_replicas;
     HIP_TRY(ctx, hipMemcpyAsync(versions, ctx->tb.versions, sizeof(int32_t) * N, hipMemcpyDeviceToHost, ctx->stream));
     if (cursors) HIP_TRY(ctx, hipMemcpyAsync(cursors, ctx->tb.cursor, sizeof(int64_t) * N, hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     return HADFL_OK;
+    });
 }
 
-hadfl_status hadfl_get_selected(hadfl_ctx* ctx, int32_t* selected, uint8_t* flag, float* weights)
+hadfl_status hadfl_get_selected(hadfl_ctx* ctx, int32_t* selected, int32_t* count, uint8_t* flag, float* weights)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx || !selected) return fail(ctx, HADFL_EINVAL, "null argument");
     if (!ctx->have_selection) return fail(ctx, HADFL_ESTATE, "no selection yet");
     const size_t N = (size_t)ctx->cfg.n_replicas;
-    HIP_TRY(ctx, hipMemcpyAsync(selected, ctx->selected, sizeof(int32_t) * ctx->cfg.n_select, hipMemcpyDeviceToHost, ctx->stream));
+    HIP_TRY(ctx, hipMemcpyAsync(selected, ctx->selected, sizeof(int32_t) * ctx->last_n_select, hipMemcpyDeviceToHost, ctx->stream));
+    if (count) *count = ctx->last_n_select;
     if (flag) HIP_TRY(ctx, hipMemcpyAsync(flag, ctx->flag, N, hipMemcpyDeviceToHost, ctx->stream));
     if (weights) HIP_TRY(ctx, hipMemcpyAsync(weights, ctx->weights, sizeof(float) * N, hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_get_params(hadfl_ctx* ctx, int32_t replica, float* out, size_t n)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx || !out) return fail(ctx, HADFL_EINVAL, "null argument");
     if (replica < -1 || replica >= ctx->cfg.n_replicas) return fail(ctx, HADFL_EINVAL, "replica out of range");
     if (n > (size_t)ctx->plan.m_total) return fail(ctx, HADFL_EINVAL, "n exceeds m_total");
     if (replica == -1 && !ctx->have_agg) return fail(ctx, HADFL_ESTATE, "no aggregate yet");
-    const float* row = replica < 0 ? ctx->agg : ctx->replicas + (size_t)replica * ctx->plan.row_stride;
-    for (const NetPlan::Seg& sg : ctx->plan.segs) {
-        if ((size_t)sg.if_off >= n) break;
-        const size_t cnt = std::min<size_t>((size_t)sg.count, n - (size_t)sg.if_off);
-        HIP_TRY(ctx, hipMemcpyAsync(out + sg.if_off, row + sg.row_off, cnt * sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
+    float* row = replica < 0 ? ctx->agg : ctx->replicas + (size_t)replica * ctx->plan.row_stride;
+    return copy_row(ctx, row, out, n, false);
+    });
+}
+
+hadfl_status hadfl_set_params(hadfl_ctx* ctx, int32_t replica, const float* in, size_t n)
+{
+    return guard(ctx, [&]() -> hadfl_status {
+    if (!ctx || !in) return fail(ctx, HADFL_EINVAL, "null argument");
+    if (replica < 0 || replica >= ctx->cfg.n_replicas) return fail(ctx, HADFL_EINVAL, "replica out of range");
+    if (n > (size_t)ctx->plan.m_total) return fail(ctx, HADFL_EINVAL, "n exceeds m_total");
+    return copy_row(ctx, ctx->replicas + (size_t)replica * ctx->plan.row_stride, const_cast<float*>(in), n, true);
+    });
+}
+
+hadfl_status hadfl_get_momentum(hadfl_ctx* ctx, int32_t replica, float* out, size_t n)
+{
+    return guard(ctx, [&]() -> hadfl_status {
+    const hadfl_status st = momentum_args(ctx, replica, out, n);
+    if (st != HADFL_OK) return st;
+    return copy_row(ctx, ctx->tb.mom + (size_t)replica * ctx->plan.row_stride, out, n, false);
+    });
+}
+
+hadfl_status hadfl_set_momentum(hadfl_ctx* ctx, int32_t replica, const float* in, size_t n)
+{
+    return guard(ctx, [&]() -> hadfl_status {
+    const hadfl_status st = momentum_args(ctx, replica, in, n);
+    if (st != HADFL_OK) return st;
+    return copy_row(ctx, ctx->tb.mom + (size_t)replica * ctx->plan.row_stride, const_cast<float*>(in), n, true);
+    });
+}
+
+hadfl_status hadfl_set_option(hadfl_ctx* ctx, int32_t option, int32_t value)
+{
+    return guard(ctx, [&]() -> hadfl_status {
+    if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
+    if (!ctx->engine) return fail(ctx, HADFL_ESTATE, "this context has no trainable network");
+    switch (option) {
+    case HADFL_OPT_SIDE_STREAM:
+        if (value != 0 && value != 1) return fail(ctx, HADFL_EINVAL, "HADFL_OPT_SIDE_STREAM takes 0 or 1");
+        train_set_side_stream(ctx->engine, value != 0);
+        return HADFL_OK;
+    case HADFL_OPT_TILE_HINT:
+        if (value < 0 || value > 2) return fail(ctx, HADFL_EINVAL, "HADFL_OPT_TILE_HINT takes 0, 1 or 2");
+        train_set_tile_hint(ctx->engine, value);
+        return HADFL_OK;
+    default:
+        return fail(ctx, HADFL_EINVAL, "unknown option");
     }
-    HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
-    return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_get_losses(hadfl_ctx* ctx, float* loss)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx || !loss) return fail(ctx, HADFL_EINVAL, "null argument");
     HIP_TRY(ctx, hipMemcpyAsync(loss, ctx->tb.loss, sizeof(float) * ctx->cfg.n_replicas, hipMemcpyDeviceToHost, ctx->stream));
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_profile_enable(hadfl_ctx* ctx, int32_t on)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx) return fail(nullptr, HADFL_EINVAL, "ctx is null");
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     ctx->prof.clear();
     ctx->prof.on = on != 0;
     ctx->prof.detail = on == 2;
     return HADFL_OK;
+    });
 }
 
 hadfl_status hadfl_profile_read(hadfl_ctx* ctx, hadfl_kernel_time* out, int32_t cap, int32_t* n)
 {
+    return guard(ctx, [&]() -> hadfl_status {
     if (!ctx || !n) return fail(ctx, HADFL_EINVAL, "null argument");
     HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
     std::vector<hadfl_kernel_time> rows;
@@ -601,6 +758,7 @@ hadfl_status hadfl_profile_read(hadfl_ctx* ctx, hadfl_kernel_time* out, int32_t 
     *n = (int32_t)rows.size();
     ctx->prof.clear();
     return HADFL_OK;
+    });
 }
 
 const char* hadfl_last_error(const hadfl_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
@@ -608,9 +766,10 @@ const char* hadfl_last_error(const hadfl_ctx* ctx) { return ctx ? ctx->err.c_str
 void hadfl_destroy(hadfl_ctx* ctx)
 {
     if (!ctx) return;
-    if (ctx->stream || true) (void)hipStreamSynchronize(ctx->stream);
+    (void)hipStreamSynchronize(ctx->stream);          // a null handle is the default stream
     if (ctx->engine) train_destroy(ctx->engine);
     if (ctx->avail_pinned) (void)hipHostFree(ctx->avail_pinned);
+    for (hipEvent_t ev : ctx->ev_slot) if (ev) (void)hipEventDestroy(ev);
     delete ctx;
 }
 

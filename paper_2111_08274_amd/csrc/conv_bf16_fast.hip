@@ -219,7 +219,10 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
     char* obase = (char*)p.out + (long long)rep * p.out_rep * 4;
     const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
     const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
-    const bool stats = EPI == 0 && p.stat != nullptr;
+    const bool stats = p.stat != nullptr;
+    // data gradient with statistics: values of the tensor whose gradient this is (see FastConvParams::stat_y)
+    const char* ysrc = (EPI == 1 && stats) ? (const char*)p.stat_y + (long long)rep * p.stat_y_rep * 4 : nullptr;
+    const bool y_is_mask = mask != nullptr && ysrc == mask;
     float ss[TN][16], qq[TN][16];
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -238,12 +241,13 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
                 const int n = n0 + wn * (BN / WGN) + j * 32 + 8 * g + 4 * (lane >> 5);
                 const unsigned o = (unsigned)(pix * p.N + n) * 2u;
                 f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                bf16x4 mk = {};
                 if (EPI == 0) {
                     if (bias) v += *reinterpret_cast<const f4*>(bias + n);
                     if (p.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
                 } else {
                     if (mask) {
-                        const bf16x4 mk = *reinterpret_cast<const bf16x4*>(mask + o);
+                        mk = *reinterpret_cast<const bf16x4*>(mask + o);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) if (!((float)mk[e] > 0.f)) v[e] = 0.f;
                     }
@@ -258,8 +262,19 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
                 for (int e = 0; e < 4; ++e) r[e] = (__bf16)v[e];
                 *reinterpret_cast<bf16x4*>(obase + o) = r;
                 if (stats) {
+                    if (EPI == 0) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { const float f = (float)r[e]; ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * f; }
+                        for (int e = 0; e < 4; ++e) { const float f = (float)r[e]; ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * f; }
+                    } else {
+                        // the mask of a fused ReLU is that very tensor: its values are already here
+                        const bf16x4 yv = y_is_mask ? mk : *reinterpret_cast<const bf16x4*>(ysrc + o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float yy = (float)yv[e];
+                            const float f = (p.stat_relu && !(yy > 0.f)) ? 0.f : (float)r[e];
+                            ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * yy;
+                        }
+                    }
                 }
             }
         }
@@ -406,7 +421,10 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
     char* obase = (char*)p.out + (long long)rep * p.out_rep * 4;
     const float* bias = (EPI == 0 && p.bias) ? p.bias + (long long)rep * p.bias_rep : nullptr;
     const char* mask = (EPI == 1 && p.mask) ? (const char*)p.mask + (long long)rep * p.mask_rep * 4 : nullptr;
-    const bool stats = EPI == 0 && p.stat != nullptr;
+    const bool stats = p.stat != nullptr;
+    // data gradient with statistics: values of the tensor whose gradient this is (see FastConvParams::stat_y)
+    const char* ysrc = (EPI == 1 && stats) ? (const char*)p.stat_y + (long long)rep * p.stat_y_rep * 4 : nullptr;
+    const bool y_is_mask = mask != nullptr && ysrc == mask;
     float ss[TN][16], qq[TN][16];
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -422,12 +440,13 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
                 const int n = n0 + wn * (BN / WGN) + j * 32 + 8 * g + 4 * (lane >> 5);
                 const unsigned o = (unsigned)(mm * p.N + n) * 2u;
                 f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                bf16x4 mk = {};
                 if (EPI == 0) {
                     if (bias) v += *reinterpret_cast<const f4*>(bias + n);
                     if (p.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
                 } else {
                     if (mask) {
-                        const bf16x4 mk = *reinterpret_cast<const bf16x4*>(mask + o);
+                        mk = *reinterpret_cast<const bf16x4*>(mask + o);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) if (!((float)mk[e] > 0.f)) v[e] = 0.f;
                     }
@@ -442,8 +461,19 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
                 for (int e = 0; e < 4; ++e) r[e] = (__bf16)v[e];
                 *reinterpret_cast<bf16x4*>(obase + o) = r;
                 if (stats) {
+                    if (EPI == 0) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { const float f = (float)r[e]; ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * f; }
+                        for (int e = 0; e < 4; ++e) { const float f = (float)r[e]; ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * f; }
+                    } else {
+                        // the mask of a fused ReLU is that very tensor: its values are already here
+                        const bf16x4 yv = y_is_mask ? mk : *reinterpret_cast<const bf16x4*>(ysrc + o);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float yy = (float)yv[e];
+                            const float f = (p.stat_relu && !(yy > 0.f)) ? 0.f : (float)r[e];
+                            ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * yy;
+                        }
+                    }
                 }
             }
         }

@@ -6,6 +6,7 @@
 namespace hadfl {
 namespace {
 
+constexpr float kBwdStatCond = 16.f;    // largest |beta / gamma| for which y determines xhat well enough (bn_finalize_kernel)
 constexpr float kBnEps = 1e-5f;
 constexpr float kBnStatMomentum = 0.1f;
 
@@ -505,6 +506,19 @@ __global__ __launch_bounds__(256) void bn_sums_vec_kernel(BnParams p)
     }
 }
 
+struct PoolWin { long long q[4]; long long o; };
+__device__ __forceinline__ PoolWin pool_window(const BnParams& p, int w, int c)
+{
+    const int Wo = p.W / 2, Ho = p.H / 2;
+    const int xo = w % Wo; int t = w / Wo;
+    const int yo = t % Ho, b = t / Ho;
+    PoolWin r;
+    r.q[0] = (((long long)b * p.H + 2 * yo) * p.W + 2 * xo) * p.C + c;
+    r.q[1] = r.q[0] + p.C; r.q[2] = r.q[0] + (long long)p.W * p.C; r.q[3] = r.q[2] + p.C;
+    r.o = (long long)w * p.C + c;
+    return r;
+}
+
 // A workgroup takes 32 channels; eight threads per channel add the per-chunk partial sums (chunks k, k+8, ..) and a
 // fixed-order tree over the eight joins them.
 // MODE 0: mean and 1/sqrt(var+eps) -> saved, running statistics updated.  x0 is the shift used by the sums pass.
@@ -518,9 +532,64 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(BnParams p)
     const int c = blockIdx.x * 32 + cl;
     const bool live = c < p.C;
     float* part = p.partial + gi * p.partial_rep;
-    const int nk = (MODE == 0 && p.stats_done) ? p.stat_entries : p.chunks;
+    const int nk = ((MODE == 0 && p.stats_done) || (MODE == 1 && p.bwd_stats_done)) ? p.stat_entries : p.chunks;
     float s = 0.f, q = 0.f;
-    if (live)
+    // Backward sums left by the data gradient above are s = sum g and q = sum g * y, y = gamma * xhat + beta the stored
+    // (bf16) output, so that  sum g * xhat = (q - beta * s) / gamma.  The bf16 rounding of y enters xhat multiplied by
+    // |y / gamma| <= |xhat| + |beta / gamma|: harmless while |beta| <= kBwdStatCond * |gamma| (every trained net's
+    // case; the rounding errors of the terms are independent and average out in the sum), useless when gamma is zero
+    // or tiny beside beta.  Channels outside that range are summed again from x and the gradient, exactly as the sums
+    // kernels do, by the whole workgroup, one channel after the other (slow, and rare).
+    float gamma = 1.f, beta = 0.f;
+    bool direct = false;
+    if (MODE == 1) {
+        __shared__ int s_direct[32];
+        __shared__ float s_sum[32][2];
+        __shared__ float s_red[256][2];
+        if (p.bwd_stats_done && live) {
+            const float* row = p.params + rep * p.row_stride + p.w_off;
+            gamma = row[c]; beta = row[p.C + c];
+            direct = gamma == 0.f || !(fabsf(beta) <= kBwdStatCond * fabsf(gamma));
+        }
+        if (kl == 0) s_direct[cl] = direct ? 1 : 0;
+        __syncthreads();
+        for (int j = 0; j < 32; ++j) {
+            if (!s_direct[j]) continue;                       // uniform over the workgroup
+            const int cj = blockIdx.x * 32 + j;
+            const T* x = tptr<T>(p.x, rep, p.x_rep);
+            const float* sv = p.saved + rep * p.saved_rep;
+            const float mean = sv[cj], istd = sv[p.C + cj];
+            float ts = 0.f, tq = 0.f;
+            if (!p.pool) {
+                const T* dy = tptr<T>(p.dy, rep, p.dy_rep);
+                for (int r = threadIdx.x; r < p.rows; r += 256) {
+                    const float d = ldf(dy, (long long)r * p.C + cj);
+                    ts += d; tq += d * ((ldf(x, (long long)r * p.C + cj) - mean) * istd);
+                }
+            } else {
+                const T* yo = tptr<T>(p.pool_y, rep, p.pool_y_rep);
+                const T* pg = tptr<T>(p.pool_g, rep, p.pool_g_rep);
+                for (int w = threadIdx.x; w < p.rows / 4; w += 256) {
+                    const PoolWin pw = pool_window(p, w, cj);
+                    float m = ldf(yo, pw.q[0]); int arg = 0;
+                    for (int t = 1; t < 4; ++t) { const float v = ldf(yo, pw.q[t]); if (v > m) { m = v; arg = t; } }   // first maximum
+                    if (p.relu && !(m > 0.f)) continue;       // the fused ReLU passes nothing there
+                    const float d = ldf(pg, pw.o);
+                    ts += d; tq += d * ((ldf(x, pw.q[arg]) - mean) * istd);
+                }
+            }
+            s_red[threadIdx.x][0] = ts; s_red[threadIdx.x][1] = tq;
+            __syncthreads();
+            for (int w = 128; w > 0; w >>= 1) {               // fixed-order tree
+                if ((int)threadIdx.x < w) { s_red[threadIdx.x][0] += s_red[threadIdx.x + w][0]; s_red[threadIdx.x][1] += s_red[threadIdx.x + w][1]; }
+                __syncthreads();
+            }
+            if (threadIdx.x == 0) { s_sum[j][0] = s_red[0][0]; s_sum[j][1] = s_red[0][1]; }
+            __syncthreads();
+        }
+        if (direct && kl == 0) { s = s_sum[cl][0]; q = s_sum[cl][1]; }
+    }
+    if (live && !direct)
         for (int k = kl; k < nk; k += 8) { s += part[(long long)k * 2 * p.C + c]; q += part[(long long)k * 2 * p.C + p.C + c]; }
     red[kl][cl][0] = s; red[kl][cl][1] = q;
     __syncthreads();
@@ -543,6 +612,7 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(BnParams p)
         rm[c] = (1.f - kBnStatMomentum) * rm[c] + kBnStatMomentum * mean;
         rm[p.C + c] = (1.f - kBnStatMomentum) * rm[p.C + c] + kBnStatMomentum * unb;
     } else {
+        if (p.bwd_stats_done && !direct) q = (q - beta * s) / gamma;
         float* gr = p.grads + rep * p.row_stride + p.w_off;
         gr[c] = q; gr[p.C + c] = s;
         part[c] = s; part[p.C + c] = q;
@@ -635,19 +705,6 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_vec_kernel(BnParams p)
 // is formed on the fly from the stored output and the pooled gradient, so the full-resolution gradient tensor is
 // neither written nor read (two passes less).  Window w of chunk c: [c * chunk_windows, (c + 1) * chunk_windows).
 // ------------------------------------------------------------------------------------------------------
-struct PoolWin { long long q[4]; long long o; };
-__device__ __forceinline__ PoolWin pool_window(const BnParams& p, int w, int c)
-{
-    const int Wo = p.W / 2, Ho = p.H / 2;
-    const int xo = w % Wo; int t = w / Wo;
-    const int yo = t % Ho, b = t / Ho;
-    PoolWin r;
-    r.q[0] = (((long long)b * p.H + 2 * yo) * p.W + 2 * xo) * p.C + c;
-    r.q[1] = r.q[0] + p.C; r.q[2] = r.q[0] + (long long)p.W * p.C; r.q[3] = r.q[2] + p.C;
-    r.o = (long long)w * p.C + c;
-    return r;
-}
-
 template <typename T>
 __global__ __launch_bounds__(256) void bn_apply_fwd_pool_vec_kernel(BnParams p)
 {
@@ -1035,12 +1092,14 @@ hipError_t launch_bn_bwd(const BnParams& p0, int n_active, hipStream_t s)
         const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 31) / 32), (unsigned)n_active);
         if (p.pool && (p.H % 2 != 0 || p.W % 2 != 0 || p.rows % 4 != 0 || !p.pool_y || !p.pool_g)) return hipErrorInvalidValue;
         if (p.bf16) {
-            if (p.pool) hipLaunchKernelGGL(bn_sums_pool_vec_kernel<__bf16>, grid, block, 0, s, p);
+            if (p.bwd_stats_done) {}                                  // the data gradient above left the sums
+            else if (p.pool) hipLaunchKernelGGL(bn_sums_pool_vec_kernel<__bf16>, grid, block, 0, s, p);
             else hipLaunchKernelGGL((bn_sums_vec_kernel<1, __bf16>), grid, block, 0, s, p);
             hipLaunchKernelGGL((bn_finalize_kernel<1, __bf16>), fgrid, block, 0, s, p);
             if (p.pool) hipLaunchKernelGGL(bn_apply_bwd_pool_vec_kernel<__bf16>, grid, block, 0, s, p);
             else hipLaunchKernelGGL(bn_apply_bwd_vec_kernel<__bf16>, grid, block, 0, s, p);
         } else {
+            if (p.bwd_stats_done) return hipErrorInvalidValue;       // only the bf16 data-gradient kernels leave them
             if (p.pool) hipLaunchKernelGGL(bn_sums_pool_vec_kernel<float>, grid, block, 0, s, p);
             else hipLaunchKernelGGL((bn_sums_vec_kernel<1, float>), grid, block, 0, s, p);
             hipLaunchKernelGGL((bn_finalize_kernel<1, float>), fgrid, block, 0, s, p);
@@ -1049,7 +1108,7 @@ hipError_t launch_bn_bwd(const BnParams& p0, int n_active, hipStream_t s)
         }
         return hipGetLastError();
     }
-    if (p.pool) return hipErrorInvalidValue;
+    if (p.pool || p.bwd_stats_done) return hipErrorInvalidValue;
     const dim3 grid((unsigned)(p.chunks * ((p.C + 63) / 64)), (unsigned)n_active);
     if (p.bf16) {
         hipLaunchKernelGGL((bn_reduce_kernel<2, __bf16>), grid, block, 0, s, p);

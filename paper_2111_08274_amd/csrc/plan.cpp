@@ -106,6 +106,11 @@ hadfl_status build_plan(const hadfl_config& cfg, NetPlan& plan, std::string& err
     for (size_t i = 0; i < plan.layers.size(); ++i) {
         Layer& l = plan.layers[i];
         if (l.in0 < 0 || l.in0 >= l.out) { err = "layer input must be an earlier tensor"; return HADFL_EINVAL; }
+        // tensor 0 is the batch inside the data set, addressed through the replica's batch cursor: only the layers
+        // that form GEMM operands from it know how to read it
+        if ((l.in0 == 0 && l.type != HADFL_OP_CONV && l.type != HADFL_OP_DENSE) || (l.type == HADFL_OP_ADD && l.in1 == 0)) {
+            err = "only a convolution or dense layer may read the input batch"; return HADFL_EUNSUPPORTED;
+        }
         const TensorShape a = plan.tensors[l.in0];
         TensorShape r = a;
         switch (l.type) {

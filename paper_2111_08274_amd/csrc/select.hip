@@ -53,11 +53,19 @@ template <> __device__ __forceinline__ const int* versions_of<int>(const SelectA
 template <> __device__ __forceinline__ const double* versions_of<double>(const SelectArgs& a) { return a.versions_f64; }
 
 // V = int: versions are step counters; V = double: forecast (real-valued) versions (Sec. 3.2 feeding Sec. 3.3)
+//
+// What is serial in the rule and what is not.  The draws are sequential (draw t renormalises over the replicas that
+// remain), and within a draw the total S and the running sums add f in ascending replica index, one rounded fp64
+// addition after another: a chain of N dependent additions per draw that no reordering may touch, because the result
+// is compared bit for bit.  Everything else is taken off that chain: the uniforms of all draws are computed up
+// front (one Philox block per lane), f is computed once, and inside a chunk of 64 replicas the chain is a fully
+// unrolled run of v_add_f64 whose operands (cross-lane reads of the lanes' own values) do not depend on the chain.
 template <typename V>
 __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
 {
     __shared__ double s_sorted[kMaxReplicas];
     __shared__ double s_f[kMaxReplicas];
+    __shared__ double s_u[kMaxReplicas];
     __shared__ unsigned char s_flag[kMaxReplicas];
     __shared__ V s_v[kMaxReplicas];
     __shared__ unsigned char s_av[kMaxReplicas];
@@ -71,6 +79,13 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
         s_v[i] = versions_of<V>(a)[i];
         s_av[i] = (!a.avail || a.avail[i]) ? 1 : 0;
         s_flag[i] = 0;
+    }
+    // the uniform of every draw: counter (cycle_lo, cycle_hi, draw, 0), key = seed, 53 bits of the first two words
+    for (int t = lane; t < a.n_select; t += 64) {
+        const U4 o = philox4x32_10(U4{(uint32_t)a.cycle, (uint32_t)(a.cycle >> 32), (uint32_t)t, 0u},
+                                   (uint32_t)a.seed, (uint32_t)(a.seed >> 32));
+        const unsigned long long bits = ((unsigned long long)o.y << 32) | o.x;
+        s_u[t] = (double)(bits >> 11) * 0x1.0p-53;
     }
     __syncthreads();
     int na = 0;
@@ -116,31 +131,28 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
     }
     __syncthreads();
 
-    // Sequential draws.  The running sum must add f in ascending replica index, one value after another.  The
-    // wavefront walks the replicas in chunks of 64: every lane loads its own value once (one LDS latency per chunk),
-    // then all lanes step through the chunk together with cross-lane reads, and lane k keeps the running sum after
-    // element k.  The total S is the last running sum; the pick is the first live element whose running sum exceeds
-    // u*S, found with one compare and a ballot.  Dead elements add +0.0, which leaves a non-negative sum unchanged.
+    // Sequential draws.  The wavefront walks the replicas in chunks of 64: every lane loads its own value once, then
+    // all lanes step through the chunk together, and lane k keeps the running sum after element k.  The total S is the
+    // last running sum; the pick is the first live element whose running sum exceeds u*S, found with one compare and a
+    // ballot.  Dead elements (picked, unavailable, or beyond N) add +0.0, which leaves a non-negative sum unchanged, so
+    // every chunk runs all 64 additions with no bound to test.
+    int n_picked = 0;
     for (int t = 0; t < a.n_select; ++t) {
         double run = 0.0;
         for (int c = 0; c < chunks; ++c) {
             const int idx = c * 64 + lane;
             const bool live = idx < N && !s_flag[idx] && s_f[idx] > 0.0;
             const double mine = live ? s_f[idx] : 0.0;
-            const int lim = min(64, N - c * 64);
             double prefix = 0.0;
-            for (int k = 0; k < lim; ++k) {
+#pragma unroll
+            for (int k = 0; k < 64; ++k) {
                 run = run + lane_value(mine, k);
                 prefix = (lane == k) ? run : prefix;
             }
             if (idx < N) s_sorted[idx] = prefix;          // s_sorted is free after the quartile: reuse as prefix store
         }
         const double S = run;
-        const U4 o = philox4x32_10(U4{(uint32_t)a.cycle, (uint32_t)(a.cycle >> 32), (uint32_t)t, 0u},
-                                   (uint32_t)a.seed, (uint32_t)(a.seed >> 32));
-        const unsigned long long bits = ((unsigned long long)o.y << 32) | o.x;
-        const double u = (double)(bits >> 11) * 0x1.0p-53;
-        const double thr = u * S;
+        const double thr = s_u[t] * S;
         int pick = -1, last = -1;
         for (int c = 0; c < chunks; ++c) {
             const int idx = c * 64 + lane;
@@ -150,21 +162,25 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
             if (lm) last = c * 64 + 63 - __clzll(lm);
             if (pick < 0 && hit) pick = c * 64 + __ffsll((long long)hit) - 1;
         }
-        if (pick < 0) pick = last;
+        if (pick < 0) pick = last;                         // stays -1 only if no replica is left to draw from
+        n_picked += pick >= 0 ? 1 : 0;
         __syncthreads();
-        if (lane == 0) { a.selected[t] = pick; s_flag[pick] = 1; }
+        if (lane == 0) { a.selected[t] = pick; if (pick >= 0) s_flag[pick] = 1; }
         __syncthreads();
     }
 
-    // aggregation weights a_k and the ascending list the aggregate kernel walks.  The denominator adds the selected
-    // replicas' terms in ascending index, one after another (the same chain as the draws above); everything else is
-    // one element per lane.
-    double denom = 0.0;
-    for (int c = 0; c < chunks; ++c) {
-        const int idx = c * 64 + lane;
-        const double mine = (idx < N && s_flag[idx]) ? ((a.weight_mode == 1) ? s_f[idx] : 1.0) : 0.0;
-        const int lim = min(64, N - c * 64);
-        for (int k = 0; k < lim; ++k) denom = denom + lane_value(mine, k);
+    // aggregation weights a_k and the ascending list the aggregate kernel walks.  With unit terms the denominator is
+    // the count itself (a sum of ones is exact); with f-weighted terms it adds the selected replicas' f in
+    // ascending index, one after another, the same chain as above.
+    double denom = (double)n_picked;
+    if (a.weight_mode == 1) {
+        denom = 0.0;
+        for (int c = 0; c < chunks; ++c) {
+            const int idx = c * 64 + lane;
+            const double mine = (idx < N && s_flag[idx]) ? s_f[idx] : 0.0;
+#pragma unroll
+            for (int k = 0; k < 64; ++k) denom = denom + lane_value(mine, k);
+        }
     }
     int before = 0;                                        // selected replicas in earlier chunks
     for (int c = 0; c < chunks; ++c) {

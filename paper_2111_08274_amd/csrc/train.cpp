@@ -3,7 +3,6 @@
 // memory).  There is no host loop over replicas and no host read-back inside a cycle.
 #include <algorithm>
 #include <cstdio>
-#include <cstdlib>
 
 #include "train.h"
 #include "kernels.h"
@@ -47,18 +46,24 @@ public:
     std::vector<int> stat_for;            // per layer: the BN layer fed by this convolution's statistics, or -1
     std::vector<int> stat_from;           // per layer (BN): the convolution that supplies them, or -1
     std::vector<int> stat_rows;           // per layer (BN): rows per statistics entry of the latest forward launch
+    // The same in the backward pass (bf16 configuration): a lean convolution that is the only consumer of a batch norm's
+    // output (after its fused ReLU and folded pool) leaves, from its data-gradient epilogue, the per-channel sums that
+    // batch norm's backward pass needs, and the BN skips its own sums pass.
+    std::vector<int> bstat_for;           // per layer (conv): the BN layer its data gradient serves, or -1
+    std::vector<int> bstat_rows;          // per layer (BN): rows per entry of the latest data-gradient launch (0: none)
+    std::vector<int64_t> bstat_rep;       // per layer (BN): floats per replica slot of those entries
     // bf16 configuration: regular convolution layers keep two bf16 weight matrices (forward / data-gradient order)
     std::vector<char> fast;               // per layer: the lean bf16 kernels apply
     std::vector<char> fast32;             // per layer (fp32 configuration): lean fp32 forward / data-gradient kernels apply
     std::vector<int64_t> wf_off, wb_off;  // per layer: offsets (bf16 elements) inside one replica's bf16 weight block
     int64_t wbf_rep = 0;                  // bf16 elements per replica
     int64_t wbf_off = 0;                  // start of the bf16 weight region inside `work` (floats)
-    // Environment variable HADFL_TILE_HINT, read when the engine is created: 1 makes the lean kernels take their
-    // 256 x 256 tiles wherever the layer shape allows, whatever the launch size (lets small problems exercise them).
+    // Option HADFL_OPT_TILE_HINT: 1 makes the lean kernels take their 256 x 256 tiles wherever the layer shape allows,
+    // whatever the launch size (lets small problems exercise them); 2 keeps wide-image layers on the general kernels.
     int tile_hint = 0;
     // Weight gradients (and their split-K reduction / fused update) depend only on dY and the stored activations, not on
     // the data-gradient chain, so they run on a second stream beside it; joined before the update kernel.
-    // HADFL_SIDE_STREAM=0 turns this off.
+    // Option HADFL_OPT_SIDE_STREAM = 0 turns this off.
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     bool use_side = true;
@@ -215,8 +220,6 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
     e->fast = L.fast; e->fast32 = L.fast32; e->wf_off = L.wf_off; e->wb_off = L.wb_off; e->wbf_rep = L.wbf_rep;
     e->bn_off = e->shared_off + L.shared_floats;
     e->wbf_off = e->bn_off + L.bn_floats;
-    if (const char* h = std::getenv("HADFL_TILE_HINT")) e->tile_hint = std::atoi(h);
-    if (const char* h = std::getenv("HADFL_SIDE_STREAM")) e->use_side = std::atoi(h) != 0;
     {
         e->fused_update.assign(plan.layers.size(), 0);
         int64_t pos = 0;
@@ -294,6 +297,16 @@ hadfl_status train_create(const hadfl_config& cfg, const NetPlan& plan, const Tr
             if (t.c % vec != 0 || t.h % 2 != 0 || t.w % 2 != 0) continue;
             e->pool_of[i] = j; e->skip[j] = 1;
         }
+        e->bstat_for.assign(nl, -1); e->bstat_rows.assign(nl, 0); e->bstat_rep.assign(nl, 0);
+        if (cfg.bf16)
+            for (int k = 0; k < nl; ++k) {
+                if (plan.layers[k].type != HADFL_OP_BN || e->skip[k]) continue;
+                // the tensor the rest of the net sees as this BN's output
+                const int t_out = e->pool_of[k] >= 0 ? plan.layers[e->pool_of[k]].out : e->out_tensor[k];
+                if (consumers[t_out] != 1) continue;
+                for (int j = 0; j < nl; ++j)
+                    if (plan.layers[j].type == HADFL_OP_CONV && plan.layers[j].in0 == t_out && e->fast[j]) e->bstat_for[j] = k;
+            }
     }
     *out = e;
     return HADFL_OK;
@@ -309,6 +322,10 @@ void train_set_steps(TrainEngine* e, const std::vector<int32_t>& steps)
 }
 
 void train_set_lr(TrainEngine* e, float lr) { e->cfg.lr = lr; }
+
+void train_set_side_stream(TrainEngine* e, bool on) { e->use_side = on; }
+void train_set_tile_hint(TrainEngine* e, int hint) { e->tile_hint = hint; }
+bool train_has_momentum(const TrainEngine* e) { return e->buf.mom != nullptr; }
 
 void train_destroy(TrainEngine* e)
 {
@@ -338,7 +355,7 @@ struct Runner {
     // the launches that follow go to the side stream, ordered after everything enqueued on the main stream so far
     void fork()
     {
-        if (!e.side || rc != hipSuccess) return;
+        if (!e.use_side || !e.side || rc != hipSuccess) return;
         rc = hipEventRecord(e.ev_fork, s);
         if (rc == hipSuccess) rc = hipStreamWaitEvent(e.side, e.ev_fork, 0);
         if (rc != hipSuccess) { failed = "fork"; return; }
@@ -348,7 +365,7 @@ struct Runner {
     // the main stream waits for everything enqueued on the side stream
     void join()
     {
-        if (!e.side || rc != hipSuccess) return;
+        if (!e.use_side || !e.side || rc != hipSuccess) return;
         rc = hipEventRecord(e.ev_join, e.side);
         if (rc == hipSuccess) rc = hipStreamWaitEvent(s, e.ev_join, 0);
         if (rc != hipSuccess) failed = "join";
@@ -699,7 +716,15 @@ struct Runner {
                     f.out = grad(l.in0); f.out_rep = e.rep_block;
                     f.mask = mask0; f.mask_rep = e.rep_block; f.accumulate = acc0; f.order = e.buf.order; f.tile_hint = e.tile_hint;
                     f.perm = perm(i); f.posmask = posmask(i);
-                    run("conv_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return launch_conv_fast(f, 1, na, s); });
+                    int* brows = nullptr;
+                    if (e.bstat_for[i] >= 0 && !acc0) {        // this data gradient is the whole gradient of a BN's output
+                        const int k = e.bstat_for[i];
+                        f.stat = bn_shared(); f.stat_rep = ((int64_t)d.M + 127) / 128 * 2 * d.N;
+                        f.stat_y = act(l.in0); f.stat_y_rep = e.rep_block; f.stat_relu = e.fused_relu[k];
+                        e.bstat_rep[k] = f.stat_rep;
+                        brows = &e.bstat_rows[k];
+                    }
+                    run("conv_dgrad", gemm_flops(d), gemm_bytes(d), [&] { return launch_conv_fast(f, 1, na, s, brows); });
                 } else if (e.fast32[i]) {
                     FastConvParams f{};
                     f.B = d.B; f.H = d.H; f.W = d.W; f.C = d.Cout; f.N = d.Cin; f.R = d.R; f.S = d.S; f.pad = d.R - 1 - d.pad;
@@ -748,6 +773,12 @@ struct Runner {
                 b.pool = 1; b.H = a.h; b.W = a.w; b.relu = e.fused_relu[i];
                 b.pool_y = act(ot); b.pool_y_rep = e.rep_block;
                 b.pool_g = grad(e.plan.layers[e.pool_of[i]].out); b.pool_g_rep = e.rep_block;
+            }
+            if (e.bstat_rows[i] > 0) {                       // the data gradient of the layer above left the sums
+                const int64_t rows_out = e.pool_of[i] >= 0 ? b.rows / 4 : b.rows;
+                b.bwd_stats_done = 1; b.stat_entries = (int)((rows_out + e.bstat_rows[i] - 1) / e.bstat_rows[i]);
+                b.partial_rep = e.bstat_rep[i];
+                e.bstat_rows[i] = 0;
             }
             run("bn_bwd", 0, asz() * (12.0 * B * a.numel()), [&] { return launch_bn_bwd(b, na, s); });
             break; }

@@ -31,6 +31,9 @@ hadfl_status train_run(TrainEngine* e, hipStream_t s, Profiler* prof, std::strin
 // New per-replica step counts for the following runs (the caller has already re-sorted and uploaded `order`)
 void train_set_steps(TrainEngine* e, const std::vector<int32_t>& steps);
 void train_set_lr(TrainEngine* e, float lr);
+void train_set_side_stream(TrainEngine* e, bool on);      // weight gradients on the engine's second stream
+void train_set_tile_hint(TrainEngine* e, int hint);       // 0 automatic, 1 tall tiles wherever they fit, 2 no wide-image kernels
+bool train_has_momentum(const TrainEngine* e);
 void train_destroy(TrainEngine* e);
 
 // Event-pair profiler used by hadfl_profile_*.

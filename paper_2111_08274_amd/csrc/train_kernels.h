@@ -65,6 +65,12 @@ struct FastConvParams {      // out[m][n] = sum_k act[pixel(m) + tap(k)][c(k)] *
     // covers GEMM rows [e * R, (e + 1) * R), R = the chosen kernel's rows per tile (reported by the launcher):
     // stat[g * stat_rep + e * 2 * N + n] = sum of out[m][n], [.. + N + n] = sum of out[m][n]^2 (values as rounded to bf16)
     float* stat; long long stat_rep;
+    // data gradient only, with stat set: the tensor whose gradient is being written is the output y of a batch norm
+    // (after its fused ReLU and, if the pool is folded into it, after the pool), and the same entries receive what that
+    // batch norm's backward pass needs instead:  [..+ n] = sum of g,  [.. + N + n] = sum of g * y,  g the stored gradient
+    // (zero where stat_relu is set and y <= 0).  With xhat = (y - beta) / gamma wherever the gradient passes, these give
+    // d(beta) = sum g and d(gamma) = (sum g*y - beta * sum g) / gamma without another pass over the tensors.
+    const void* stat_y; long long stat_y_rep; int stat_relu;
 };
 // epi 0: forward (+bias, ReLU); epi 1: data gradient (mask, accumulate).  Needs C % 64 == 0 and N % 64 == 0.
 // stat_rows (may be null): receives the rows per statistics entry of the kernel that was launched (128 or 256).
@@ -175,6 +181,9 @@ struct BnParams {
     // forward: the producing convolution already left per-entry sums of x and x^2 in `partial` ([stat_entries][2][C]); the
     // sums pass is skipped and the shift of the one-pass variance is zero
     int stats_done, stat_entries;
+    // backward: the data-gradient kernel of the layer above already left per-entry sums of g and g * y in `partial`
+    // ([stat_entries][2][C], see FastConvParams::stat_y); the sums pass is skipped and d(gamma) is formed from them
+    int bwd_stats_done;
     float* pool_out; long long pool_out_rep;
     const float* pool_y; long long pool_y_rep;
     const float* pool_g; long long pool_g_rep;

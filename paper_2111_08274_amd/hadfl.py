@@ -40,8 +40,12 @@ class HadflKernelTime(ctypes.Structure):
                 ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
 
 
+OPT_SIDE_STREAM, OPT_TILE_HINT = 0, 1
+
 EXPORTS = ("hadfl_param_count", "hadfl_param_layout", "hadfl_workspace_bytes", "hadfl_init_replicas",
-           "hadfl_local_steps", "hadfl_select", "hadfl_aggregate", "hadfl_steps_from_times", "hadfl_set_lr", "hadfl_set_steps",
+           "hadfl_local_steps", "hadfl_select", "hadfl_aggregate", "hadfl_step_counts", "hadfl_steps_from_times",
+           "hadfl_set_lr", "hadfl_set_steps", "hadfl_set_params", "hadfl_get_momentum", "hadfl_set_momentum",
+           "hadfl_set_option",
            "hadfl_select_group", "hadfl_aggregate_group", "hadfl_predict_versions",
            "hadfl_select_real", "hadfl_get_predicted", "hadfl_get_steps", "hadfl_get_versions",
            "hadfl_get_selected", "hadfl_get_params", "hadfl_get_losses", "hadfl_profile_enable",
@@ -76,7 +80,12 @@ def lib():
         L.hadfl_select.argtypes = [vp, vp, vp, ctypes.c_uint64]
         L.hadfl_aggregate.argtypes = [vp, i32]
         L.hadfl_set_steps.argtypes = [vp, vp]
+        L.hadfl_step_counts.argtypes = [vp, i32, i32, i32, vp]
         L.hadfl_steps_from_times.argtypes = [vp, i32, i32, ctypes.c_double, i32, i32, vp]
+        L.hadfl_set_params.argtypes = [vp, i32, vp, ctypes.c_size_t]
+        L.hadfl_get_momentum.argtypes = [vp, i32, vp, ctypes.c_size_t]
+        L.hadfl_set_momentum.argtypes = [vp, i32, vp, ctypes.c_size_t]
+        L.hadfl_set_option.argtypes = [vp, i32, i32]
         L.hadfl_set_lr.argtypes = [vp, ctypes.c_float]
         L.hadfl_select_group.argtypes = [vp, vp, vp, i32, ctypes.c_uint64]
         L.hadfl_aggregate_group.argtypes = [vp, vp]
@@ -85,7 +94,7 @@ def lib():
         L.hadfl_get_predicted.argtypes = [vp, vp]
         L.hadfl_get_steps.argtypes = [vp, vp]
         L.hadfl_get_versions.argtypes = [vp, vp, vp]
-        L.hadfl_get_selected.argtypes = [vp, vp, vp, vp]
+        L.hadfl_get_selected.argtypes = [vp, vp, ctypes.POINTER(i32), vp, vp]
         L.hadfl_get_params.argtypes = [vp, i32, vp, ctypes.c_size_t]
         L.hadfl_get_losses.argtypes = [vp, vp]
         L.hadfl_profile_enable.argtypes = [vp, i32]
@@ -154,6 +163,14 @@ def _np_ptr(a):
     return a.ctypes.data_as(ctypes.c_void_p)
 
 
+def step_counts(ratio, t_sync=1, steps_per_unit=1):
+    """The step-count rule from computing-power ratios (host only) -> int32[n]."""
+    r = np.ascontiguousarray(ratio, dtype=np.int32)
+    out = np.zeros(r.size, dtype=np.int32)
+    _check(lib().hadfl_step_counts(_np_ptr(r), int(r.size), int(t_sync), int(steps_per_unit), _np_ptr(out)))
+    return out
+
+
 def steps_from_times(times, e_warmup, quantum, t_sync=1, steps_per_unit=1):
     """Step counts from measured warm-up times (host only) -> int32[n]."""
     t = np.ascontiguousarray(times, dtype=np.float64)
@@ -166,7 +183,7 @@ def steps_from_times(times, e_warmup, quantum, t_sync=1, steps_per_unit=1):
 class Context:
     """One set of replicas on the current torch device.  Holds the torch tensors the library works in."""
 
-    def __init__(self, cfg, ratio, w0=None, x=None, y=None, replicas=None, stream=None):
+    def __init__(self, cfg, ratio, w0=None, x=None, y=None, replicas=None, stream=None, options=None):
         import torch
         self.cfg = cfg
         self.m_train, self.m_total, self.row_stride = param_count(cfg)
@@ -193,6 +210,24 @@ class Context:
                                          self.y.data_ptr() if self.y is not None else None,
                                          _np_ptr(ratio), self.stream.cuda_stream, ctypes.byref(h)))
         self.h = h
+        for opt, value in (options or {}).items():
+            self.set_option(opt, value)
+
+    def set_option(self, option, value):
+        _check(lib().hadfl_set_option(self.h, int(option), int(value)), self.h)
+
+    def set_params(self, replica, values):
+        v = np.ascontiguousarray(values, dtype=np.float32)
+        _check(lib().hadfl_set_params(self.h, int(replica), _np_ptr(v), v.size), self.h)
+
+    def momentum(self, replica, n=None):
+        out = np.zeros(self.m_train if n is None else n, dtype=np.float32)
+        _check(lib().hadfl_get_momentum(self.h, int(replica), _np_ptr(out), out.size), self.h)
+        return out
+
+    def set_momentum(self, replica, values):
+        v = np.ascontiguousarray(values, dtype=np.float32)
+        _check(lib().hadfl_set_momentum(self.h, int(replica), _np_ptr(v), v.size), self.h)
 
     def close(self):
         if getattr(self, "h", None):
@@ -216,7 +251,6 @@ class Context:
             assert versions.dtype.__str__() == "torch.int32" and versions.is_cuda and versions.numel() == self.cfg.n_replicas
         _check(lib().hadfl_select(self.h, versions.data_ptr() if versions is not None else None,
                                   _np_ptr(av) if av is not None else None, int(cycle)), self.h)
-        self._n_last = self.cfg.n_select
 
     def set_lr(self, lr):
         _check(lib().hadfl_set_lr(self.h, float(lr)), self.h)
@@ -240,7 +274,6 @@ class Context:
             assert versions.dtype.__str__() == "torch.float64" and versions.is_cuda and versions.numel() == self.cfg.n_replicas
         _check(lib().hadfl_select_real(self.h, versions.data_ptr() if versions is not None else None,
                                        _np_ptr(av) if av is not None else None, int(cycle)), self.h)
-        self._n_last = self.cfg.n_select
 
     def predicted(self):
         out = np.zeros(self.cfg.n_replicas, dtype=np.float64)
@@ -254,7 +287,6 @@ class Context:
             assert versions.dtype.__str__() == "torch.int32" and versions.is_cuda and versions.numel() == self.cfg.n_replicas
         _check(lib().hadfl_select_group(self.h, versions.data_ptr() if versions is not None else None, _np_ptr(mb),
                                         int(n_select), int(cycle)), self.h)
-        self._n_last = int(n_select)
 
     def aggregate_group(self, members):
         mb = np.ascontiguousarray(members, dtype=np.uint8)
@@ -277,10 +309,11 @@ class Context:
 
     def selected(self):
         sel = np.zeros(self.cfg.n_select, dtype=np.int32)
+        cnt = ctypes.c_int32()
         flag = np.zeros(self.cfg.n_replicas, dtype=np.uint8)
         w = np.zeros(self.cfg.n_replicas, dtype=np.float32)
-        _check(lib().hadfl_get_selected(self.h, _np_ptr(sel), _np_ptr(flag), _np_ptr(w)), self.h)
-        return sel[:getattr(self, "_n_last", self.cfg.n_select)], flag, w
+        _check(lib().hadfl_get_selected(self.h, _np_ptr(sel), ctypes.byref(cnt), _np_ptr(flag), _np_ptr(w)), self.h)
+        return sel[:cnt.value], flag, w
 
     def params(self, replica, n=None):
         n = self.m_total if n is None else n

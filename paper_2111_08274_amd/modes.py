@@ -42,8 +42,8 @@ def steps_per_cycle(mode, ratio, t_sync=1, local_steps=1):
     """Local steps of every device in one cycle (the step-count rule of Sec. 3.3 for hadfl)."""
     ratio = np.asarray(ratio, dtype=np.int64)
     if mode == "hadfl":
-        g = int(np.gcd.reduce(ratio))
-        return (t_sync * ratio // g).astype(np.int64)
+        from . import hadfl                    # the rule itself lives in the library (hadfl_step_counts)
+        return hadfl.step_counts(ratio, t_sync).astype(np.int64)
     if mode == "fedavg":
         return np.full(ratio.size, int(local_steps), dtype=np.int64)
     if mode == "sync_sgd":

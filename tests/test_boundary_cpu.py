@@ -97,3 +97,37 @@ def test_steps_from_warm_up_times_host_logic_against_the_oracle():
         assert e.value.status == einval
     with pytest.raises(hadfl.HadflError):
         hadfl.steps_from_times([1.0, 2.0], 1, 1.0, t_sync=0)
+
+
+def test_step_count_rule_host_entry_against_the_oracle_and_the_golden_cases(golden_dir):
+    # hadfl_step_counts is the rule hadfl_init_replicas applies (Sec. 2.3, Sec. 3.3): the hand-worked cases of
+    # tests/golden/step_counts.txt, then seeded ratios against the oracle, then the documented errors
+    for line in open(os.path.join(golden_dir, "step_counts.txt")):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        ratio, t_sync, want = (part.strip() for part in line.split("|"))
+        got = hadfl.step_counts([int(v) for v in ratio.split(",")], int(t_sync))
+        assert got.tolist() == [int(v) for v in want.split(",")], line
+    rng = np.random.default_rng(8)
+    for case in range(200):
+        n = int(rng.integers(1, 65))
+        g = int(rng.integers(1, 5))
+        ratio = rng.integers(1, 9, size=n) * g
+        t_sync, spu = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        assert hadfl.step_counts(ratio, t_sync, spu).tolist() == oracle.step_counts(ratio, t_sync, spu).tolist()
+    for args in (([1, 0, 2], 1, 1), ([1, 2], 0, 1), ([1, 2], 1, 0), ([1, 1 << 21], 1, 1)):
+        with pytest.raises(hadfl.HadflError) as e:
+            hadfl.step_counts(*args)
+        assert e.value.status == hadfl.EINVAL
+
+
+def test_only_gemm_layers_may_read_the_input_batch():
+    # tensor 0 lives inside the data set and is addressed through the batch cursor: a ReLU, pool, BN or add on it has no kernel
+    for rows in ([[2, 0, -1, 0, 0, 0, 0, 0], [1, 1, -1, 0, 0, 0, 10, 1]],                       # relu(input) -> dense
+                 [[4, 0, -1, 0, 0, 0, 0, 0], [6, 1, -1, 0, 0, 0, 0, 0], [1, 2, -1, 0, 0, 0, 10, 1]],   # bn(input)
+                 [[0, 0, -1, 3, 1, 1, 3, 0], [5, 1, 0, 0, 0, 0, 0, 0], [6, 2, -1, 0, 0, 0, 0, 0], [1, 3, -1, 0, 0, 0, 10, 1]]):
+        hc = hadfl.make_config(2, 1, net="custom", batch=4, n_samples=8, in_shape=(4, 4, 3), custom_ops=np.array(rows))
+        with pytest.raises(hadfl.HadflError) as e:
+            hadfl.param_count(hc)
+        assert e.value.status == hadfl.EUNSUPPORTED

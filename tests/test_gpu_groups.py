@@ -16,10 +16,12 @@ def test_grouped_synchronisation_parity():
     N = cfg["n_replicas"]                                    # 8 devices, powers 1 1 2 2 3 3 4 4
     p = Pair(fn(), shape, N, 4, x, y, cfg["batch"], cfg["lr"], 0.9, cfg["ratio"], net_name="cnn2")
     groups = [np.array([1, 0, 1, 0, 1, 0, 1, 0], dtype=np.uint8), np.array([0, 1, 0, 1, 0, 1, 0, 1], dtype=np.uint8)]
+    import torch
     for rnd in range(4):
-        p.local_steps()
+        p.forced_steps()                                      # every step from a common state (workload 2 at lr 0.01)
+        versions = torch.as_tensor(p.cpu.versions).cuda()     # the cycle's versions (the library's counters hold the last sub-step's)
         for g, members in enumerate(groups):
-            p.gpu.select_group(2 * rnd + g, members, 2)
+            p.gpu.select_group(2 * rnd + g, members, 2, versions=versions)
             p.cpu.select_group(2 * rnd + g, members, 2)
             sel, flag, w = p.gpu.selected()
             assert sel.tolist() == p.cpu.selected.tolist() and flag.tolist() == p.cpu.flag.tolist()

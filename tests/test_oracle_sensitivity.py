@@ -43,3 +43,86 @@ def test_fp64_trajectory_is_chaotic_at_lr_0p1_and_stable_at_0p01():
         gap[lr] = np.abs(a.params[:, :net.m_train] - b.params[:, :net.m_train]).max()
     assert gap[0.1] > 1e-3          # measured 2.4e-2
     assert gap[0.01] < 1e-6         # measured 2.3e-7 (the perturbation itself)
+
+
+def test_cnn_workload_amplifies_one_rounding_past_the_bar_at_lr_0p01():
+    """Workload 2 (8 x the two-convolution CNN, momentum 0.9, 10 cycles) states no learning rate; the paper's is 0.01
+    (Sec. 4.1).  There the first steps overshoot (loss 5.8 -> 50) and the fp64 oracle, run beside a copy of itself whose
+    initial weights differ by one fp32 rounding, ends the 10 configured cycles 2.4e-4 apart: more than the 1e-4 parity
+    bar, so free-running 10-cycle parity at that rate is not a property any fp32 implementation can have.  (At 0.001 the
+    same perturbation ends at 2.3e-5.)  Both copies run as one 16-replica batch of local steps, 8 + 8, and are selected
+    and aggregated half by half with the same draws."""
+    cfg, x, y = synth.config_inputs(2)
+    net = oracle.Net.named("cnn2")
+    N, n = cfg["n_replicas"], cfg["n_samples"]
+    w0 = synth.he_normal_init(net.layout()).astype(np.float64)
+    w1 = w0 * (1 + 6e-8 * np.random.default_rng(0).standard_normal(w0.size))
+    xs = x.reshape(N, n, -1)
+    both = oracle.Cycle(net, 2 * N, cfg["n_select"], w0, np.concatenate([xs, xs]), np.concatenate([y, y]), cfg["batch"],
+                        0.01, cfg["momentum"], np.concatenate([cfg["ratio"], cfg["ratio"]]), seed=synth.SELECT_SEED)
+    both.params[N:] = w1
+    gaps, first_losses = [], None
+    for cycle in range(cfg["cycles"]):
+        both.local_steps()
+        if first_losses is None:
+            first_losses = both.loss[:N].copy()
+        assert both.versions[:N].tolist() == both.versions[N:].tolist() == list(cfg["ratio"])
+        sel, flag, f, _ = oracle.select(both.versions[:N], cfg["n_select"], synth.SELECT_SEED, cycle)
+        a = oracle.aggregation_weights(flag)
+        for half in (slice(0, N), slice(N, 2 * N)):
+            both.params[half] = oracle.aggregate(both.params[half], a)
+        gaps.append(float(np.abs(both.params[:N, :net.m_train] - both.params[N:, :net.m_train]).max()))
+    assert first_losses.max() > 20           # the overshoot of the first cycle (measured 50)
+    assert gaps[-1] > 1e-4                   # measured 2.4e-4
+    assert gaps[2] < 1e-5                    # the first cycles are still comparable (measured 2.6e-6)
+
+
+def test_one_bf16_step_is_ill_conditioned_in_deep_batch_normalised_stacks():
+    """The oracle in its bf16 mode against a copy of itself whose weights differ by one fp32 rounding, one step each:
+    the update of the worst tensor differs by more than 1 % (Euclidean) on a seven-convolution VGG-shaped net and by
+    more than 30 % on a stack of twenty conv-BN-ReLU layers; in fp64 mode the same perturbation moves no tensor's update
+    by more than 1e-5.  Every stored activation sits next to a bf16 rounding boundary, one crossing is a 0.4 % change
+    of that value, and each batch-normalised layer amplifies what arrives.  So a fixed per-step, per-tensor bound of
+    2e-2 cannot be asked of any implementation on deep nets; the GPU tests measure the oracle's own twin beside every
+    comparison instead (tests/parity_metrics.py)."""
+    from tests import parity_metrics as pm
+
+    def worst_l2(ops, shape, x, y, batch, bf16):
+        net = oracle.Net(ops, shape, bf16=bf16)
+        layout = net.layout()
+        w0 = synth.he_normal_init(layout).astype(np.float64)
+        w1 = w0 * (1 + 6e-8 * np.random.default_rng(0).standard_normal(w0.size))
+        N = x.shape[0]
+        both = oracle.Cycle(net, 2 * N, 1, w0, np.concatenate([x, x]).reshape(2 * N, x.shape[1], -1),
+                            np.concatenate([y, y]), batch, 0.01, 0.9, [1] * (2 * N), seed=1)
+        both.params[N:] = w1
+        both.local_steps()
+        worst = 0.0
+        for k in range(N):
+            as_if = w0 + (both.params[N + k] - w1)
+            worst = max(worst, pm.worst_update_error(layout, w0, as_if, both.params[k], norm="l2")[0])
+        return worst
+
+    b = nets._Builder()
+    t = b.relu(b.bn(b.conv(0, 64, bias=False)))
+    for _ in range(19):
+        t = b.relu(b.bn(b.conv(t, 64, bias=False)))
+    b.dense(b.gap(t), 5)
+    rng = np.random.default_rng(91)
+    x = rng.standard_normal((2, 16, 4, 4, 3)).astype(np.float32)
+    y = rng.integers(0, 5, size=(2, 16)).astype(np.int32)
+    deep_bf16 = worst_l2(b.array(), (4, 4, 3), x, y, 8, True)
+    deep_f64 = worst_l2(b.array(), (4, 4, 3), x, y, 8, False)
+    assert deep_bf16 > 0.3 and deep_f64 < 1e-5          # measured 0.54-0.58 and 2e-6
+
+    b = nets._Builder()
+    t = 0
+    for width, reps in ((16, 2), (32, 2), (64, 3)):
+        for _ in range(reps):
+            t = b.relu(b.bn(b.conv(t, width)))
+        t = b.maxpool(t)
+    b.dense(t, 10)
+    x, y = synth.class_shift_images(2, 64, (16, 16, 3), 10, seed=105, dirichlet=0.3)
+    vgg_bf16 = worst_l2(b.array(), (16, 16, 3), x, y, 16, True)
+    vgg_f64 = worst_l2(b.array(), (16, 16, 3), x, y, 16, False)
+    assert vgg_bf16 > 1e-2 and vgg_f64 < 1e-5           # measured 1.2e-2 ... 1.6e-2 and 4e-7
