@@ -161,6 +161,28 @@ HADFL_API hadfl_status hadfl_select(hadfl_ctx *ctx, const int32_t *versions_dev,
 HADFL_API hadfl_status hadfl_step_counts(const int32_t *ratio_host, int32_t n, int32_t t_sync, int32_t steps_per_unit,
                                          int32_t *steps_host);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc: the selection of hadfl_select without a context and without a workspace.  The kernel's
+ * working memory (the selection function's values and the ascending list of the selected) is a static device array of
+ * 16 KiB inside the library, enough for 1024 replicas; the call allocates nothing, on the host or on the device, and
+ * creates no stream or event.  It enqueues one kernel on `stream` and returns without waiting.
+ *   versions_dev  dev, [n_replicas] int32
+ *   avail_dev     dev, [n_replicas] bytes (0 = absent this round), or NULL = all present.  A device array, unlike
+ *                 hadfl_select's host mask: there is no staging copy.  If fewer than n_select replicas are present,
+ *                 the surplus entries of selected_dev are -1 (the host cannot check a device mask).
+ *   n_replicas    in [1, 1024]; EINVAL beyond that, with the limit in hadfl_last_error(NULL)
+ *   n_select      in [1, n_replicas]; weight_mode as hadfl_config.weight_mode; seed, cycle as hadfl_select
+ *   selected_dev  dev out, [n_select] int32, draw order
+ *   flag_dev      dev out, [n_replicas] bytes
+ *   weights_dev   dev out, [n_replicas] floats, the aggregation weights a_k
+ *   stream        hipStream_t (NULL = the default stream)
+ * Every call on one GPU uses that GPU's one array: calls that overlap in time on one GPU (two streams, two threads)
+ * race and must be serialised by the caller.  Nothing in the array has to survive between calls and nothing has to be
+ * cleared: the kernel writes every entry before it reads it. */
+HADFL_API hadfl_status hadfl_select_static(const int32_t *versions_dev, const uint8_t *avail_dev, int32_t n_replicas,
+                                           int32_t n_select, int32_t weight_mode, uint64_t seed, uint64_t cycle,
+                                           int32_t *selected_dev, uint8_t *flag_dev, float *weights_dev, void *stream);
+
 /* Sec. 3.2 (mutual-negotiation phase) with Sec. 3.3 (hyperperiod): step counts from measured calculation times.
  * Device k reports the time times_host[k] it needed for e_warmup warm-up units.  Its time per unit,
  * times_host[k] / e_warmup, is rounded to the nearest whole number q_k >= 1 of `quantum`; the hyperperiod is

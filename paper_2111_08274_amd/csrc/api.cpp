@@ -449,6 +449,28 @@ hadfl_status hadfl_select(hadfl_ctx* ctx, const int32_t* versions_dev, const uin
     });
 }
 
+hadfl_status hadfl_select_static(const int32_t* versions_dev, const uint8_t* avail_dev, int32_t n_replicas, int32_t n_select,
+                                 int32_t weight_mode, uint64_t seed, uint64_t cycle, int32_t* selected_dev, uint8_t* flag_dev,
+                                 float* weights_dev, void* stream)
+{
+    return guard(nullptr, [&]() -> hadfl_status {
+    if (!versions_dev || !selected_dev || !flag_dev || !weights_dev) return fail(nullptr, HADFL_EINVAL, "null argument");
+    if (((uintptr_t)versions_dev | (uintptr_t)selected_dev | (uintptr_t)weights_dev) & 3)
+        return fail(nullptr, HADFL_EINVAL, "versions_dev, selected_dev and weights_dev must be 4-byte aligned");
+    if (n_replicas < 1 || n_replicas > kMaxReplicas)
+        return fail(nullptr, HADFL_EINVAL, "n_replicas must be in [1, 1024]: the static working memory holds 1024 replicas");
+    if (n_select < 1 || n_select > n_replicas) return fail(nullptr, HADFL_EINVAL, "n_select must be in [1, n_replicas]");
+    if (weight_mode != 0 && weight_mode != 1) return fail(nullptr, HADFL_EINVAL, "weight_mode must be 0 or 1");
+    SelectArgs a{};
+    a.versions = versions_dev; a.avail = avail_dev;
+    a.n = n_replicas; a.n_select = n_select; a.weight_mode = weight_mode; a.seed = seed; a.cycle = cycle;
+    a.selected = selected_dev; a.flag = flag_dev; a.weights = weights_dev;
+    const hipError_t e = launch_select_static(a, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "static selection");
+    return HADFL_OK;
+    });
+}
+
 hadfl_status hadfl_select_real(hadfl_ctx* ctx, const double* versions_dev, const uint8_t* avail_host, uint64_t cycle)
 {
     return guard(ctx, [&]() -> hadfl_status {

@@ -19,6 +19,9 @@ struct SelectArgs {
     double* f;                     // [n]
 };
 hipError_t launch_select(const SelectArgs& a, hipStream_t s);
+// The same kernel with f, sel_sorted and sel_weight taken from a static device array (at most kMaxReplicas replicas);
+// allocates nothing.  a.f / a.sel_sorted / a.sel_weight are ignored.
+hipError_t launch_select_static(SelectArgs a, hipStream_t s);
 // Sec. 3.2: feed versions[n] into the smoothing states s1[n], s2[n] and write the forecast m cycles ahead to out[n]
 hipError_t launch_predict(const int32_t* versions, double* s1, double* s2, double* out, int n, double alpha, int m,
                           int first, hipStream_t s);

@@ -1,7 +1,16 @@
 // Probability-based replica selection (paper Sec. 3.3) as one wavefront on the device.
 // Built with -ffp-contract=off: every fp64 operation below is rounded on its own, so the result is a
 // function of the inputs alone and any IEEE-754 implementation of the same written steps gives the same bits.
+#include <mutex>
+
 #include "kernels.h"
+
+// Working memory of hadfl_select_static, the selection for callers that cannot allocate device memory: the selection
+// function's values f[kMaxReplicas] (fp64), then the ascending list of the selected replicas and their weights.
+// Every GPU the library runs on holds its own copy until the process ends.  Host code never passes this name to a
+// kernel: it is a host-side stand-in, the device address comes from hipGetSymbolAddress (static_scratch below).
+constexpr size_t kStaticScratchBytes = hadfl::kMaxReplicas * (sizeof(double) + sizeof(int32_t) + sizeof(float));
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace hadfl {
 namespace {
@@ -230,6 +239,43 @@ hipError_t launch_predict(const int32_t* versions, double* s1, double* s2, doubl
 {
     hipLaunchKernelGGL(predict_kernel, dim3(1), dim3(64), 0, s, versions, s1, s2, out, n, alpha, m, first);
     return hipGetLastError();
+}
+
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+hipError_t static_scratch(unsigned char** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<unsigned char*>(g_scratch_ptr[dev]);
+    return hipSuccess;
+}
+}  // namespace
+
+hipError_t launch_select_static(SelectArgs a, hipStream_t s)
+{
+    if (a.n < 1 || a.n > kMaxReplicas || a.n_select < 1 || a.n_select > a.n) return hipErrorInvalidValue;
+    unsigned char* base = nullptr;
+    const hipError_t e = static_scratch(&base);
+    if (e != hipSuccess) return e;
+    // the kernel writes every entry of these three before it reads it, so nothing has to be cleared between calls
+    a.f = reinterpret_cast<double*>(base);
+    a.sel_sorted = reinterpret_cast<int32_t*>(base + kMaxReplicas * sizeof(double));
+    a.sel_weight = reinterpret_cast<float*>(base + kMaxReplicas * (sizeof(double) + sizeof(int32_t)));
+    return launch_select(a, s);
 }
 
 hipError_t launch_select(const SelectArgs& a, hipStream_t s)

@@ -45,7 +45,7 @@ OPT_SIDE_STREAM, OPT_TILE_HINT = 0, 1
 EXPORTS = ("hadfl_param_count", "hadfl_param_layout", "hadfl_workspace_bytes", "hadfl_init_replicas",
            "hadfl_local_steps", "hadfl_select", "hadfl_aggregate", "hadfl_step_counts", "hadfl_steps_from_times",
            "hadfl_set_lr", "hadfl_set_steps", "hadfl_set_params", "hadfl_get_momentum", "hadfl_set_momentum",
-           "hadfl_set_option",
+           "hadfl_set_option", "hadfl_select_static",
            "hadfl_select_group", "hadfl_aggregate_group", "hadfl_predict_versions",
            "hadfl_select_real", "hadfl_get_predicted", "hadfl_get_steps", "hadfl_get_versions",
            "hadfl_get_selected", "hadfl_get_params", "hadfl_get_losses", "hadfl_profile_enable",
@@ -86,6 +86,7 @@ def lib():
         L.hadfl_get_momentum.argtypes = [vp, i32, vp, ctypes.c_size_t]
         L.hadfl_set_momentum.argtypes = [vp, i32, vp, ctypes.c_size_t]
         L.hadfl_set_option.argtypes = [vp, i32, i32]
+        L.hadfl_select_static.argtypes = [vp, vp, i32, i32, i32, ctypes.c_uint64, ctypes.c_uint64, vp, vp, vp, vp]
         L.hadfl_set_lr.argtypes = [vp, ctypes.c_float]
         L.hadfl_select_group.argtypes = [vp, vp, vp, i32, ctypes.c_uint64]
         L.hadfl_aggregate_group.argtypes = [vp, vp]
@@ -178,6 +179,23 @@ def steps_from_times(times, e_warmup, quantum, t_sync=1, steps_per_unit=1):
     _check(lib().hadfl_steps_from_times(_np_ptr(t), int(t.size), int(e_warmup), float(quantum), int(t_sync),
                                         int(steps_per_unit), _np_ptr(out)))
     return out
+
+
+def select_static(versions, n_select, seed, cycle, selected, flag, weights, avail=None, weight_mode=0, stream=None):
+    """hadfl_select_static on torch device tensors the CALLER has allocated: versions int32[n], avail uint8[n] or None;
+    outputs selected int32[n_select], flag uint8[n], weights float32[n].  The library allocates nothing."""
+    import torch
+    n = versions.numel()
+    assert versions.dtype == torch.int32 and versions.is_cuda and versions.is_contiguous()
+    assert selected.dtype == torch.int32 and selected.numel() >= n_select and selected.is_cuda
+    assert flag.dtype == torch.uint8 and flag.numel() >= n and flag.is_cuda
+    assert weights.dtype == torch.float32 and weights.numel() >= n and weights.is_cuda
+    if avail is not None:
+        assert avail.dtype == torch.uint8 and avail.numel() == n and avail.is_cuda
+    st = (torch.cuda.current_stream() if stream is None else stream).cuda_stream
+    _check(lib().hadfl_select_static(versions.data_ptr(), avail.data_ptr() if avail is not None else None, int(n),
+                                     int(n_select), int(weight_mode), int(seed), int(cycle), selected.data_ptr(),
+                                     flag.data_ptr(), weights.data_ptr(), st))
 
 
 class Context:
