@@ -591,7 +591,7 @@ __device__ __forceinline__ void update_block32(const f16& acc, const UpdateOpera
 
 // Tile BMT x BN, WGM x WGN waves, slabs of BKT contraction indices, two LDS buffers.
 template <int BMT, int BN, int WGM, int WGN, int BKT>
-__global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN == 8 ? 1 : 2) void wgrad_kernel(FastWgradParams p)
+__global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN == 8 ? 1 : 3) void wgrad_kernel(FastWgradParams p)
 {
     constexpr int NT = WGM * WGN * 64;
     constexpr int TM = BMT / WGM / 32, TN = BN / WGN / 32;

@@ -1,7 +1,9 @@
 // Probability-based replica selection (paper Sec. 3.3) as one wavefront on the device.
 // Built with -ffp-contract=off: every fp64 operation below is rounded on its own, so the result is a
 // function of the inputs alone and any IEEE-754 implementation of the same written steps gives the same bits.
+#include <climits>
 #include <mutex>
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -57,6 +59,37 @@ __device__ __forceinline__ double lane_value(double v, int k)
 
 __device__ __forceinline__ int lane_value(int v, int k) { return __builtin_amdgcn_readlane(v, k); }
 
+// Lane L receives the value of lane L - 1 (a wavefront-wide shift by one lane, DPP control wave_shr:1); lane 0, which
+// has no lane below it, receives +0.0.
+__device__ __forceinline__ double from_lane_below(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), 0x138, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), 0x138, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+
+// Running sums of one chunk of 64 non-negative values, one per lane, added strictly one after another in ascending
+// lane order starting from `carry`: lane L ends with ((carry + v_0) + v_1) + ... + v_L, every addition rounded on its
+// own.  Each pass hands every lane its lower neighbour's sum and adds the lane's own value (lane 0 adds carry + v_0
+// to the +0.0 it is handed, which is exact).  A lane's sum is final one pass after its lower neighbour's is, and
+// recomputing a final sum gives the same value again, so the passes need no lane test, no cross-lane read into
+// scalar registers and no LDS.  On entry lanes below `first` must already hold their final sums in r (what they held
+// after an earlier call whose values differed only at lanes >= first); the other lanes' r is ignored.  64 - first
+// passes finish the chunk; they run in blocks of eight, the surplus passes change nothing.
+__device__ __forceinline__ double ascending_sums(double mine, double carry, double r, int first)
+{
+    const double add = __lane_id() == 0 ? carry + mine : mine;
+    for (int blk = (64 - first + 7) >> 3; blk > 0; --blk) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r = from_lane_below(r) + add;
+    }
+    return r;
+}
+
+// Sixteen fp64 registers that a wave-uniform index can address (the compiler turns an indexed write into one
+// register-relative move)
+typedef double F16 __attribute__((ext_vector_type(16)));
+
 template <typename V> __device__ __forceinline__ const V* versions_of(const SelectArgs& a);
 template <> __device__ __forceinline__ const int* versions_of<int>(const SelectArgs& a) { return a.versions; }
 template <> __device__ __forceinline__ const double* versions_of<double>(const SelectArgs& a) { return a.versions_f64; }
@@ -67,27 +100,37 @@ template <> __device__ __forceinline__ const double* versions_of<double>(const S
 // remain), and within a draw the total S and the running sums add f in ascending replica index, one rounded fp64
 // addition after another: a chain of N dependent additions per draw that no reordering may touch, because the result
 // is compared bit for bit.  Everything else is taken off that chain: the uniforms of all draws are computed up
-// front (one Philox block per lane), f is computed once, and inside a chunk of 64 replicas the chain is a fully
-// unrolled run of v_add_f64 whose operands (cross-lane reads of the lanes' own values) do not depend on the chain.
+// front (one Philox block per lane), f is computed once, and a step of the chain is a single v_add_f64 from
+// registers when N <= 64 (a one-lane shift of the running sums and a v_add_f64 per step above that, ascending_sums).
+// One wavefront on its own issues a dependent instruction only every 5 to 8 clocks, so what counts is the number of
+// instructions on the path, and straight-line code that runs once is paid for in instruction fetches: the loops
+// below are kept short rather than unrolled over all 64 lanes.
 template <typename V>
 __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
 {
+    constexpr bool kIntVersions = std::is_same<V, int>::value;
     __shared__ double s_sorted[kMaxReplicas];
     __shared__ double s_f[kMaxReplicas];
     __shared__ double s_u[kMaxReplicas];
     __shared__ unsigned char s_flag[kMaxReplicas];
     __shared__ V s_v[kMaxReplicas];
     __shared__ unsigned char s_av[kMaxReplicas];
+    __shared__ long long s_key[kIntVersions ? kMaxReplicas : 1];
     const int lane = threadIdx.x, N = a.n;
 
     // versions and availability into LDS (one parallel load), then a rank-counting sort of the available versions:
-    // rank(i) = #{available j : v_j < v_i or (v_j == v_i and j < i)}.  Lanes own elements i = 64q + lane and walk all j
-    // chunk by chunk with cross-lane reads, so no step waits on memory.
+    // rank(i) = #{available j : v_j < v_i or (v_j == v_i and j < i)}.
     const int chunks = (N + 63) / 64;
-    for (int i = lane; i < N; i += 64) {
-        s_v[i] = versions_of<V>(a)[i];
-        s_av[i] = (!a.avail || a.avail[i]) ? 1 : 0;
-        s_flag[i] = 0;
+    for (int i = lane; i < chunks * 64; i += 64) {
+        const bool on = i < N && (!a.avail || a.avail[i]);
+        if (i < N) {
+            s_v[i] = versions_of<V>(a)[i];
+            s_av[i] = on ? 1 : 0;
+            s_flag[i] = 0;
+        }
+        // step counters: (version, index) pairs are ordered by one integer key, version * 1024 + index; a replica
+        // that is not available, or beyond N, gets the largest key and is counted before nobody
+        if constexpr (kIntVersions) s_key[i] = on ? (long long)versions_of<V>(a)[i] * kMaxReplicas + i : LLONG_MAX;
     }
     // the uniform of every draw: counter (cycle_lo, cycle_hi, draw, 0), key = seed, 53 bits of the first two words
     for (int t = lane; t < a.n_select; t += 64) {
@@ -98,25 +141,41 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
     }
     __syncthreads();
     int na = 0;
-    for (int q = 0; q < chunks; ++q) {
-        const int i = q * 64 + lane;
-        const V vi = i < N ? s_v[i] : V(0);
-        int rank = 0;
-        na = 0;
-        for (int c = 0; c < chunks; ++c) {
-            const int idx = c * 64 + lane;
-            const V vjm = idx < N ? s_v[idx] : V(0);
-            const unsigned long long mask = __ballot(idx < N && s_av[idx]);
-            na += __popcll(mask);
+    if constexpr (kIntVersions) {
+        // every lane compares its own key with all keys, read from LDS at a wave-uniform address (a broadcast)
+        for (int q = 0; q < chunks; ++q) {
+            const int i = q * 64 + lane;
+            const long long mine = s_key[i];
+            na += __popcll(__ballot(mine != LLONG_MAX));
+            int rank = 0;
+            for (int j = 0; j < chunks * 64; j += 16) {
 #pragma unroll
-            for (int k = 0; k < 64; ++k) {
-                const V vj = lane_value(vjm, k);
-                const int j = c * 64 + k;
-                const bool bj = (mask >> k) & 1ull;
-                rank += (bj && (vj < vi || (vj == vi && j < i))) ? 1 : 0;
+                for (int u = 0; u < 16; ++u) rank += s_key[j + u] < mine ? 1 : 0;
             }
+            if (mine != LLONG_MAX) s_sorted[rank] = (double)s_v[i];
         }
-        if (i < N && s_av[i]) s_sorted[rank] = (double)vi;
+    } else {
+        // real-valued versions: lanes own elements i = 64q + lane and walk all j chunk by chunk with cross-lane reads
+        for (int q = 0; q < chunks; ++q) {
+            const int i = q * 64 + lane;
+            const V vi = i < N ? s_v[i] : V(0);
+            int rank = 0;
+            na = 0;
+            for (int c = 0; c < chunks; ++c) {
+                const int idx = c * 64 + lane;
+                const V vjm = idx < N ? s_v[idx] : V(0);
+                const unsigned long long mask = __ballot(idx < N && s_av[idx]);
+                na += __popcll(mask);
+#pragma unroll
+                for (int k = 0; k < 64; ++k) {
+                    const V vj = lane_value(vjm, k);
+                    const int j = c * 64 + k;
+                    const int before = (int)(vj < vi) | ((int)(vj == vi) & (int)(j < i));
+                    rank += before & (int)((mask >> k) & 1ull);
+                }
+            }
+            if (i < N && s_av[i]) s_sorted[rank] = (double)vi;
+        }
     }
     __syncthreads();
     // third quartile: linear interpolation at 0.75*(na-1)
@@ -127,55 +186,118 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
     if (lo + 1 < na) mu = s_sorted[lo] + frac * (s_sorted[lo + 1] - s_sorted[lo]);
     __syncthreads();                                       // every lane has read the quartile before s_sorted is reused
 
-    for (int i = lane; i < N; i += 64) {
+    for (int i = lane; i < chunks * 64; i += 64) {         // f = +0.0 beyond N: the draws below need no bound test
         double f = 0.0;
-        if (s_av[i]) {
+        if (i < N && s_av[i]) {
             const double d = (double)s_v[i] - mu;
             double e = -(d * d) * 0.5;
             if (e < -690.0) e = -690.0;
             f = exp_neg(e);
         }
         s_f[i] = f;
-        a.f[i] = f;
+        if (i < N) a.f[i] = f;
     }
     __syncthreads();
 
-    // Sequential draws.  The wavefront walks the replicas in chunks of 64: every lane loads its own value once, then
-    // all lanes step through the chunk together, and lane k keeps the running sum after element k.  The total S is the
-    // last running sum; the pick is the first live element whose running sum exceeds u*S, found with one compare and a
-    // ballot.  Dead elements (picked, unavailable, or beyond N) add +0.0, which leaves a non-negative sum unchanged, so
-    // every chunk runs all 64 additions with no bound to test.
+    // Sequential draws: draw t picks the first live replica whose running sum of f exceeds u_t * S, S the total over
+    // the live replicas; dead replicas (picked, unavailable, or beyond N) add +0.0, which leaves a non-negative sum
+    // unchanged.
     int n_picked = 0;
-    for (int t = 0; t < a.n_select; ++t) {
-        double run = 0.0;
-        for (int c = 0; c < chunks; ++c) {
-            const int idx = c * 64 + lane;
-            const bool live = idx < N && !s_flag[idx] && s_f[idx] > 0.0;
-            const double mine = live ? s_f[idx] : 0.0;
-            double prefix = 0.0;
+    if (chunks == 1) {
+        // At most 64 replicas: the draws run from registers.  Lane L keeps g[j] = f_j for j <= L and +0.0 above, so
+        // the plain chain ((0 + g[0]) + g[1]) + ... + g[63], the same instructions in every lane and no lane
+        // waiting for another, leaves lane L with the running sum after replica L (the zeros above L change nothing)
+        // and lane 63 with S.  A dependent v_add_f64 issues every 5 to 6 clocks, a quarter of what one step costs
+        // when the running sum has to move to the next lane.  A picked replica is zeroed in every lane's g.
+        F16 g0, g1, g2, g3, g4;
 #pragma unroll
-            for (int k = 0; k < 64; ++k) {
-                run = run + lane_value(mine, k);
-                prefix = (lane == k) ? run : prefix;
+        for (int k = 0; k < 15; ++k) {
+            g0[k] = k <= lane ? s_f[k] : 0.0;
+            g1[k] = 15 + k <= lane ? s_f[15 + k] : 0.0;
+            g2[k] = 30 + k <= lane ? s_f[30 + k] : 0.0;
+            g3[k] = 45 + k <= lane ? s_f[45 + k] : 0.0;
+            g4[k] = (k < 4 && 60 + k <= lane) ? s_f[60 + k] : 0.0;
+        }
+        g0[15] = 0.0; g1[15] = 0.0; g2[15] = 0.0; g3[15] = 0.0; g4[15] = 0.0;
+        unsigned long long livemask = __ballot(s_f[lane] > 0.0);
+        const unsigned long long could = livemask;
+        const double my_u = lane < a.n_select ? s_u[lane] : 0.0;
+        int my_pick = -1;
+        for (int t = 0; t < a.n_select; ++t) {
+            double q = 0.0;
+#pragma unroll
+            for (int k = 0; k < 15; ++k) q = q + g0[k];
+#pragma unroll
+            for (int k = 0; k < 15; ++k) q = q + g1[k];
+#pragma unroll
+            for (int k = 0; k < 15; ++k) q = q + g2[k];
+#pragma unroll
+            for (int k = 0; k < 15; ++k) q = q + g3[k];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) q = q + g4[k];
+            const double S = lane_value(q, 63);
+            const double thr = lane_value(my_u, t) * S;
+            const unsigned long long hit = __ballot(q > thr) & livemask;
+            int pick = -1;
+            if (hit) pick = __ffsll((long long)hit) - 1;
+            else if (livemask) pick = 63 - __clzll(livemask);   // stays -1 only if no replica is left to draw from
+            pick = __builtin_amdgcn_readfirstlane(pick);
+            if (lane == t) my_pick = pick;
+            // the picked replica leaves every lane's g: one register-indexed write per group, aimed at the spare
+            // sixteenth element in the groups that do not hold it (and in all of them when nothing was picked)
+            const int grp = pick >= 0 ? pick / 15 : 5, slot = pick - 15 * grp;
+            g0[grp == 0 ? slot : 15] = 0.0;
+            g1[grp == 1 ? slot : 15] = 0.0;
+            g2[grp == 2 ? slot : 15] = 0.0;
+            g3[grp == 3 ? slot : 15] = 0.0;
+            g4[grp == 4 ? slot : 15] = 0.0;
+            if (pick >= 0) {
+                ++n_picked;
+                livemask &= ~(1ull << pick);
             }
-            if (idx < N) s_sorted[idx] = prefix;          // s_sorted is free after the quartile: reuse as prefix store
         }
-        const double S = run;
-        const double thr = s_u[t] * S;
-        int pick = -1, last = -1;
-        for (int c = 0; c < chunks; ++c) {
-            const int idx = c * 64 + lane;
-            const bool live = idx < N && !s_flag[idx] && s_f[idx] > 0.0;
-            const unsigned long long lm = __ballot(live);
-            const unsigned long long hit = __ballot(live && s_sorted[idx < N ? idx : 0] > thr);
-            if (lm) last = c * 64 + 63 - __clzll(lm);
-            if (pick < 0 && hit) pick = c * 64 + __ffsll((long long)hit) - 1;
+        if (lane < a.n_select) a.selected[lane] = my_pick;
+        if (lane < N) s_flag[lane] = (unsigned char)(((could & ~livemask) >> lane) & 1ull);
+        __syncthreads();
+    } else {
+        // Sequential draws.  The wavefront walks the replicas in chunks of 64: every lane loads its own value once and
+        // ends with the running sum after its element (ascending_sums), the last lane's carries into the next chunk.  The
+        // total S is the last running sum; the pick is the first live element whose running sum exceeds u*S, found with one
+        // compare and a ballot.  Dead elements (picked, unavailable, or beyond N) add +0.0, which leaves a non-negative sum
+        // unchanged, so every chunk runs all 64 additions with no bound to test.
+        //
+        // Draw t + 1 differs from draw t in one element, the replica p picked last: the running sums below p are the same
+        // additions of the same values and are kept (in LDS, s_sorted is free after the quartile), the chain restarts at p.
+        int changed = 0;                                       // lowest replica whose running sum is not valid
+        for (int t = 0; t < a.n_select; ++t) {
+            const int c0 = changed >> 6;
+            double run = c0 > 0 ? s_sorted[c0 * 64 - 1] : 0.0;
+            for (int c = c0; c < chunks; ++c) {
+                const int idx = c * 64 + lane;
+                const bool live = idx < N && !s_flag[idx] && s_f[idx] > 0.0;
+                const int first = c == c0 ? (changed & 63) : 0;
+                const double prefix = ascending_sums(live ? s_f[idx] : 0.0, run, idx < N ? s_sorted[idx] : 0.0, first);
+                if (idx < N) s_sorted[idx] = prefix;
+                run = lane_value(prefix, 63);
+            }
+            const double S = run;
+            const double thr = s_u[t] * S;
+            int pick = -1, last = -1;
+            for (int c = 0; c < chunks; ++c) {
+                const int idx = c * 64 + lane;
+                const bool live = idx < N && !s_flag[idx] && s_f[idx] > 0.0;
+                const unsigned long long lm = __ballot(live);
+                const unsigned long long hit = __ballot(live && s_sorted[idx < N ? idx : 0] > thr);
+                if (lm) last = c * 64 + 63 - __clzll(lm);
+                if (pick < 0 && hit) pick = c * 64 + __ffsll((long long)hit) - 1;
+            }
+            if (pick < 0) pick = last;                         // stays -1 only if no replica is left to draw from
+            n_picked += pick >= 0 ? 1 : 0;
+            __syncthreads();
+            if (lane == 0) { a.selected[t] = pick; if (pick >= 0) s_flag[pick] = 1; }
+            changed = pick >= 0 ? pick : N;                     // nothing left: later draws change nothing either
+            __syncthreads();
         }
-        if (pick < 0) pick = last;                         // stays -1 only if no replica is left to draw from
-        n_picked += pick >= 0 ? 1 : 0;
-        __syncthreads();
-        if (lane == 0) { a.selected[t] = pick; if (pick >= 0) s_flag[pick] = 1; }
-        __syncthreads();
     }
 
     // aggregation weights a_k and the ascending list the aggregate kernel walks.  With unit terms the denominator is
@@ -186,9 +308,7 @@ __global__ __launch_bounds__(64) void select_kernel(SelectArgs a)
         denom = 0.0;
         for (int c = 0; c < chunks; ++c) {
             const int idx = c * 64 + lane;
-            const double mine = (idx < N && s_flag[idx]) ? s_f[idx] : 0.0;
-#pragma unroll
-            for (int k = 0; k < 64; ++k) denom = denom + lane_value(mine, k);
+            denom = lane_value(ascending_sums((idx < N && s_flag[idx]) ? s_f[idx] : 0.0, denom, 0.0, 0), 63);
         }
     }
     int before = 0;                                        // selected replicas in earlier chunks
