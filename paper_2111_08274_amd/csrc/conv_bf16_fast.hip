@@ -242,8 +242,9 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
                 const unsigned o = (unsigned)(pix * p.N + n) * 2u;
                 f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
                 bf16x4 mk = {};
+                f4 sh = {0.f, 0.f, 0.f, 0.f};                  // what the statistics are centred on: the bias
                 if (EPI == 0) {
-                    if (bias) v += *reinterpret_cast<const f4*>(bias + n);
+                    if (bias) { sh = *reinterpret_cast<const f4*>(bias + n); v += sh; }
                     if (p.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
                 } else {
                     if (mask) {
@@ -264,7 +265,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
                 if (stats) {
                     if (EPI == 0) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) { const float f = (float)r[e]; ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * f; }
+                        for (int e = 0; e < 4; ++e) { const float f = (float)r[e] - sh[e]; ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * f; }
                     } else {
                         // the mask of a fused ReLU is that very tensor: its values are already here
                         const bf16x4 yv = y_is_mask ? mk : *reinterpret_cast<const bf16x4*>(ysrc + o);
@@ -441,8 +442,9 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
                 const unsigned o = (unsigned)(mm * p.N + n) * 2u;
                 f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
                 bf16x4 mk = {};
+                f4 sh = {0.f, 0.f, 0.f, 0.f};                  // what the statistics are centred on: the bias
                 if (EPI == 0) {
-                    if (bias) v += *reinterpret_cast<const f4*>(bias + n);
+                    if (bias) { sh = *reinterpret_cast<const f4*>(bias + n); v += sh; }
                     if (p.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
                 } else {
                     if (mask) {
@@ -463,7 +465,7 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
                 if (stats) {
                     if (EPI == 0) {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) { const float f = (float)r[e]; ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * f; }
+                        for (int e = 0; e < 4; ++e) { const float f = (float)r[e] - sh[e]; ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * f; }
                     } else {
                         // the mask of a fused ReLU is that very tensor: its values are already here
                         const bf16x4 yv = y_is_mask ? mk : *reinterpret_cast<const bf16x4*>(ysrc + o);

@@ -204,8 +204,9 @@ __global__ __launch_bounds__(WGM * WGN * 64, 2) void conv_f32_kernel(FastConvPar
                 const int n = n0 + wn * (BN / WGN) + j * 32 + 8 * g + 4 * (lane >> 5);
                 const long long o = (long long)pix * p.N + n;
                 f4 v = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                f4 sh = {0.f, 0.f, 0.f, 0.f};                  // what the statistics are centred on: the bias
                 if (EPI == 0) {
-                    if (bias) v += *reinterpret_cast<const f4*>(bias + n);
+                    if (bias) { sh = *reinterpret_cast<const f4*>(bias + n); v += sh; }
                     if (p.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
                 } else {
                     if (mask) {
@@ -218,7 +219,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, 2) void conv_f32_kernel(FastConvPar
                 *reinterpret_cast<f4*>(obase + o) = v;
                 if (stats) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { ss[j][4 * g + e] += v[e]; qq[j][4 * g + e] += v[e] * v[e]; }
+                    for (int e = 0; e < 4; ++e) { const float f = v[e] - sh[e]; ss[j][4 * g + e] += f; qq[j][4 * g + e] += f * f; }
                 }
             }
         }

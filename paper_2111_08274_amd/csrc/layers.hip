@@ -601,7 +601,9 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(BnParams p)
     s = red[0][cl][0]; q = red[0][cl][1];
     if (MODE == 0) {
         const float n = (float)p.rows;
-        const float x0 = p.stats_done ? 0.f : ldf(tptr<T>(p.x, rep, p.x_rep), c);   // the shift the sums were taken with
+        // the shift the sums were taken with: the producing convolution's bias, or the tensor's first row
+        const float x0 = p.stats_done ? (p.stat_shift ? p.stat_shift[rep * p.stat_shift_rep + c] : 0.f)
+                                      : ldf(tptr<T>(p.x, rep, p.x_rep), c);
         const float md = s / n;                               // mean of the shifted values
         const float cen = fmaxf(q - s * md, 0.f);             // sum of squared deviations from the mean
         const float mean = x0 + md, var = cen / n;

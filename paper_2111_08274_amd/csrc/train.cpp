@@ -567,6 +567,8 @@ struct Runner {
             if (e.stat_from[i] >= 0 && e.stat_rows[i] > 0) {          // the convolution in front left the sums
                 b.stats_done = 1; b.stat_entries = (b.rows + e.stat_rows[i] - 1) / e.stat_rows[i];
                 b.partial_rep = ((int64_t)b.rows + 127) / 128 * 2 * b.C;
+                const Layer& conv = e.plan.layers[e.stat_from[i]];
+                b.stat_shift = conv.bias ? e.buf.replicas + conv.b_off : nullptr; b.stat_shift_rep = e.plan.row_stride;
             }
             if (e.pool_of[i] >= 0) {
                 b.pool = 1; b.H = a.h; b.W = a.w;

@@ -178,9 +178,11 @@ struct BnParams {
     // a 2x2 / stride-2 max-pool folded into the layer (vector kernels only; H, W even): forward also writes the pooled
     // output; backward takes the gradient of the pooled output and the stored forward output instead of dy
     int pool, H, W;
-    // forward: the producing convolution already left per-entry sums of x and x^2 in `partial` ([stat_entries][2][C]); the
-    // sums pass is skipped and the shift of the one-pass variance is zero
+    // forward: the producing convolution already left per-entry sums of d = x - x0 and d^2 in `partial`
+    // ([stat_entries][2][C]) and the sums pass is skipped; the shift x0 of channel c is that convolution's bias
+    // stat_shift[c] (zero without one): what the outputs are centred on when the bias is large beside their spread
     int stats_done, stat_entries;
+    const float* stat_shift; long long stat_shift_rep;
     // backward: the data-gradient kernel of the layer above already left per-entry sums of g and g * y in `partial`
     // ([stat_entries][2][C], see FastConvParams::stat_y); the sums pass is skipped and d(gamma) is formed from them
     int bwd_stats_done;

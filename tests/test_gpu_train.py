@@ -256,3 +256,26 @@ def test_lean_fp32_kernels_position_sorted_rows(hint):
     assert d <= TOL
     assert np.abs(p.gpu.losses() - p.cpu.loss).max() <= 1e-4
     p.close()
+
+
+@pytest.mark.parametrize("bf16,bias", [(False, 200.0), (True, 8.0)])
+def test_batch_norm_statistics_from_a_convolution_with_a_large_bias(bf16, bias):
+    """A convolution whose bias is large beside the spread of its outputs, followed by a batch norm that takes its
+    statistics from that convolution's epilogue (64 channels: the lean kernels).  Sums of x and x^2 taken about zero
+    would lose the variance to cancellation in fp32 (mean^2 / var = 4e4 here: an error of 1e-2 in the variance); the
+    epilogue centres them on the bias.  (In the workloads a bias in front of a batch norm has zero gradient and
+    stays where the initialisation put it.)"""
+    b = nets._Builder()
+    t = b.relu(b.conv(0, 64))
+    t = b.relu(b.bn(b.conv(t, 64)))
+    b.dense(b.gap(t), 5)
+    ops, shape, batch = b.array(), (8, 8, 3), 32
+    N = 2
+    x, y = _data(N, 2 * batch, shape, 5, seed=93)
+    p = Pair(ops, shape, N, 1, x, y, batch, 0.01, 0.9, [2, 1], bf16=bf16)
+    second_bias = [(o, c) for o, c, k, _ in p.layout if k == "bias"][1]
+    p.cpu.params[:, second_bias[0]:second_bias[0] + second_bias[1]] = bias
+    w = p.forced_steps()
+    print("large bias before BN, bf16 %d: updates %s" % (bf16, pm.show(w)), flush=True)
+    assert w["compared"] > 0 and w["ill"] == 0
+    p.close()
