@@ -27,13 +27,22 @@ PAPER_CONTEXT = {"speedup_vs_decentralized_fedavg": 3.15, "speedup_vs_pytorch_di
 TRAFFIC = {
     ("aggregate", "agg-stress-n64"): (("paper_2111_08274_amd/csrc/aggregate.hip",),
                                       "ee3f9871add01e241b80b96d0fcdd3250747a0ef8da76f148d5575daca1ed43f",
-                                      402288103.0),
-    # all weight-gradient launches of a cycle, averaged (the figure includes the fused update's parameter traffic)
-    ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
-                                        "paper_2111_08274_amd/csrc/conv_first_bf16.hip",
+                                      402288271.6),
+    # all launches of the class in a cycle, averaged
+    ("conv_dgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_stats.h"),
-                                       "d78fd9aa4c1e9d65725e24af3a24aa46b63359f9e285fc3cd45236bc0e4960ff",
-                                       547779490.0),
+                                       "ed0fd9b393b07a21972f37eb9cf8048eeed72044c964814b0af1914330abed37",
+                                       460940902.2),
+    ("conv_fwd", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
+                                      "paper_2111_08274_amd/csrc/conv_first_bf16.hip",
+                                      "paper_2111_08274_amd/csrc/conv_stats.h"),
+                                     "fdc2f27968050b8bbc296229bcb9bfb1adee3cc1041810ffd571ad101ce40ad7",
+                                     324472793.4),
+    # (the figure includes the fused update's parameter and momentum traffic)
+    ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
+                                        "paper_2111_08274_amd/csrc/conv_first_bf16.hip"),
+                                       "bb416b92057a5e2d5bd35ebd8a38da96ab2387a020885aa5f471c66876345837",
+                                       547863789.3),
 }
 
 
