@@ -521,6 +521,25 @@ __device__ __forceinline__ PoolWin pool_window(const BnParams& p, int w, int c)
 
 // A workgroup takes 32 channels; eight threads per channel add the per-chunk partial sums (chunks k, k+8, ..) and a
 // fixed-order tree over the eight joins them.
+// Scale and shift of the normalisation and the stored output of one element.  The kernels of a batch norm with a
+// folded max-pool do not keep the full-resolution output: the backward ones form a window's four outputs again from x.
+// Both directions go through these two functions -- explicit fused multiply-adds, the rounding of the stored type --
+// so the values compared for the window's maximum are bit for bit the ones the forward pass took the maximum of.
+__device__ __forceinline__ void bn_scale_shift(float mean, float istd, float gamma, float beta, float& sc, float& sh)
+{
+    sc = gamma * istd;
+    sh = __builtin_fmaf(-mean, sc, beta);
+}
+__device__ __forceinline__ float bn_value(float x, float sc, float sh, bool relu)
+{
+    const float t = __builtin_fmaf(x, sc, sh);
+    return relu ? fmaxf(t, 0.f) : t;
+}
+template <typename T> __device__ __forceinline__ float bn_stored_value(float x, float sc, float sh, bool relu)
+{
+    return (float)(T)bn_value(x, sc, sh, relu);
+}
+
 // MODE 0: mean and 1/sqrt(var+eps) -> saved, running statistics updated.  x0 is the shift used by the sums pass.
 // MODE 1: totals of dy and dy*xhat -> gradient of beta and gamma, and into chunk 0 of the partial buffer.
 template <int MODE, typename T>
@@ -567,15 +586,22 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(BnParams p)
                     ts += d; tq += d * ((ldf(x, (long long)r * p.C + cj) - mean) * istd);
                 }
             } else {
-                const T* yo = tptr<T>(p.pool_y, rep, p.pool_y_rep);
                 const T* pg = tptr<T>(p.pool_g, rep, p.pool_g_rep);
+                const float* row = p.params + rep * p.row_stride + p.w_off;
+                float sc, sh;
+                bn_scale_shift(mean, istd, row[cj], row[p.C + cj], sc, sh);
                 for (int w = threadIdx.x; w < p.rows / 4; w += 256) {
                     const PoolWin pw = pool_window(p, w, cj);
-                    float m = ldf(yo, pw.q[0]); int arg = 0;
-                    for (int t = 1; t < 4; ++t) { const float v = ldf(yo, pw.q[t]); if (v > m) { m = v; arg = t; } }   // first maximum
+                    float xw[4];
+                    for (int t = 0; t < 4; ++t) xw[t] = ldf(x, pw.q[t]);
+                    float m = bn_stored_value<T>(xw[0], sc, sh, p.relu != 0), xs = xw[0];
+                    for (int t = 1; t < 4; ++t) {             // first maximum of the window's (recomputed) outputs
+                        const float v = bn_stored_value<T>(xw[t], sc, sh, p.relu != 0);
+                        if (v > m) { m = v; xs = xw[t]; }
+                    }
                     if (p.relu && !(m > 0.f)) continue;       // the fused ReLU passes nothing there
                     const float d = ldf(pg, pw.o);
-                    ts += d; tq += d * ((ldf(x, pw.q[arg]) - mean) * istd);
+                    ts += d; tq += d * ((xs - mean) * istd);
                 }
             }
             s_red[threadIdx.x][0] = ts; s_red[threadIdx.x][1] = tq;
@@ -636,9 +662,7 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_vec_kernel(BnParams p)
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
         const int c = g.c + e;
-        const float mean = sv[c], istd = sv[p.C + c];
-        const float gamma = row[p.w_off + c], beta = row[p.w_off + p.C + c];
-        sc[e] = gamma * istd; sh[e] = beta - mean * gamma * istd;
+        bn_scale_shift(sv[c], sv[p.C + c], row[p.w_off + c], row[p.w_off + p.C + c], sc[e], sh[e]);
     }
     const int r0 = g.chunk * p.chunk_rows, r1 = min(p.rows, r0 + p.chunk_rows);
 #pragma unroll 4
@@ -647,7 +671,7 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_vec_kernel(BnParams p)
         const long long i = (long long)r * p.C + g.c;
         ldv(x, i, v);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) { const float t = v[e] * sc[e] + sh[e]; v[e] = p.relu ? fmaxf(t, 0.f) : t; }
+        for (int e = 0; e < VEC; ++e) v[e] = bn_value(v[e], sc[e], sh[e], p.relu != 0);
         stv(y, i, v);
     }
 }
@@ -715,7 +739,6 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_pool_vec_kernel(BnParams p)
     const BnGeo g = bn_geo(p, VEC);
     if (!g.live) return;
     const T* x = tptr<T>(p.x, rep, p.x_rep);
-    T* y = tptr<T>(p.y, rep, p.y_rep);
     T* po = tptr<T>(p.pool_out, rep, p.pool_out_rep);
     const float* row = p.params + rep * p.row_stride;
     float sc[VEC], sh[VEC];
@@ -723,9 +746,7 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_pool_vec_kernel(BnParams p)
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
         const int c = g.c + e;
-        const float mean = sv[c], istd = sv[p.C + c];
-        const float gamma = row[p.w_off + c], beta = row[p.w_off + p.C + c];
-        sc[e] = gamma * istd; sh[e] = beta - mean * gamma * istd;
+        bn_scale_shift(sv[c], sv[p.C + c], row[p.w_off + c], row[p.w_off + p.C + c], sc[e], sh[e]);
     }
     const int windows = p.rows / 4, cw = (windows + p.chunks - 1) / p.chunks;
     const int w0 = g.chunk * cw, w1 = min(windows, w0 + cw);
@@ -738,9 +759,8 @@ __global__ __launch_bounds__(256) void bn_apply_fwd_pool_vec_kernel(BnParams p)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) { const float t = v[j][e] * sc[e] + sh[e]; v[j][e] = p.relu ? fmaxf(t, 0.f) : t; }
-            stv(y, pw.q[j], v[j]);
-        }
+            for (int e = 0; e < VEC; ++e) v[j][e] = bn_value(v[j][e], sc[e], sh[e], p.relu != 0);
+        }                                                     // (the four outputs themselves are not stored)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) m[e] = fmaxf(fmaxf(v[0][e], v[1][e]), fmaxf(v[2][e], v[3][e]));
         stv(po, pw.o, m);
@@ -768,15 +788,18 @@ __global__ __launch_bounds__(256) void bn_sums_pool_vec_kernel(BnParams p)
     const int gi = blockIdx.y, rep = p.order[gi];
     const BnGeo g = bn_geo(p, VEC);
     const T* x = tptr<T>(p.x, rep, p.x_rep);
-    const T* yo = tptr<T>(p.pool_y, rep, p.pool_y_rep);
     const T* pg = tptr<T>(p.pool_g, rep, p.pool_g_rep);
-    float s0[VEC], s1[VEC], a[VEC], b[VEC];
+    float s0[VEC], s1[VEC], a[VEC], b[VEC], sc[VEC], sh[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) { s0[e] = 0.f; s1[e] = 0.f; a[e] = 0.f; b[e] = 1.f; }
+    for (int e = 0; e < VEC; ++e) { s0[e] = 0.f; s1[e] = 0.f; a[e] = 0.f; b[e] = 1.f; sc[e] = 0.f; sh[e] = 0.f; }
     if (g.live) {
         const float* sv = p.saved + rep * p.saved_rep;
+        const float* row = p.params + rep * p.row_stride + p.w_off;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) { a[e] = sv[g.c + e]; b[e] = sv[p.C + g.c + e]; }
+        for (int e = 0; e < VEC; ++e) {
+            a[e] = sv[g.c + e]; b[e] = sv[p.C + g.c + e];
+            bn_scale_shift(a[e], b[e], row[g.c + e], row[p.C + g.c + e], sc[e], sh[e]);
+        }
         const int windows = p.rows / 4, cw = (windows + p.chunks - 1) / p.chunks;
         const int w0 = g.chunk * cw, w1 = min(windows, w0 + cw);
 #pragma unroll 2
@@ -785,7 +808,11 @@ __global__ __launch_bounds__(256) void bn_sums_pool_vec_kernel(BnParams p)
             float yv[4][VEC], xv[4][VEC], gv[VEC];
             int arg[VEC];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { ldv(yo, pw.q[j], yv[j]); ldv(x, pw.q[j], xv[j]); }
+            for (int j = 0; j < 4; ++j) {
+                ldv(x, pw.q[j], xv[j]);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) yv[j][e] = bn_stored_value<T>(xv[j][e], sc[e], sh[e], p.relu != 0);
+            }
             ldv(pg, pw.o, gv);
             pool_argmax<VEC>(yv, p.relu != 0, arg);
 #pragma unroll
@@ -823,21 +850,22 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_pool_vec_kernel(BnParams p)
     const BnGeo g = bn_geo(p, VEC);
     if (!g.live) return;
     const T* x = tptr<T>(p.x, rep, p.x_rep);
-    const T* yo = tptr<T>(p.pool_y, rep, p.pool_y_rep);
     const T* pg = tptr<T>(p.pool_g, rep, p.pool_g_rep);
     T* dx = tptr<T>(p.y, rep, p.y_rep);
     const T* mask = p.mask ? tptr<T>(p.mask, rep, p.mask_rep) : nullptr;
     const float* part = p.partial + gi * p.partial_rep;
     const float* sv = p.saved + rep * p.saved_rep;
     const float inv_n = 1.0f / (float)p.rows;
-    float mean[VEC], istd[VEC], k1[VEC], kb[VEC], kg[VEC];
+    float mean[VEC], istd[VEC], k1[VEC], kb[VEC], kg[VEC], sc[VEC], sh[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
         const int c = g.c + e;
         const float db = part[c], dg = part[p.C + c];       // totals left in chunk 0 by bn_finalize_kernel<1>
+        const float* row = p.params + rep * p.row_stride + p.w_off;
         mean[e] = sv[c]; istd[e] = sv[p.C + c];
-        k1[e] = p.params[rep * p.row_stride + p.w_off + c] * istd[e];
+        k1[e] = row[c] * istd[e];
         kb[e] = db * inv_n; kg[e] = dg * inv_n;
+        bn_scale_shift(mean[e], istd[e], row[c], row[p.C + c], sc[e], sh[e]);
     }
     const int windows = p.rows / 4, cw = (windows + p.chunks - 1) / p.chunks;
     const int w0 = g.chunk * cw, w1 = min(windows, w0 + cw);
@@ -847,7 +875,11 @@ __global__ __launch_bounds__(256) void bn_apply_bwd_pool_vec_kernel(BnParams p)
         float yv[4][VEC], xv[4][VEC], gv[VEC];
         int arg[VEC];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { ldv(yo, pw.q[j], yv[j]); ldv(x, pw.q[j], xv[j]); }
+        for (int j = 0; j < 4; ++j) {
+            ldv(x, pw.q[j], xv[j]);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) yv[j][e] = bn_stored_value<T>(xv[j][e], sc[e], sh[e], p.relu != 0);
+        }
         ldv(pg, pw.o, gv);
         pool_argmax<VEC>(yv, p.relu != 0, arg);
 #pragma unroll
@@ -1092,7 +1124,7 @@ hipError_t launch_bn_bwd(const BnParams& p0, int n_active, hipStream_t s)
         p.cvb = bn_cvb(p.C, vec);
         const int cgroups = (p.C / vec + p.cvb - 1) / p.cvb;
         const dim3 grid((unsigned)(p.chunks * cgroups), (unsigned)n_active), fgrid((unsigned)((p.C + 31) / 32), (unsigned)n_active);
-        if (p.pool && (p.H % 2 != 0 || p.W % 2 != 0 || p.rows % 4 != 0 || !p.pool_y || !p.pool_g)) return hipErrorInvalidValue;
+        if (p.pool && (p.H % 2 != 0 || p.W % 2 != 0 || p.rows % 4 != 0 || !p.pool_g)) return hipErrorInvalidValue;
         if (p.bf16) {
             if (p.bwd_stats_done) {}                                  // the data gradient above left the sums
             else if (p.pool) hipLaunchKernelGGL(bn_sums_pool_vec_kernel<__bf16>, grid, block, 0, s, p);

@@ -773,7 +773,6 @@ struct Runner {
             b.mask = mask0; b.mask_rep = e.rep_block;
             if (e.pool_of[i] >= 0) {
                 b.pool = 1; b.H = a.h; b.W = a.w; b.relu = e.fused_relu[i];
-                b.pool_y = act(ot); b.pool_y_rep = e.rep_block;
                 b.pool_g = grad(e.plan.layers[e.pool_of[i]].out); b.pool_g_rep = e.rep_block;
             }
             if (e.bstat_rows[i] > 0) {                       // the data gradient of the layer above left the sums

@@ -175,8 +175,9 @@ struct BnParams {
     const float* mask; long long mask_rep; // backward: zero dx where mask <= 0
     int bf16;
     const int* order;
-    // a 2x2 / stride-2 max-pool folded into the layer (vector kernels only; H, W even): forward also writes the pooled
-    // output; backward takes the gradient of the pooled output and the stored forward output instead of dy
+    // a 2x2 / stride-2 max-pool folded into the layer (vector kernels only; H, W even): forward writes the pooled
+    // output only; backward takes the gradient of the pooled output instead of dy and forms each window's outputs
+    // again from x
     int pool, H, W;
     // forward: the producing convolution already left per-entry sums of d = x - x0 and d^2 in `partial`
     // ([stat_entries][2][C]) and the sums pass is skipped; the shift x0 of channel c is that convolution's bias
@@ -187,7 +188,6 @@ struct BnParams {
     // ([stat_entries][2][C], see FastConvParams::stat_y); the sums pass is skipped and d(gamma) is formed from them
     int bwd_stats_done;
     float* pool_out; long long pool_out_rep;
-    const float* pool_y; long long pool_y_rep;
     const float* pool_g; long long pool_g_rep;
 };
 hipError_t launch_bn_fwd(const BnParams& p, int n_active, hipStream_t s);
