@@ -760,7 +760,8 @@ __global__ __launch_bounds__(WGM * WGN * 64, WGM * WGN == 8 ? 1 : 3) void wgrad_
 // per slab of 32 pixels (whole image rows) it loads those rows with their one-pixel border ONCE into LDS and forms
 // the nine shifted operands from that patch by offsetting the row the transposing read points at.
 // Waves: (input-channel half, output-channel half); each keeps nine 32 x 32 blocks (one per tap), the waves of the
-// first half of slice 0 also the bias row.  IW = image width; 3 x 3 filter, pad 1.
+// first half of slice 0 also the bias row.  IW = image width (a slab is 32 / IW whole rows of one image, so the image
+// height is a multiple of that); 3 x 3 filter, pad 1.
 template <int IW>
 __global__ __launch_bounds__(256, 2) void wgrad_taps_kernel(FastWgradParams p)
 {
@@ -1001,11 +1002,16 @@ hipError_t launch_wgrad_fast(const FastWgradParams& p0, int n_active, hipStream_
     p.n_active = n_active;
     if (p.C % 8 != 0 || p.N % 64 != 0) return hipErrorInvalidValue;
     // wide images with at most 128 channels in and out: all taps from one patch
-    if ((p.W == 16 || p.W == 32) && p.C <= 128 && p.N <= 128 && p.C % 64 == 0 && p.R == 3 && p.S == 3 && p.pad == 1 && !p.perm &&
+    const bool wide = (p.W == 16 || p.W == 32) && p.C <= 128 && p.N <= 128 && !p.perm;
+    const bool eight = p.W == 8 && p.H % 4 == 0;             // (the kernel walks pixels in memory order: no position table)
+    if ((wide || eight) && p.C % 64 == 0 && p.R == 3 && p.S == 3 && p.pad == 1 &&
         (p.H * p.W) % 32 == 0 && p.K % 32 == 0 && (p.splits == 1 || p.kchunk % 32 == 0) && p.M == 9 * p.C + (p.has_bias ? 1 : 0) &&
         p.tile_hint != 2) {
         const dim3 grid(die_grid((long long)(p.C / 64) * (p.N / 64) * p.splits * n_active));
-        if (p.W == 32) {
+        if (p.W == 8) {
+            constexpr size_t lds = 2 * ((size_t)6 * 10 + 32) * 192;
+            hipLaunchKernelGGL(wgrad_taps_kernel<8>, grid, dim3(256), lds, s, p);
+        } else if (p.W == 32) {
             constexpr size_t lds = 2 * ((size_t)3 * 34 + 32) * 192;
             hipLaunchKernelGGL(wgrad_taps_kernel<32>, grid, dim3(256), lds, s, p);
         } else {

@@ -649,7 +649,7 @@ struct Runner {
                 // The planned split count fills the chip when every replica is active.  A sub-step with fewer active
                 // replicas splits K further; the partial-sum buffer (sized for all replicas at the planned count) and
                 // K bound how far.  Wide-image layers run the all-taps kernel with one tile per 64 x 64 channel pair.
-                const bool wide = (p.W == 16 || p.W == 32) && p.Cin <= 128 && p.N <= 128;
+                const bool wide = ((p.W == 16 || p.W == 32) && p.Cin <= 128 && p.N <= 128) || (p.W == 8 && p.H % 4 == 0);
                 const int64_t tiles = wide ? (int64_t)(p.Cin / 64) * (p.N / 64) : ((p.M + 127) / 128) * ((p.N + 127) / 128);
                 const int64_t want = (1024 + tiles * na - 1) / (tiles * na);
                 const int64_t by_buffer = e.shared_floats / ((int64_t)na * ((mn + 63) / 64 * 64));
