@@ -27,22 +27,22 @@ PAPER_CONTEXT = {"speedup_vs_decentralized_fedavg": 3.15, "speedup_vs_pytorch_di
 TRAFFIC = {
     ("aggregate", "agg-stress-n64"): (("paper_2111_08274_amd/csrc/aggregate.hip",),
                                       "ee3f9871add01e241b80b96d0fcdd3250747a0ef8da76f148d5575daca1ed43f",
-                                      402288271.6),
+                                      402288378.1),
     # all launches of the class in a cycle, averaged
     ("conv_dgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_stats.h"),
-                                       "ed0fd9b393b07a21972f37eb9cf8048eeed72044c964814b0af1914330abed37",
-                                       460940902.2),
+                                       "d03050f1d06eee94815acfd1ae351bdf8e4f6cb8a2cb6f23da16edd8b923d1d5",
+                                       460902536.0),
     ("conv_fwd", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                       "paper_2111_08274_amd/csrc/conv_first_bf16.hip",
                                       "paper_2111_08274_amd/csrc/conv_stats.h"),
-                                     "fdc2f27968050b8bbc296229bcb9bfb1adee3cc1041810ffd571ad101ce40ad7",
-                                     324472793.4),
+                                     "9c93fa2bd96b8f519b6420310fc1d01b8e116146a262addd8cdf1517865bb269",
+                                     324264002.9),
     # (the figure includes the fused update's parameter and momentum traffic)
     ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_first_bf16.hip"),
-                                       "bb416b92057a5e2d5bd35ebd8a38da96ab2387a020885aa5f471c66876345837",
-                                       547863789.3),
+                                       "6e452c202dc1cbb8154e84389d0ce3cc0acaa619cf32d6f4c61b81a411c79572",
+                                       552066643.7),
 }
 
 
