@@ -290,7 +290,7 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
 }
 
 // Wide images (16 or 32 pixels per row) with few channels move more bytes per multiply-add than the general kernel can
-// fetch: it reads every activation once per tap.  Here a workgroup owns 256 consecutive pixels of one image (whole
+// fetch: it reads every activation once per tap.  Here a workgroup owns BMT consecutive pixels of one image (whole
 // rows), loads them ONCE per 64-channel slice together with their one-pixel border (zeros outside the image) into
 // LDS, and serves all R*S taps from that patch by shifting the row it reads; only the weights still stream per tap.
 // IW = image width; 3x3-style filters with pad = (R-1)/2 <= 1.
@@ -298,20 +298,23 @@ __global__ __launch_bounds__(WGM * WGN * 64, NBUF == 2 && WGM * WGN == 8 ? 1 : 2
 // second row starts a multiple of 256 bytes after the first (measured: half rate otherwise), so patch rows are padded
 // to kPatchRowBytes<16>.
 template <int IW> constexpr int kPatchRowBytes = IW == 16 ? ((IW + 2) * 144 + 255) / 256 * 256 : (IW + 2) * 144;
-template <int IW, int BN, int WGM, int EPI>
-__global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
+// TPS = taps per step (R * S a multiple of it): the weights of TPS taps of a channel slice are staged together, so a
+// wave multiplies TPS * 64 contraction indices between two barriers instead of 64.
+template <int IW, int BN, int WGM, int EPI, int TPS = 1, int BMT = 256>
+__global__ __launch_bounds__(256, BMT == 256 ? 2 : 4) void conv_patch_kernel(FastConvParams p)
 {
-    constexpr int BMT = 256, LDQ = 72, PW = IW + 2, TR = BMT / IW, PR = (TR + 2) * PW;   // patch: (TR + 2) x (IW + 2) pixels
+    constexpr int LDQ = 72, PW = IW + 2, TR = BMT / IW, PR = (TR + 2) * PW;   // patch: (TR + 2) x (IW + 2) pixels
     constexpr int RPB = kPatchRowBytes<IW>;                   // bytes per patch row
-    constexpr int WGN = 4 / WGM;                              // wave grid WGM x WGN, wave tile (256 / WGM) x (BN / WGN)
-    constexpr int TM = 256 / WGM / 32, TN = BN / WGN / 32;
+    constexpr int WGN = 4 / WGM;                              // wave grid WGM x WGN, wave tile (BMT / WGM) x (BN / WGN)
+    constexpr int TM = BMT / WGM / 32, TN = BN / WGN / 32;
     static_assert(TM >= 1 && TN >= 1, "");
     constexpr int NQB = BN * 8 / 256;
     constexpr int NQP = (PR * 8 + 255) / 256;                 // patch slots per thread
     constexpr unsigned P_BYTES = (TR + 2) * RPB;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     char* const sP = smem;                                    // [TR + 2][RPB]: rows of PW pixels x LDQ, activations with border
-    char* const sB = smem + P_BYTES;                          // [BN][LDQ] weights of one tap and channel slice
+    char* const sB = smem + P_BYTES;                          // [TPS][BN][LDQ] weights of TPS taps of one channel slice
+    constexpr unsigned B_TAP = BN * LDQ * 2;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -346,7 +349,7 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
     unsigned a_rd[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int pm = wm * (256 / WGM) + i * 32 + (lane & 31);
+        const int pm = wm * (BMT / WGM) + i * 32 + (lane & 31);
         a_rd[i] = (unsigned)((pm / IW) * RPB + ((pm % IW) * LDQ + (lane >> 5) * 8) * 2);
     }
     const unsigned b_rd = (unsigned)((wn * (BN / WGN) + (lane & 31)) * LDQ + (lane >> 5) * 8) * 2u;
@@ -361,16 +364,21 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
 
     const int taps = p.R * p.S;
     const int off0 = 1 - p.pad;                               // patch border is one pixel: tap (r, s) reads patch pixel + (r + off0, s + off0)
-    // One step = one tap of one 64-channel slice: 64 contraction indices, too little matrix work to cover the latency of
-    // its own weight load.  The weights of step i are therefore requested D steps ahead, into a ring of register sets.
-    constexpr int D = BN <= 64 ? 4 : 2;
-    const int steps = (p.C / 64) * taps;
-    u4 rb[D][NQB];
-    auto load_w = [&](int step, u4 (&dst)[NQB]) {
-        const int sl = step / taps, tap = step - sl * taps;
-        const unsigned kb = (unsigned)(tap * p.C + sl * 64) * 2u;
+    // One step = TPS taps of one 64-channel slice: TPS * 64 contraction indices, too little matrix work to cover the
+    // latency of its own weight load.  The weights of step i are therefore requested D steps ahead, into a ring of
+    // register sets.
+    constexpr int D = TPS > 1 ? 2 : (BN <= 64 ? 4 : 2);
+    const int spt = taps / TPS;                               // steps per channel slice
+    const int steps = (p.C / 64) * spt;
+    u4 rb[D][TPS][NQB];
+    auto load_w = [&](int step, u4 (&dst)[TPS][NQB]) {
+        const int sl = step / spt, tap0 = (step - sl * spt) * TPS;
 #pragma unroll
-        for (int q = 0; q < NQB; ++q) dst[q] = ldg16(wbase, boff[q] + kb);
+        for (int t = 0; t < TPS; ++t) {
+            const unsigned kb = (unsigned)((tap0 + t) * p.C + sl * 64) * 2u;
+#pragma unroll
+            for (int q = 0; q < NQB; ++q) dst[t][q] = ldg16(wbase, boff[q] + kb);
+        }
     };
 #pragma unroll
     for (int d = 0; d < D; ++d)
@@ -380,8 +388,8 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
         for (int d = 0; d < D; ++d) {
             const int step = step0 + d;
             if (step >= steps) break;
-            const int sl = step / taps, tap = step - sl * taps;
-            if (tap == 0) {
+            const int sl = step / spt, tap0 = (step - sl * spt) * TPS;
+            if (tap0 == 0) {
                 u4 rp[NQP];
 #pragma unroll
                 for (int q = 0; q < NQP; ++q) {
@@ -394,26 +402,32 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
                 for (int q = 0; q < NQP; ++q)
                     if (tid + q * 256 < PR * 8) *reinterpret_cast<u4*>(sP + pst[q]) = rp[q];
             } else {
-                __syncthreads();                              // every wave is done reading the previous tap's weights
+                __syncthreads();                              // every wave is done reading the previous step's weights
             }
 #pragma unroll
-            for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sB + sb_st[q]) = rb[d][q];
+            for (int t = 0; t < TPS; ++t)
+#pragma unroll
+                for (int q = 0; q < NQB; ++q) *reinterpret_cast<u4*>(sB + t * B_TAP + sb_st[q]) = rb[d][t][q];
             __syncthreads();
             if (step + D < steps) load_w(step + D, rb[d]);
-            const int r = tap / p.S, s2 = tap - r * p.S;
-            const unsigned toff = (unsigned)((r + off0) * RPB + (s2 + off0) * LDQ * 2);
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) {
-                bf16x8 a[TM], b[TN];
+            for (int t = 0; t < TPS; ++t) {
+                const int tap = tap0 + t;
+                const int r = tap / p.S, s2 = tap - r * p.S;
+                const unsigned toff = (unsigned)((r + off0) * RPB + (s2 + off0) * LDQ * 2);
 #pragma unroll
-                for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sP + a_rd[i] + toff + ks * 32);
+                for (int ks = 0; ks < 4; ++ks) {
+                    bf16x8 a[TM], b[TN];
 #pragma unroll
-                for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sB + b_rd + (j * 32 * LDQ + ks * 16) * 2);
+                    for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(sP + a_rd[i] + toff + ks * 32);
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                    for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(sB + t * B_TAP + b_rd + (j * 32 * LDQ + ks * 16) * 2);
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+                }
             }
         }
     }
@@ -433,7 +447,7 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
         for (int kk = 0; kk < 16; ++kk) { ss[j][kk] = 0.f; qq[j][kk] = 0.f; }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int mm = m0 + wm * (256 / WGM) + i * 32 + (lane & 31);
+        const int mm = m0 + wm * (BMT / WGM) + i * 32 + (lane & 31);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -481,7 +495,7 @@ __global__ __launch_bounds__(256, 2) void conv_patch_kernel(FastConvParams p)
         }
     }
     if (stats) {
-        static_assert(kStatLdsBytes<TN, WGM, WGN> <= (size_t)P_BYTES, "statistics area does not fit the patch");
+        // (the launcher asks for the larger of the K loop's LDS and kStatLdsBytes)
         __syncthreads();                                      // every wave is past its last operand read
         const int slot = (int)(item / (tiles_m * tiles_n));
         store_column_stats<TN, WGM, WGN>(ss, qq, reinterpret_cast<float*>(smem), wave, lane, p.stat + (long long)slot * p.stat_rep,
@@ -951,20 +965,28 @@ hipError_t launch_conv_fast(const FastConvParams& p0, int epi, int n_active, hip
     if ((p.W == 16 || p.W == 32) && p.C <= 128 && p.N <= 128 && p.R == p.S && p.R <= 3 && 2 * p.pad == p.R - 1 &&
         (p.H * p.W) % 256 == 0 && p.M % 256 == 0 && p.tile_hint != 2) {
         const int bn = (p.N % 128 == 0) ? 128 : 64;
-        const dim3 grid(die_grid((long long)(p.M / 256) * (p.N / bn) * n_active)), block(256);
-#define HADFL_PATCH(IW_, BN_, WGM_) do { \
-            constexpr size_t lds = (size_t)(256 / IW_ + 2) * kPatchRowBytes<IW_> + (size_t)BN_ * 72 * 2; \
-            static const bool ok = hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, WGM_, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess && \
-                                   hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, WGM_, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess; \
+        const dim3 block(256);
+#define HADFL_PATCH(IW_, BN_, WGM_, TPS_, BMT_) do { \
+            constexpr size_t loop_lds = (size_t)(BMT_ / IW_ + 2) * kPatchRowBytes<IW_> + (size_t)TPS_ * BN_ * 72 * 2; \
+            constexpr size_t stat_lds = kStatLdsBytes<BN_ / (4 / WGM_) / 32, WGM_, 4 / WGM_>; \
+            constexpr size_t lds = loop_lds > stat_lds ? loop_lds : stat_lds; \
+            static const bool ok = hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, WGM_, 0, TPS_, BMT_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess && \
+                                   hipFuncSetAttribute((const void*)conv_patch_kernel<IW_, BN_, WGM_, 1, TPS_, BMT_>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess; \
             if (!ok) return hipErrorInvalidValue; \
-            if (epi == 0) hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, WGM_, 0>), grid, block, lds, s, p); \
-            else hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, WGM_, 1>), grid, block, lds, s, p); } while (0)
-        // 128 output channels: waves 2 x 2 (128 x 64 each); 64: waves 4 x 1 (64 x 64 each)
-        srows = 256;
-        if (p.W == 32 && bn == 128) HADFL_PATCH(32, 128, 2);
-        else if (p.W == 32) HADFL_PATCH(32, 64, 4);
-        else if (bn == 128) HADFL_PATCH(16, 128, 2);
-        else HADFL_PATCH(16, 64, 4);
+            const dim3 grid(die_grid((long long)(p.M / BMT_) * (p.N / bn) * n_active)); \
+            srows = BMT_; \
+            if (epi == 0) hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, WGM_, 0, TPS_, BMT_>), grid, block, lds, s, p); \
+            else hipLaunchKernelGGL((conv_patch_kernel<IW_, BN_, WGM_, 1, TPS_, BMT_>), grid, block, lds, s, p); } while (0)
+        // 128 output channels: waves 2 x 2; 64: waves 4 x 1
+        // 32-pixel rows, 64 channels: 128-pixel tiles, four workgroups per compute unit (a tile's nine steps are too
+        // short to hide its own patch load and stores: 10 % faster than 256-pixel tiles with two).  16-pixel rows, 64
+        // channels: a whole filter row of weights per step where the filter has three (3-6 % faster); 128-pixel tiles
+        // measured no different there, nor with 128 channels.
+        if (p.W == 32 && bn == 128) HADFL_PATCH(32, 128, 2, 1, 256);
+        else if (p.W == 32) HADFL_PATCH(32, 64, 4, 1, 128);
+        else if (bn == 128) HADFL_PATCH(16, 128, 2, 1, 256);
+        else if (p.R == 3 && p.S == 3) HADFL_PATCH(16, 64, 4, 3, 256);
+        else HADFL_PATCH(16, 64, 4, 1, 256);
 #undef HADFL_PATCH
         return hipGetLastError();
     }
