@@ -615,8 +615,12 @@ __global__ __launch_bounds__(256) void bn_finalize_kernel(BnParams p)
         }
         if (direct && kl == 0) { s = s_sum[cl][0]; q = s_sum[cl][1]; }
     }
-    if (live && !direct)
+    if (live && !direct) {
+        // (up to a thousand entries per lane after a convolution with small tiles: keep many loads in flight; the
+        // additions stay in ascending order)
+#pragma unroll 16
         for (int k = kl; k < nk; k += 8) { s += part[(long long)k * 2 * p.C + c]; q += part[(long long)k * 2 * p.C + p.C + c]; }
+    }
     red[kl][cl][0] = s; red[kl][cl][1] = q;
     __syncthreads();
     for (int w = 4; w > 0; w >>= 1) {
