@@ -27,22 +27,22 @@ PAPER_CONTEXT = {"speedup_vs_decentralized_fedavg": 3.15, "speedup_vs_pytorch_di
 TRAFFIC = {
     ("aggregate", "agg-stress-n64"): (("paper_2111_08274_amd/csrc/aggregate.hip",),
                                       "ee3f9871add01e241b80b96d0fcdd3250747a0ef8da76f148d5575daca1ed43f",
-                                      402288378.1),
+                                      402288516.7),
     # all launches of the class in a cycle, averaged
     ("conv_dgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_stats.h"),
-                                       "d03050f1d06eee94815acfd1ae351bdf8e4f6cb8a2cb6f23da16edd8b923d1d5",
-                                       460902536.0),
+                                       "cc0afcd2862a6484e800f471bc016390d19f86eb04bffca742fcb93523bb020d",
+                                       469247850.6),
     ("conv_fwd", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                       "paper_2111_08274_amd/csrc/conv_first_bf16.hip",
                                       "paper_2111_08274_amd/csrc/conv_stats.h"),
-                                     "9c93fa2bd96b8f519b6420310fc1d01b8e116146a262addd8cdf1517865bb269",
-                                     324264002.9),
+                                     "6d0b5b6f326de0b4d04d62e23f359ecac5d4aeece24567464504b1531826c890",
+                                     324866754.0),
     # (the figure includes the fused update's parameter and momentum traffic)
     ("conv_wgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_first_bf16.hip"),
-                                       "6e452c202dc1cbb8154e84389d0ce3cc0acaa619cf32d6f4c61b81a411c79572",
-                                       552066643.7),
+                                       "3a34545bbf20a11296692c6e63155e1cb74b497520169af88177b48f30ff7ecd",
+                                       552096395.9),
 }
 
 
