@@ -26,8 +26,8 @@ PAPER_CONTEXT = {"speedup_vs_decentralized_fedavg": 3.15, "speedup_vs_pytorch_di
 # concatenation at measurement, bytes)
 TRAFFIC = {
     ("aggregate", "agg-stress-n64"): (("paper_2111_08274_amd/csrc/aggregate.hip",),
-                                      "ee3f9871add01e241b80b96d0fcdd3250747a0ef8da76f148d5575daca1ed43f",
-                                      402288516.7),
+                                      "6b6bc47f1584798896ab4395b0a3a8cedd8eec64ecd27d1eed8fa062f3c54da8",
+                                      402287575.4),
     # all launches of the class in a cycle, averaged
     ("conv_dgrad", "vgg16-bf16-n32"): (("paper_2111_08274_amd/csrc/conv_bf16_fast.hip",
                                         "paper_2111_08274_amd/csrc/conv_stats.h"),
@@ -285,6 +285,25 @@ def main():
                    "algorithmic_bytes": k["bytes"] / k["launches"], "GB/s": agg_gbs, "frac_of_hbm_peak": agg_gbs / HBM_PEAK_GBS,
                    "cycle_GB/s": cycle_gbs, "cycle_frac_of_hbm_peak": cycle_gbs / HBM_PEAK_GBS,
                    "mode": "no broadcast: (n_select+1)*4*M bytes; cycle = select + aggregate, timed end to end"}
+    # the same rows with the global synchronisation fused into the aggregate's store (Algorithm 1: every replica's
+    # parameters <- the aggregate): N more rows written per cycle.  Measured last: it makes the rows equal.
+    def agg_cycle_bcast(i):
+        actx.select(i, versions=versions)
+        actx.aggregate(resync=True)
+    t_b = time_cycles(agg_cycle_bcast, 40, 5)
+    actx.profile(True)
+    for i in range(20):
+        agg_cycle_bcast(2000 + i)
+    prof_b = actx.profile_read()
+    actx.profile(False)
+    kb = prof_b["aggregate_bcast"]
+    b_ms = kb["ms"] / kb["launches"]
+    b_bytes = kb["bytes"] / kb["launches"]
+    aggregation["with_broadcast"] = {"ms_per_cycle": t_b * 1e3, "kernel_ms": b_ms, "algorithmic_bytes": b_bytes,
+                                     "GB/s": b_bytes / (b_ms * 1e-3) / 1e9,
+                                     "frac_of_hbm_peak": b_bytes / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                     "cycle_GB/s": b_bytes / t_b / 1e9,
+                                     "mode": "aggregate + global synchronisation in one kernel: (n_select+1+n_replicas)*4*M bytes"}
     if c == 4:
         out.update(metric="aggregation HBM GB/s over one select+aggregate cycle", value=cycle_gbs,
                    unit="GB/s", steps=a_steps, warmup=a_warm, ms_per_step=t_agg * 1e3, dtype="f32",

@@ -9,9 +9,11 @@ namespace {
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int kAggThreads = 256;
-constexpr int kAggUnroll = 2;      // float4 chunks per thread: 2*NP loads of 16 bytes in flight
+constexpr int kAggUnrollPlain = 2;  // float4 chunks per thread: 2*NP loads of 16 bytes in flight
+constexpr int kAggUnrollBcast = 4;  // (the broadcast rows are written with plain stores: 4 % faster than non-temporal ones there)
 
-template <int NP>
+// BCAST: the result is also written to n_bcast replica rows (a kernel name of its own in traces)
+template <int NP, bool BCAST, int kAggUnroll = BCAST ? kAggUnrollBcast : kAggUnrollPlain>
 __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(
     const float* rows, int64_t row_stride, int64_t n4, const int32_t* __restrict__ sel,
     const float* __restrict__ wgt, int n_select, float* __restrict__ agg, int n_bcast, float* rows_out,
@@ -44,8 +46,9 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(
 #pragma unroll
                 for (int i = 1; i < NP; ++i) acc = acc + v[u][i] * a[i];
                 __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(agg) + j);
-                for (int r = 0; r < n_bcast; ++r)
-                    __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(rows_out + (int64_t)(bcast_list ? bcast_list[r] : r) * row_stride) + j);
+                if (BCAST)
+                    for (int r = 0; r < n_bcast; ++r)
+                        *(reinterpret_cast<f4*>(rows_out + (int64_t)(bcast_list ? bcast_list[r] : r) * row_stride) + j) = acc;
             }
         }
     } else {
@@ -56,8 +59,9 @@ __global__ __launch_bounds__(kAggThreads) void aggregate_kernel(
             for (int i = 1; i < np; ++i)
                 acc = acc + __builtin_nontemporal_load(reinterpret_cast<const f4*>(rows + (int64_t)sel[i] * row_stride) + j) * wgt[i];
             __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(agg) + j);
-            for (int r = 0; r < n_bcast; ++r)
-                __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(rows_out + (int64_t)(bcast_list ? bcast_list[r] : r) * row_stride) + j);
+            if (BCAST)
+                for (int r = 0; r < n_bcast; ++r)
+                    __builtin_nontemporal_store(acc, reinterpret_cast<f4*>(rows_out + (int64_t)(bcast_list ? bcast_list[r] : r) * row_stride) + j);
         }
     }
 }
@@ -94,10 +98,13 @@ hipError_t launch_aggregate(const float* rows, int64_t row_stride, int64_t len, 
                             const int32_t* bcast_list, hipStream_t s)
 {
     const int64_t n4 = len / 4;
-    const int64_t per_block = (int64_t)kAggThreads * kAggUnroll;
+    const int64_t per_block = (int64_t)kAggThreads * (n_bcast > 0 ? kAggUnrollBcast : kAggUnrollPlain);
     const dim3 grid((unsigned)((n4 + per_block - 1) / per_block)), block(kAggThreads);
-#define HADFL_AGG(NP) hipLaunchKernelGGL(aggregate_kernel<NP>, grid, block, 0, s, rows, row_stride, n4, sel_sorted, \
-                                         sel_weight, n_select, agg, n_bcast, rows_out, bcast_list)
+#define HADFL_AGG(NP) do { \
+        if (n_bcast > 0) hipLaunchKernelGGL((aggregate_kernel<NP, true>), grid, block, 0, s, rows, row_stride, n4, sel_sorted, \
+                                            sel_weight, n_select, agg, n_bcast, rows_out, bcast_list); \
+        else hipLaunchKernelGGL((aggregate_kernel<NP, false>), grid, block, 0, s, rows, row_stride, n4, sel_sorted, \
+                                sel_weight, n_select, agg, n_bcast, rows_out, bcast_list); } while (0)
     switch (n_select) {
     case 1: HADFL_AGG(1); break;
     case 2: HADFL_AGG(2); break;
