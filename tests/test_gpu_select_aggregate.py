@@ -61,6 +61,26 @@ def test_selection_weight_mode_1_and_errors():
     ctx.close()
 
 
+@pytest.mark.parametrize("N,n_select", [(64, 9), (150, 20)])
+def test_selection_weight_mode_1_weights_match_the_oracle(N, n_select):
+    """f-weighted aggregation weights (the extension, not in the paper) with one chunk of 64 replicas and with
+    several: the denominator adds the selected replicas' f in ascending index, in fp64, on both sides."""
+    import torch
+    rng = np.random.default_rng(N + n_select)
+    ctx, _ = _ctx(N, n_select, 64, weight_mode=1, seed=91)
+    for cycle in range(6):
+        v = rng.integers(0, 30, size=N).astype(np.int32)
+        avail = np.ones(N, dtype=np.uint8)
+        avail[rng.choice(N, size=N // 5, replace=False)] = 0
+        ctx.select(cycle, versions=torch.as_tensor(v).cuda(), avail=avail)
+        sel, flag, w = ctx.selected()
+        osel, oflag, of, _ = oracle.select(v, n_select, 91, cycle, avail)
+        assert sel.tolist() == osel.tolist() and flag.tolist() == oflag.tolist()
+        ow = oracle.aggregation_weights(oflag, of, 1)
+        assert np.array_equal(w, ow.astype(np.float32)), (N, cycle)
+    ctx.close()
+
+
 @pytest.mark.parametrize("N,n_select,m", [(6, 3, 100037), (4, 1, 5), (9, 8, 70001), (12, 11, 4099), (3, 3, 1 << 20)])
 def test_aggregate_matches_fp64_sum_and_resync_copies_it(N, n_select, m):
     import torch
